@@ -1,0 +1,241 @@
+#!/usr/bin/env python3
+"""Benchmark of the prefill-only adapter-apply hot path on one MI355X.
+
+A "step" is one pass of the whole path over one synthetic batch of the Llama-3.1-8B LoRA
+configuration (32 prompts of U[256,2048] rows + 224 decode rows, 64 adapters, bf16):
+
+    1 x token-segment scheduler                              (preft_schedule)
+    7 x segmented multi-adapter LoRA, rank R, prefill-only   (q, k, v, o, gate, up, down)
+    1 x segmented multi-adapter DiReFT, rank R, prefill-only (residual stream d = 4096)
+
+i.e. the adapter work of one decoder layer on that batch.  Every projection has its own
+activation buffers (about 6 GB per step in total), so every launch streams cold data from HBM;
+adapter weights are warm (steady-state serving).  `value` = active (prefill) rows per second
+through the step.
+
+The same JSON line also carries: the HBM roofline of the dominant kernel (the LoRA tile kernel,
+timed per launch with HIP events on the launch stream inside the timed region), the all-token
+(conventional PEFT) time for the same batch, the batch's decode rows alone as a decode-only
+step in both modes, and the CPU oracle timed on a sample of the same batch.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E, published
+
+
+def lora_bytes(T_act, d_in, d_out, r, n_adapters, e=2):
+    """Algorithmic bytes of one LoRA apply: x once in, y once in and once out, each distinct
+    active adapter's two factors once."""
+    return e * T_act * (d_in + 2 * d_out) + e * r * (d_in + d_out) * n_adapters
+
+
+def direft_bytes(T_act, d, r, n_adapters, e=2):
+    """Algorithmic bytes of one DiReFT apply: h once in, once out; factors and bias once."""
+    return e * T_act * 2 * d + e * (2 * r * d + r) * n_adapters
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--rank", type=int, default=16, help="adapter rank (the configuration lists 1, 8, 16)")
+    ap.add_argument("--config", default="llama8b_lora")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the all-token / decode-only legs")
+    ap.add_argument("--variant", type=int, default=0)
+    ap.add_argument("--waves", type=int, default=0)
+    ap.add_argument("--rowblocks", type=int, default=0)
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (the path has no cross-GPU step); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2605_14217_amd as preft
+    from paper_2605_14217_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    preft.load_library()
+    preft.preft_set_knob(preft.PREFT_KNOB_VARIANT, args.variant)
+    preft.preft_set_knob(preft.PREFT_KNOB_WAVES, args.waves)
+    preft.preft_set_knob(preft.PREFT_KNOB_ROWBLOCKS, args.rowblocks)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    cfg = wl.CONFIGS[args.config]
+    N, r, d_res = cfg["N"], args.rank, cfg["direft_d"]
+    scale = cfg["lora_scale"]
+    tab = wl.make_segments(args.config, seed=args.seed)
+    T, S = tab.T, tab.S
+    T_act = tab.active_rows(False, N)
+    n_ad = tab.distinct_active_adapters(False, N)
+    ss, sa, sp = (torch.from_numpy(a.copy()).to(dev) for a in (tab.seg_start, tab.seg_adapter, tab.seg_prefill_len))
+    ws = preft.new_workspace(T, S, device=dev)
+
+    # ---- buffers and pools --------------------------------------------------------------
+    projs = []
+    for i, (name, (d_in, d_out)) in enumerate(cfg["lora_shapes"].items()):
+        pool = wl.lora_pool(N, r, d_in, d_out, "bf16", device=dev, seed=args.seed + 10 + i)
+        A = [pool.A[j] for j in range(N)]
+        B = [pool.B[j] for j in range(N)]
+        projs.append(dict(name=name, d_in=d_in, d_out=d_out, pool=pool,
+                          Ap=preft.pointer_table(A), Bp=preft.pointer_table(B),
+                          x=wl.activations(T, d_in, "bf16", device=dev, seed=args.seed + 100 + i),
+                          y=wl.activations(T, d_out, "bf16", device=dev, seed=args.seed + 200 + i)))
+    dpool = wl.direft_pool(N, r, d_res, "bf16", device=dev, seed=args.seed + 50)
+    W1 = [dpool.A[j] for j in range(N)]
+    W2t = [dpool.B[j].t().contiguous() for j in range(N)]
+    bb = [dpool.b[j] for j in range(N)]
+    W1p, W2tp, bp = preft.pointer_table(W1), preft.pointer_table(W2t), preft.pointer_table(bb)
+    h = wl.activations(T, d_res, "bf16", device=dev, seed=args.seed + 300)
+    direft_scale = 1.0
+
+    def step(mode, tables=(ss, sa, sp), T_=T, events=None):
+        s0, s1, s2 = tables
+        preft.preft_schedule(ws, s0, s1, s2, T_, N, mode)
+        ready = mode | preft.PREFT_SCHEDULE_READY
+        for i, p in enumerate(projs):
+            if events is not None:
+                events[i][0].record()
+            preft.preft_lora_apply(p["y"][:T_], p["x"][:T_], s0, s1, s2, p["Ap"], p["Bp"], r, scale, ready, ws)
+            if events is not None:
+                events[i][1].record()
+        if events is not None:
+            events[len(projs)][0].record()
+        preft.preft_direft_apply(h[:T_], s0, s1, s2, W1p, W2tp, bp, r, direft_scale, ready, ws)
+        if events is not None:
+            events[len(projs)][1].record()
+
+    def timed(fn, iters, warm):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / iters * 1e3
+
+    # ---- timed region: K prefill-only steps ------------------------------------------------
+    K, W = args.steps, args.warmup
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(len(projs) + 1)] for _ in range(K)]
+    for _ in range(W):
+        step(preft.PREFT_PREFILL_ONLY)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(K):
+        step(preft.PREFT_PREFILL_ONLY, events=ev[k])
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) / K * 1e3
+    counts = preft.preft_schedule_counts(ws)
+
+    per_launch_ms = np.array([[a.elapsed_time(b) for (a, b) in evk] for evk in ev])     # [K, 8]
+    mean_ms = per_launch_ms.mean(axis=0)
+    breakdown = {}
+    lora_b, lora_t = 0.0, 0.0
+    for i, p in enumerate(projs):
+        b = lora_bytes(T_act, p["d_in"], p["d_out"], r, n_ad)
+        breakdown[p["name"]] = dict(us=round(mean_ms[i] * 1e3, 2), GBps=round(b / mean_ms[i] / 1e6, 1),
+                                    frac=round(b / mean_ms[i] / 1e6 / PEAK_HBM_GBPS, 4))
+        lora_b += b
+        lora_t += mean_ms[i]
+    db = direft_bytes(T_act, d_res, r, n_ad)
+    breakdown["direft"] = dict(us=round(mean_ms[-1] * 1e3, 2), GBps=round(db / mean_ms[-1] / 1e6, 1),
+                               frac=round(db / mean_ms[-1] / 1e6 / PEAK_HBM_GBPS, 4))
+    achieved = lora_b / lora_t / 1e6                                                     # GB/s
+    roofline = dict(bound="hbm", kernel="lora tile kernel (7 launches per step: q,k,v,o,gate,up,down)",
+                    achieved=round(achieved, 1), peak=PEAK_HBM_GBPS, unit="GB/s",
+                    frac=round(achieved / PEAK_HBM_GBPS, 4), traffic=None,
+                    bytes_per_launch=int(lora_b / len(projs)), us_per_launch=round(lora_t / len(projs) * 1e3, 2))
+
+    out = {
+        "metric": "prefill tokens/s through multi-adapter LoRA/DiReFT apply; % of peak HBM GB/s",
+        "value": round(T_act / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{args.config}: one decoder layer's adapter work = scheduler + 7 LoRA projections "
+                               f"(q,k,v,o,gate,up,down) + DiReFT d={d_res}, rank {r}, prefill-only",
+                   "T": T, "S": S, "active_rows": T_act, "decode_rows": int(T - T_act), "adapters": N,
+                   "distinct_active_adapters": n_ad, "rank": r, "seed": args.seed,
+                   "schedule": {"chunks": counts[0], "short_rows": counts[1]}},
+        "roofline": roofline,
+        "pct_peak_hbm": round(100 * achieved / PEAK_HBM_GBPS, 2),
+        "breakdown": breakdown,
+    }
+
+    # ---- practical ceiling: a plain device copy ------------------------------------------------
+    src, dst = projs[-1]["x"], torch.empty_like(projs[-1]["x"])
+    ms = timed(lambda: dst.copy_(src), 20, 3)
+    out["copy_GBps"] = round(2 * src.numel() * 2 / ms / 1e6, 1)
+    del dst
+
+    # ---- conventional baseline and the decode-only step ----------------------------------------
+    if not args.no_extras:
+        ms_all = timed(lambda: step(preft.PREFT_ALL_TOKENS), max(5, K // 4), 3)
+        dec = tab.decode_only()
+        dt = tuple(torch.from_numpy(a.copy()).to(dev) for a in (dec.seg_start, dec.seg_adapter, dec.seg_prefill_len))
+        ms_dec_all = timed(lambda: step(preft.PREFT_ALL_TOKENS, dt, dec.T), 50, 5)
+        ms_dec_pre = timed(lambda: step(preft.PREFT_PREFILL_ONLY, dt, dec.T), 50, 5)
+        out["all_token"] = {"ms_per_step": round(ms_all, 4), "speedup_prefill_only": round(ms_all / ms_per_step, 4)}
+        out["decode_only_step"] = {"rows": dec.T, "all_token_ms": round(ms_dec_all, 4),
+                                   "prefill_only_ms": round(ms_dec_pre, 4),
+                                   "speedup_prefill_only": round(ms_dec_all / ms_dec_pre, 2)}
+
+    # ---- CPU oracle on a sample of the same batch ---------------------------------------------
+    if not args.no_cpu_baseline:
+        from oracle import preft_oracle as ora
+        budget_rows = 6144
+        keep, rows_kept = [], 0
+        for s in np.argsort(-tab.seg_prefill_len, kind="stable"):
+            if tab.seg_prefill_len[s] == 0 or rows_kept >= budget_rows:
+                break
+            keep.append(int(s))
+            rows_kept += int(tab.seg_len[s])
+        keep = sorted(keep)
+        sub = wl.from_lengths(tab.seg_len[keep], tab.seg_adapter[keep], tab.seg_prefill_len[keep])
+        idx = torch.from_numpy(np.concatenate([np.arange(tab.seg_start[s], tab.seg_start[s + 1]) for s in keep])).to(dev)
+        used = set(int(a) for a in sub.seg_adapter)
+        cpu_in = []
+        for p in projs:
+            cpu_in.append((p["x"][idx].cpu(), p["y"][idx].cpu(),
+                           [p["pool"].A[j].cpu() if j in used else None for j in range(N)],
+                           [p["pool"].B[j].cpu() if j in used else None for j in range(N)]))
+        h_cpu = h[idx].cpu()
+        dA = [dpool.A[j].cpu() if j in used else None for j in range(N)]
+        dB = [dpool.B[j].cpu() if j in used else None for j in range(N)]
+        db_ = [dpool.b[j].cpu() if j in used else None for j in range(N)]
+        t0 = time.perf_counter()
+        for (x_c, y_c, A_c, B_c) in cpu_in:
+            ora.lora(y_c, x_c, sub.seg_start, sub.seg_adapter, sub.seg_prefill_len, A_c, B_c, r, scale, ora.PROMPT_ONLY)
+        ora.direft(h_cpu, sub.seg_start, sub.seg_adapter, sub.seg_prefill_len, dA, dB, db_, r, direft_scale,
+                   ora.PROMPT_ONLY)
+        dt_cpu = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(sub.T / dt_cpu, 1), "unit": "tokens/s", "cores": ora.threads(),
+                               "kind": "oracle",
+                               "sample": f"the {len(keep)} longest prompts of the batch ({sub.T} of {T_act} active rows), "
+                                         f"full step (7 LoRA projections + DiReFT), fp64 loops, {dt_cpu:.1f} s"}
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,181 @@
+/*
+ * preft.h -- C ABI of the MI355X (gfx950) prefill-only adapter-apply library.
+ *
+ * The library applies per-request adapters to a flattened, mixed prefill+decode token
+ * batch, in place, on one GPU:
+ *
+ *   LoRA    (paper Eq. 2):             y_t <- y_t + s * B_i (A_i x_t)
+ *   DiReFT  (paper Eq. 3, App. C.2):   h_t <- h_t + s * W2_i^T (W1_i h_t + b_i)
+ *
+ * for every row t whose position lies in the adapter's position set (paper Eq. 1):
+ * the prompt positions of its sequence only (PREFT_PREFILL_ONLY, paper Eq. 4) or every
+ * position (PREFT_ALL_TOKENS, the all-position set of Sec. 3.2).  Every other row -- decode
+ * tokens in prefill-only mode, sequences without an adapter -- is neither read nor
+ * written: it stays bit-identical.
+ *
+ * Batch description (App. D.3: the flattened batch and its cumulative sequence offsets;
+ * App. D.5/D.6: one adapter and one position schedule per request):
+ *   seg_start[S+1]      int32, device.  Rows seg_start[s] .. seg_start[s+1]-1 belong to
+ *                       sequence s.  seg_start[0] = 0, seg_start[S] = T, non-decreasing.
+ *   seg_adapter[S]      int32, device.  Index into the adapter pools; a value < 0 or >= N
+ *                       means "no adapter" (rows untouched).
+ *   seg_prefill_len[S]  int32, device.  How many leading rows of the segment are prompt
+ *                       positions (clamped to [0, segment length]).  A decode token is a
+ *                       segment of length 1 with prefill length 0; a prompt chunk has
+ *                       prefill length == length.  Ignored in PREFT_ALL_TOKENS mode.
+ * The tables are read on the device only; their contents are not validated on the host
+ * (that would need a synchronisation).  Rows are clamped to [0,T) on the device, so a
+ * malformed table cannot cause an out-of-range access, but its result is unspecified.
+ *
+ * Adapter pools: device arrays of N device pointers, one matrix per adapter, all of one
+ * rank, row-major, in the activation dtype:
+ *   A_pool[i]   [rank, d_in]   the paper's A as printed in Eq. 2
+ *   B_pool[i]   [d_out, rank]  the paper's B as printed in Eq. 2
+ *   W1_pool[i]  [rank, d]      the paper's A of Eq. 3
+ *   W2t_pool[i] [d, rank]      the TRANSPOSE of the paper's B of Eq. 3 (rank contiguous)
+ *   b_pool[i]   [rank]         the paper's b of Eq. 3; b_pool == NULL means b = 0
+ * Every matrix must be 16-byte aligned.  Pool slots are caller-owned and may be overwritten
+ * in place between calls.  Only the slots named by active segments are dereferenced.
+ *
+ * Ownership / execution: every pointer is caller-owned device memory unless marked
+ * "host".  The library allocates nothing and keeps no state between calls (apart from the
+ * benchmarking knobs of preft_set_knob).  Calls only
+ * enqueue work on `stream` (a hipStream_t passed as void*, NULL = the default stream) and
+ * return; they never synchronise.  All launch shapes depend on host-visible sizes only,
+ * so a call may be captured into a HIP graph.
+ *
+ * Arithmetic: products and sums are accumulated in fp32 (PREFT_BF16 and PREFT_F32); the
+ * rank-r intermediate stays in fp32; each output element is rounded once, to nearest
+ * even, to the activation dtype.
+ *
+ * Errors: every entry point returns PREFT_OK (0) or a negative code and leaves the output
+ * untouched when it returns an error detected before launch.
+ */
+#ifndef PREFT_H
+#define PREFT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* mode: position set, optionally OR-ed with PREFT_SCHEDULE_READY */
+enum {
+    PREFT_PREFILL_ONLY   = 0,      /* paper Eq. 4: prompt positions only                 */
+    PREFT_ALL_TOKENS     = 1,      /* all positions: the conventional PEFT baseline      */
+    PREFT_SCHEDULE_READY = 0x100   /* workspace already holds this batch's schedule      */
+};
+
+/* dtype of activations AND adapter weights */
+enum { PREFT_F32 = 0, PREFT_BF16 = 1 };
+
+enum {
+    PREFT_OK           =  0,
+    PREFT_EINVAL       = -1,   /* null pointer, negative size, bad enum, ld < width      */
+    PREFT_EUNSUPPORTED = -2,   /* rank outside 1..PREFT_MAX_RANK                         */
+    PREFT_EALIGN       = -3,   /* base pointer or row stride not 16-byte aligned, or a   */
+                               /* width that is not a multiple of 16 bytes               */
+    PREFT_EWORKSPACE   = -4,   /* workspace missing, misaligned or too small             */
+    PREFT_EHIP         = -5    /* the HIP runtime refused a launch                       */
+};
+
+#define PREFT_MAX_RANK 128
+
+/*
+ * Bytes of device workspace that hold the schedule of a batch of T rows in S segments.
+ * The workspace must be 16-byte aligned.  Returns 0 if T or S is negative.
+ */
+size_t preft_workspace_bytes(int32_t T, int32_t S);
+
+/*
+ * Token-segment scheduler (paper Eq. 1 and Eq. 4; App. D.3 "position mask", which the
+ * paper derives once per forward pass from the sequence offsets and skips for all-decode
+ * batches).  Reads the three segment tables on the device and writes into `workspace` the
+ * list of work units that cover exactly the active rows -- inactive rows appear in no
+ * unit, and a batch without active rows yields an empty list, which makes every apply
+ * call that consumes it return after an empty launch.
+ *
+ * The schedule depends on (tables, S, T, N, position set) only -- not on dtype, rank or
+ * widths -- so one schedule serves every projection and layer of an engine step: pass the
+ * same workspace with mode | PREFT_SCHEDULE_READY to the apply calls that follow on the
+ * same stream.
+ *
+ * mode: PREFT_PREFILL_ONLY or PREFT_ALL_TOKENS.
+ */
+int preft_schedule(void *workspace, size_t workspace_bytes,
+                   const int32_t *seg_start, const int32_t *seg_adapter,
+                   const int32_t *seg_prefill_len, int32_t S, int32_t T, int32_t N,
+                   int mode, void *stream);
+
+/*
+ * Segmented multi-adapter LoRA (paper Eq. 2 under the position set of Eq. 1/4):
+ *   y[t, :] += scale * B_i (A_i x[t, :])     for active rows t of segments with adapter i.
+ *
+ * y  [T, d_out]  in/out, row stride ldy elements.   x  [T, d_in]  in, row stride ldx.
+ * x and y must not overlap.  d_in, d_out, ldx, ldy must be multiples of 16 bytes worth of
+ * elements (8 for bf16, 4 for fp32) and x, y 16-byte aligned, else PREFT_EALIGN.
+ * rank in 1..PREFT_MAX_RANK.  scale is the paper's alpha (or alpha/r), already evaluated.
+ * Unless mode carries PREFT_SCHEDULE_READY the call first runs the scheduler into
+ * `workspace` (>= preft_workspace_bytes(T, S) bytes).
+ * T == 0 or S == 0 returns PREFT_OK without launching.
+ */
+int preft_lora_apply(void *y, int64_t ldy, const void *x, int64_t ldx,
+                     int32_t T, int32_t d_in, int32_t d_out,
+                     const int32_t *seg_start, const int32_t *seg_adapter,
+                     const int32_t *seg_prefill_len, int32_t S,
+                     const void *const *A_pool, const void *const *B_pool, int32_t N,
+                     int32_t rank, float scale, int dtype, int mode,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Segmented multi-adapter DiReFT (paper Eq. 3 with the prefactor of App. C.2, under the
+ * position set of Eq. 1/4), in place on the residual stream:
+ *   h[t, :] += scale * W2_i^T (W1_i h[t, :] + b_i)     for active rows t.
+ * Every read of a row precedes every write of that row.  scale = 1 gives Eq. 3 as
+ * printed; scale = 1/sqrt(rank) gives the rank-stable form.  The prefactor multiplies the
+ * bias term too.
+ *
+ * h [T, d] in/out, row stride ldh elements; alignment rules as for preft_lora_apply.
+ * b_pool may be NULL (no bias); if not NULL every active slot must be a valid pointer.
+ */
+int preft_direft_apply(void *h, int64_t ldh, int32_t T, int32_t d,
+                       const int32_t *seg_start, const int32_t *seg_adapter,
+                       const int32_t *seg_prefill_len, int32_t S,
+                       const void *const *W1_pool, const void *const *W2t_pool,
+                       const void *const *b_pool, int32_t N,
+                       int32_t rank, float scale, int dtype, int mode,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Copies the schedule counters of a workspace to the host: counts[0] = multi-row work
+ * units, counts[1] = single rows handled by the per-row path, counts[2] = active rows.
+ * `counts` is a host pointer to 3 int32.  This call synchronises `stream`; it is meant
+ * for tests, statistics and debugging, never for the serving loop.
+ */
+int preft_schedule_counts(const void *workspace, int32_t *counts, void *stream);
+
+/*
+ * Tuning knobs for benchmarking and tests (process-wide, not thread-safe; the defaults
+ * are what a serving loop should use).  Returns the previous value or PREFT_EINVAL.
+ *   PREFT_KNOB_VARIANT   0 = automatic choice (default)
+ *                        1 = per-row kernel everywhere
+ *                        2 = vector-ALU tile kernel where it applies (bf16, rank <= 8)
+ *                        3 = MFMA tile kernel where it applies (bf16, rank % 4 == 0)
+ *   PREFT_KNOB_WAVES     wavefronts per tile workgroup: 0 = automatic, else 1, 2 or 4
+ *   PREFT_KNOB_ROWBLOCKS MFMA kernel: 16-row blocks per wavefront: 0 = automatic, 1 or 2
+ */
+enum { PREFT_KNOB_VARIANT = 0, PREFT_KNOB_WAVES = 1, PREFT_KNOB_ROWBLOCKS = 2 };
+int preft_set_knob(int knob, int value);
+
+/* Static, NUL-terminated description of a return code (host pointer, never freed). */
+const char *preft_strerror(int code);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int preft_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PREFT_H */

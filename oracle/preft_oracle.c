@@ -125,6 +125,9 @@ void ora_direft_row(double *out, const void *h,
  * otherwise out[q] holds row rows[q], q < n_rows.  Rows outside the position set are
  * the widened copy of y0 (Eq. 1, "otherwise" branch).
  * x:[T,m] (row stride ldx), y0:[T,n] (row stride ldy), A_pool[a]:[r,m], B_pool[a]:[n,r].
+ * With rows != NULL and gathered != 0 the caller has already gathered the selected rows:
+ * x and y0 then hold n_rows rows, row q being batch row rows[q] (for batches too large
+ * to copy whole); positions and adapters still come from the full segment table.
  */
 int ora_lora_batch(double *out, const int64_t *rows, int64_t n_rows,
                    const void *y0, int64_t ldy, const void *x, int64_t ldx,
@@ -132,7 +135,7 @@ int ora_lora_batch(double *out, const int64_t *rows, int64_t n_rows,
                    const int32_t *seg_start, const int32_t *seg_adapter,
                    const int32_t *seg_prompt_len, int32_t S,
                    const void *const *A_pool, const void *const *B_pool, int32_t N,
-                   int32_t r, double alpha, int position_set, int dt_act, int dt_w)
+                   int32_t r, double alpha, int position_set, int dt_act, int dt_w, int gathered)
 {
     int32_t *row_adapter = (int32_t *)malloc(sizeof(int32_t) * (size_t)(T > 0 ? T : 1));
     if (ora_positions(row_adapter, T, seg_start, seg_adapter, seg_prompt_len, S, N, position_set)) {
@@ -145,11 +148,12 @@ int ora_lora_batch(double *out, const int64_t *rows, int64_t n_rows,
         int64_t t = rows ? rows[q] : q;
         double *o = out + q * n;
         int32_t a = row_adapter[t];
-        const void *y0_t = row_ptr(y0, t, ldy, dt_act);
+        int64_t src = (rows && gathered) ? q : t;            /* where row t's data sits */
+        const void *y0_t = row_ptr(y0, src, ldy, dt_act);
         if (a < 0) {
             for (int64_t i = 0; i < n; ++i) o[i] = ld(y0_t, i, dt_act);
         } else {
-            ora_lora_row(o, y0_t, row_ptr(x, t, ldx, dt_act), A_pool[a], B_pool[a],
+            ora_lora_row(o, y0_t, row_ptr(x, src, ldx, dt_act), A_pool[a], B_pool[a],
                          m, n, r, alpha, dt_act, dt_w);
         }
     }
@@ -157,14 +161,14 @@ int ora_lora_batch(double *out, const int64_t *rows, int64_t n_rows,
     return 0;
 }
 
-/* DiReFT over a batch; same row-selection convention.  h:[T,d] (row stride ldh). */
+/* DiReFT over a batch; same row-selection and gathering convention.  h:[T,d] (row stride ldh). */
 int ora_direft_batch(double *out, const int64_t *rows, int64_t n_rows,
                      const void *h, int64_t ldh, int64_t T, int64_t d,
                      const int32_t *seg_start, const int32_t *seg_adapter,
                      const int32_t *seg_prompt_len, int32_t S,
                      const void *const *A_pool, const void *const *B_pool,
                      const void *const *b_pool, int32_t N,
-                     int32_t r, double s, int position_set, int dt_act, int dt_w)
+                     int32_t r, double s, int position_set, int dt_act, int dt_w, int gathered)
 {
     int32_t *row_adapter = (int32_t *)malloc(sizeof(int32_t) * (size_t)(T > 0 ? T : 1));
     if (ora_positions(row_adapter, T, seg_start, seg_adapter, seg_prompt_len, S, N, position_set)) {
@@ -177,7 +181,7 @@ int ora_direft_batch(double *out, const int64_t *rows, int64_t n_rows,
         int64_t t = rows ? rows[q] : q;
         double *o = out + q * d;
         int32_t a = row_adapter[t];
-        const void *h_t = row_ptr(h, t, ldh, dt_act);
+        const void *h_t = row_ptr(h, (rows && gathered) ? q : t, ldh, dt_act);
         if (a < 0) {
             for (int64_t j = 0; j < d; ++j) o[j] = ld(h_t, j, dt_act);
         } else {

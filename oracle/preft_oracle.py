@@ -57,14 +57,14 @@ def _load():
                                        i32p, i32p, i32p, ctypes.c_int32,
                                        vpp, vpp, ctypes.c_int32,
                                        ctypes.c_int32, ctypes.c_double, ctypes.c_int,
-                                       ctypes.c_int, ctypes.c_int]
+                                       ctypes.c_int, ctypes.c_int, ctypes.c_int]
         lib.ora_direft_batch.restype = ctypes.c_int
         lib.ora_direft_batch.argtypes = [dblp, i64p, ctypes.c_int64,
                                          ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                          i32p, i32p, i32p, ctypes.c_int32,
                                          vpp, vpp, vpp, ctypes.c_int32,
                                          ctypes.c_int32, ctypes.c_double, ctypes.c_int,
-                                         ctypes.c_int, ctypes.c_int]
+                                         ctypes.c_int, ctypes.c_int, ctypes.c_int]
         lib.ora_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -151,19 +151,25 @@ def positions(T, seg_start, seg_adapter, seg_prompt_len, N, position_set):
 
 
 def lora(y0, x, seg_start, seg_adapter, seg_prompt_len, A_pool, B_pool, r, alpha,
-         position_set, rows=None):
-    """Eq. 1/2/4 over a batch: fp64 array [T,n] (or [len(rows),n])."""
+         position_set, rows=None, gathered=False):
+    """Eq. 1/2/4 over a batch: fp64 array [T,n] (or [len(rows),n]).
+
+    gathered=True (needs rows): y0 and x hold only the selected rows, in the order of `rows`."""
     lib = _load()
     y0a, dt_y = _as_typed(y0)
     xa, dt_x = _as_typed(x)
     if dt_y != dt_x:
         raise ValueError("x and y0 must share a dtype")
-    T, n = y0a.shape
-    T2, m = xa.shape
-    assert T == T2
     ss, sa, sp = _i32(seg_start), _i32(seg_adapter), _i32(seg_prompt_len)
     S = len(sa)
     assert len(ss) == S + 1 and len(sp) == S
+    n, m = y0a.shape[1], xa.shape[1]
+    assert y0a.shape[0] == xa.shape[0]
+    if gathered:
+        assert rows is not None and len(rows) == y0a.shape[0]
+        T = int(ss[-1])
+    else:
+        T = y0a.shape[0]
     N = len(A_pool)
     assert len(B_pool) == N
     Ap, dt_w, keepA = _pool(A_pool, (r, m))
@@ -181,21 +187,28 @@ def lora(y0, x, seg_start, seg_adapter, seg_prompt_len, A_pool, B_pool, r, alpha
                             y0a.ctypes.data, n, xa.ctypes.data, m, T, m, n,
                             _ptr(ss, ctypes.c_int32), _ptr(sa, ctypes.c_int32),
                             _ptr(sp, ctypes.c_int32), S,
-                            Ap, Bp, N, r, float(alpha), position_set, dt_x, dt_w)
+                            Ap, Bp, N, r, float(alpha), position_set, dt_x, dt_w, int(bool(gathered)))
     if rc:
         raise ValueError("malformed segment table")
     return out
 
 
 def direft(h, seg_start, seg_adapter, seg_prompt_len, A_pool, B_pool, b_pool, r, s,
-           position_set, rows=None):
-    """Eq. 1/3/4 (with the prefactor s of App. C.2) over a batch: fp64 [T,d] or [len(rows),d]."""
+           position_set, rows=None, gathered=False):
+    """Eq. 1/3/4 (with the prefactor s of App. C.2) over a batch: fp64 [T,d] or [len(rows),d].
+
+    gathered=True (needs rows): h holds only the selected rows, in the order of `rows`."""
     lib = _load()
     ha, dt_h = _as_typed(h)
-    T, d = ha.shape
+    d = ha.shape[1]
     ss, sa, sp = _i32(seg_start), _i32(seg_adapter), _i32(seg_prompt_len)
     S = len(sa)
     assert len(ss) == S + 1 and len(sp) == S
+    if gathered:
+        assert rows is not None and len(rows) == ha.shape[0]
+        T = int(ss[-1])
+    else:
+        T = ha.shape[0]
     N = len(A_pool)
     assert len(B_pool) == N
     Ap, dt_w, keepA = _pool(A_pool, (r, d))
@@ -220,7 +233,7 @@ def direft(h, seg_start, seg_adapter, seg_prompt_len, A_pool, B_pool, b_pool, r,
                               ha.ctypes.data, d, T, d,
                               _ptr(ss, ctypes.c_int32), _ptr(sa, ctypes.c_int32),
                               _ptr(sp, ctypes.c_int32), S,
-                              Ap, Bp, bp, N, r, float(s), position_set, dt_h, dt_w)
+                              Ap, Bp, bp, N, r, float(s), position_set, dt_h, dt_w, int(bool(gathered)))
     if rc:
         raise ValueError("malformed segment table")
     return out

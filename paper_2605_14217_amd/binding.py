@@ -1,0 +1,195 @@
+"""ctypes binding of libpreft.so: argument marshalling only, same names as the C ABI.
+
+PyTorch supplies device memory and the current HIP stream; every step of the path runs in
+the library's kernels.  There is no fallback: if the library is missing, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpreft.so")
+
+PREFT_PREFILL_ONLY = 0
+PREFT_ALL_TOKENS = 1
+PREFT_SCHEDULE_READY = 0x100
+PREFT_F32 = 0
+PREFT_BF16 = 1
+PREFT_KNOB_VARIANT = 0
+PREFT_KNOB_WAVES = 1
+PREFT_KNOB_ROWBLOCKS = 2
+
+# every symbol include/preft.h declares
+ABI_SYMBOLS = ("preft_workspace_bytes", "preft_schedule", "preft_lora_apply", "preft_direft_apply",
+               "preft_schedule_counts", "preft_set_knob", "preft_strerror", "preft_version")
+
+_lib = None
+
+
+class PreftError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {preft_strerror(code)} (code {code})")
+
+
+def load_library(path: Optional[str] = None):
+    """Load libpreft.so (built in-tree by paper_2605_14217_amd.build) and declare its prototypes."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or LIB_PATH
+    if not os.path.exists(path):
+        raise FileNotFoundError(
+            f"{path} not found: build the HIP library first (python -m paper_2605_14217_amd.build); "
+            "there is no CPU or PyTorch fallback for this path")
+    lib = ctypes.CDLL(path)
+    c = ctypes
+    vp, i32, i64, sz = c.c_void_p, c.c_int32, c.c_int64, c.c_size_t
+    lib.preft_workspace_bytes.restype = sz
+    lib.preft_workspace_bytes.argtypes = [i32, i32]
+    lib.preft_schedule.restype = c.c_int
+    lib.preft_schedule.argtypes = [vp, sz, vp, vp, vp, i32, i32, i32, c.c_int, vp]
+    lib.preft_lora_apply.restype = c.c_int
+    lib.preft_lora_apply.argtypes = [vp, i64, vp, i64, i32, i32, i32, vp, vp, vp, i32, vp, vp, i32, i32,
+                                     c.c_float, c.c_int, c.c_int, vp, sz, vp]
+    lib.preft_direft_apply.restype = c.c_int
+    lib.preft_direft_apply.argtypes = [vp, i64, i32, i32, vp, vp, vp, i32, vp, vp, vp, i32, i32,
+                                       c.c_float, c.c_int, c.c_int, vp, sz, vp]
+    lib.preft_schedule_counts.restype = c.c_int
+    lib.preft_schedule_counts.argtypes = [vp, c.POINTER(i32), vp]
+    lib.preft_set_knob.restype = c.c_int
+    lib.preft_set_knob.argtypes = [c.c_int, c.c_int]
+    lib.preft_strerror.restype = c.c_char_p
+    lib.preft_strerror.argtypes = [c.c_int]
+    lib.preft_version.restype = c.c_int
+    lib.preft_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+# ----------------------------------------------------------------------------------------
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return PREFT_BF16
+    if t.dtype == torch.float32:
+        return PREFT_F32
+    raise TypeError(f"unsupported activation dtype {t.dtype}")
+
+
+def _matrix(t: torch.Tensor, name: str):
+    if t.dim() != 2 or t.stride(1) != 1 or not t.is_cuda:
+        raise ValueError(f"{name}: need a 2-D device tensor with unit column stride")
+    return t.data_ptr(), int(t.stride(0)), int(t.shape[0]), int(t.shape[1])
+
+
+def _table(t: torch.Tensor, name: str, n: int):
+    if t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous() or t.numel() != n:
+        raise ValueError(f"{name}: need a contiguous int32 device tensor of {n} entries")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise PreftError(rc, where)
+
+
+def pointer_table(mats: Sequence[torch.Tensor]) -> torch.Tensor:
+    """Device array of device pointers, one per adapter slot (the pool argument of the C ABI)."""
+    dev = mats[0].device
+    for m in mats:
+        if not m.is_cuda or not m.is_contiguous():
+            raise ValueError("pool slots must be contiguous device tensors")
+    return torch.tensor([m.data_ptr() for m in mats], dtype=torch.int64, device=dev)
+
+
+def preft_version() -> int:
+    return int(load_library().preft_version())
+
+
+def preft_strerror(code: int) -> str:
+    return load_library().preft_strerror(int(code)).decode()
+
+
+def preft_set_knob(knob: int, value: int) -> int:
+    rc = int(load_library().preft_set_knob(int(knob), int(value)))
+    if rc < 0:
+        raise PreftError(rc, "preft_set_knob")
+    return rc
+
+
+def preft_workspace_bytes(T: int, S: int) -> int:
+    return int(load_library().preft_workspace_bytes(int(T), int(S)))
+
+
+def new_workspace(T: int, S: int, device="cuda") -> torch.Tensor:
+    """Caller-owned workspace for a batch of T rows in S segments."""
+    return torch.empty(max(preft_workspace_bytes(T, S), 16), dtype=torch.uint8, device=device)
+
+
+def preft_schedule(workspace: torch.Tensor, seg_start, seg_adapter, seg_prefill_len, T: int, N: int,
+                   mode: int, stream=None) -> None:
+    S = int(seg_adapter.numel())
+    rc = load_library().preft_schedule(
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+        _table(seg_start, "seg_start", S + 1), _table(seg_adapter, "seg_adapter", S),
+        _table(seg_prefill_len, "seg_prefill_len", S), S, int(T), int(N), int(mode), _stream(stream))
+    _check(rc, "preft_schedule")
+
+
+def preft_schedule_counts(workspace: torch.Tensor, stream=None):
+    out = (ctypes.c_int32 * 3)()
+    _check(load_library().preft_schedule_counts(workspace.data_ptr(), out, _stream(stream)),
+           "preft_schedule_counts")
+    return int(out[0]), int(out[1]), int(out[2])
+
+
+def preft_lora_apply(y: torch.Tensor, x: torch.Tensor, seg_start, seg_adapter, seg_prefill_len,
+                     A_pool: torch.Tensor, B_pool: torch.Tensor, rank: int, scale: float, mode: int,
+                     workspace: torch.Tensor, stream=None) -> None:
+    """y[t] += scale * B_i (A_i x[t]) on active rows, in place.  A_pool/B_pool: pointer tables
+    (see pointer_table) of [rank, d_in] and [d_out, rank] matrices."""
+    yp, ldy, T, d_out = _matrix(y, "y")
+    xp, ldx, T2, d_in = _matrix(x, "x")
+    if T != T2 or x.dtype != y.dtype:
+        raise ValueError("x and y must agree in rows and dtype")
+    S = int(seg_adapter.numel())
+    N = int(A_pool.numel())
+    if B_pool.numel() != N or A_pool.dtype != torch.int64 or B_pool.dtype != torch.int64:
+        raise ValueError("A_pool and B_pool must be int64 pointer tables of equal length")
+    rc = load_library().preft_lora_apply(
+        yp, ldy, xp, ldx, T, d_in, d_out,
+        _table(seg_start, "seg_start", S + 1), _table(seg_adapter, "seg_adapter", S),
+        _table(seg_prefill_len, "seg_prefill_len", S), S,
+        A_pool.data_ptr(), B_pool.data_ptr(), N, int(rank), float(scale), _dtype_code(y), int(mode),
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc, "preft_lora_apply")
+
+
+def preft_direft_apply(h: torch.Tensor, seg_start, seg_adapter, seg_prefill_len,
+                       W1_pool: torch.Tensor, W2t_pool: torch.Tensor, b_pool: Optional[torch.Tensor],
+                       rank: int, scale: float, mode: int, workspace: torch.Tensor, stream=None) -> None:
+    """h[t] += scale * W2_i^T (W1_i h[t] + b_i) on active rows, in place.  W1_pool: [rank, d]
+    matrices; W2t_pool: [d, rank] matrices (W2 transposed); b_pool: [rank] vectors or None."""
+    hp, ldh, T, d = _matrix(h, "h")
+    S = int(seg_adapter.numel())
+    N = int(W1_pool.numel())
+    if W2t_pool.numel() != N or (b_pool is not None and b_pool.numel() != N):
+        raise ValueError("pools must be pointer tables of equal length")
+    rc = load_library().preft_direft_apply(
+        hp, ldh, T, d,
+        _table(seg_start, "seg_start", S + 1), _table(seg_adapter, "seg_adapter", S),
+        _table(seg_prefill_len, "seg_prefill_len", S), S,
+        W1_pool.data_ptr(), W2t_pool.data_ptr(), None if b_pool is None else b_pool.data_ptr(), N,
+        int(rank), float(scale), _dtype_code(h), int(mode),
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc, "preft_direft_apply")

@@ -1,0 +1,142 @@
+// Shared device-side definitions of the gfx950 adapter-apply kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace preft {
+
+// ---------------------------------------------------------------------------------------
+// Schedule (written by schedule_kernel, read by every apply kernel)
+//
+//   header   int32[16]   [0] number of chunks  [1] number of short rows  [2] active rows
+//   chunks   int4[]      {adapter, first row, rows (1..CHUNK_ROWS), segment}
+//   shorts   int2[]      {adapter, row}
+//
+// A chunk is a run of at most CHUNK_ROWS consecutive active rows of one segment; a tile
+// kernel of height R (a divisor of CHUNK_ROWS) splits it into CHUNK_ROWS / R tiles.
+// Segments with at most SHORT_ROWS active rows (decode tokens, speculative tokens, the
+// last token of a chunked prompt) are listed row by row for the per-row kernel.
+// ---------------------------------------------------------------------------------------
+constexpr int CHUNK_ROWS  = 128;
+constexpr int SHORT_ROWS  = 4;
+constexpr int HEADER_INTS = 16;
+constexpr int PREFT_MAX_RANK_DEV = 128;   // must equal PREFT_MAX_RANK of the public header
+
+struct ScheduleView {
+    int32_t *header;
+    int4    *chunks;
+    int2    *shorts;
+    int32_t  chunk_cap;
+    int32_t  short_cap;
+};
+
+// Upper bounds from host-visible sizes only (a long segment has > SHORT_ROWS rows).
+__host__ __device__ inline int64_t chunk_capacity(int64_t T, int64_t S)
+{
+    int64_t long_segs = T / (SHORT_ROWS + 1);
+    if (long_segs > S) long_segs = S;
+    return T / CHUNK_ROWS + long_segs + 1;
+}
+__host__ __device__ inline int64_t short_capacity(int64_t T, int64_t S)
+{
+    int64_t c = (int64_t)SHORT_ROWS * S;
+    return (c < T ? c : T) + 1;
+}
+
+// ---------------------------------------------------------------------------------------
+// bf16 <-> fp32
+// ---------------------------------------------------------------------------------------
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float  f32x2_t  __attribute__((ext_vector_type(2)));
+typedef float  f32x4_t  __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+
+// two fp32 -> packed bf16x2, round to nearest even (v_cvt_pk_bf16_f32 on gfx950)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    f32x2_t v = {lo, hi};
+    bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
+    return __builtin_bit_cast(uint32_t, b);
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// 16-byte global accesses
+__device__ __forceinline__ u32x4_t ld16(const void *p) { return *reinterpret_cast<const u32x4_t *>(p); }
+__device__ __forceinline__ void st16(void *p, u32x4_t v) { *reinterpret_cast<u32x4_t *>(p) = v; }
+
+// Element traits: V = elements per 16-byte vector
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr int V = 4;
+    static constexpr int BYTES = 4;
+    __device__ static __forceinline__ void unpack(u32x4_t raw, float (&f)[4])
+    {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) f[i] = __uint_as_float(raw[i]);
+    }
+    __device__ static __forceinline__ u32x4_t pack(const float (&f)[4])
+    {
+        u32x4_t r;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = __float_as_uint(f[i]);
+        return r;
+    }
+    __device__ static __forceinline__ float load1(const void *p, int64_t i) { return reinterpret_cast<const float *>(p)[i]; }
+    __device__ static __forceinline__ void store1(void *p, int64_t i, float v) { reinterpret_cast<float *>(p)[i] = v; }
+};
+struct bf16_tag {};
+template <> struct Elem<bf16_tag> {
+    static constexpr int V = 8;
+    static constexpr int BYTES = 2;
+    __device__ static __forceinline__ void unpack(u32x4_t raw, float (&f)[8])
+    {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { f[2 * i] = bf16_lo(raw[i]); f[2 * i + 1] = bf16_hi(raw[i]); }
+    }
+    __device__ static __forceinline__ u32x4_t pack(const float (&f)[8])
+    {
+        u32x4_t r;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = pack_bf16(f[2 * i], f[2 * i + 1]);
+        return r;
+    }
+    __device__ static __forceinline__ float load1(const void *p, int64_t i)
+    {
+        return __uint_as_float((uint32_t) reinterpret_cast<const uint16_t *>(p)[i] << 16);
+    }
+    __device__ static __forceinline__ void store1(void *p, int64_t i, float v)
+    {
+        reinterpret_cast<uint16_t *>(p)[i] = (uint16_t)(pack_bf16(v, 0.0f) & 0xffffu);
+    }
+};
+
+// Arguments common to every apply kernel.  For DiReFT x == y == h, d_in == d_out == d,
+// A = W1, Bt = W2^T and bias may be non-null.
+struct ApplyArgs {
+    void               *y;
+    const void         *x;
+    int64_t             ldy, ldx;        // row strides in elements
+    int32_t             T, d_in, d_out;
+    const void *const  *A_pool;          // [rank, d_in] each
+    const void *const  *Bt_pool;         // [d_out, rank] each
+    const void *const  *bias_pool;       // [rank] each, or null
+    int32_t             N, rank;
+    float               scale;
+    const int32_t      *header;
+    const int4         *chunks;
+    const int2         *shorts;
+};
+
+}  // namespace preft

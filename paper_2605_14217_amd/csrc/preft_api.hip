@@ -1,0 +1,316 @@
+// C ABI of the adapter-apply library: argument validation, variant choice, launches.
+// See include/preft.h for the contract of every entry point.
+#include "../../include/preft.h"
+
+#include "common.hpp"
+#include "mfma_kernel.hpp"
+#include "row_kernel.hpp"
+#include "schedule.hpp"
+#include "valu_kernel.hpp"
+
+static_assert(preft::PREFT_MAX_RANK_DEV == PREFT_MAX_RANK, "device and public rank limits differ");
+
+namespace {
+
+using namespace preft;
+
+int g_variant = 0;      // PREFT_KNOB_VARIANT
+int g_waves = 0;        // PREFT_KNOB_WAVES
+int g_rowblocks = 0;    // PREFT_KNOB_ROWBLOCKS
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+size_t workspace_bytes(int64_t T, int64_t S)
+{
+    return (size_t)HEADER_INTS * 4 + (size_t)chunk_capacity(T, S) * sizeof(int4) +
+           (size_t)short_capacity(T, S) * sizeof(int2);
+}
+
+ScheduleView view_of(void *workspace, int64_t T, int64_t S)
+{
+    ScheduleView v;
+    char *base = reinterpret_cast<char *>(workspace);
+    v.header = reinterpret_cast<int32_t *>(base);
+    v.chunks = reinterpret_cast<int4 *>(base + HEADER_INTS * 4);
+    v.chunk_cap = (int32_t)chunk_capacity(T, S);
+    v.shorts = reinterpret_cast<int2 *>(base + HEADER_INTS * 4 + (size_t)v.chunk_cap * sizeof(int4));
+    v.short_cap = (int32_t)short_capacity(T, S);
+    return v;
+}
+
+int check_launch()
+{
+    return hipGetLastError() == hipSuccess ? PREFT_OK : PREFT_EHIP;
+}
+
+int check_tables(const void *workspace, size_t bytes, const int32_t *seg_start, const int32_t *seg_adapter,
+                 const int32_t *seg_prefill_len, int32_t S, int32_t T, int32_t N, int mode)
+{
+    if (T < 0 || S < 0 || N < 0) return PREFT_EINVAL;
+    if ((mode & ~(PREFT_ALL_TOKENS | PREFT_SCHEDULE_READY)) != 0) return PREFT_EINVAL;
+    if (T == 0 || S == 0) return PREFT_OK;
+    if (!seg_start || !seg_adapter || !seg_prefill_len) return PREFT_EINVAL;
+    if (!workspace || !aligned16(workspace) || bytes < workspace_bytes(T, S)) return PREFT_EWORKSPACE;
+    return PREFT_OK;
+}
+
+int launch_schedule(void *workspace, const int32_t *seg_start, const int32_t *seg_adapter,
+                    const int32_t *seg_prefill_len, int32_t S, int32_t T, int32_t N, int mode,
+                    hipStream_t stream)
+{
+    ScheduleView v = view_of(workspace, T, S);
+    hipLaunchKernelGGL(schedule_kernel, dim3(1), dim3(SCHED_THREADS), 0, stream, seg_start, seg_adapter,
+                       seg_prefill_len, S, T, N, (mode & PREFT_ALL_TOKENS) ? 1 : 0, v);
+    return check_launch();
+}
+
+// ------------------------------------------------------------------------------------
+// tile-kernel dispatch
+// ------------------------------------------------------------------------------------
+inline unsigned tile_grid(int64_t T, int64_t S, int tiles_per_chunk)
+{
+    const int64_t units = chunk_capacity(T, S) * tiles_per_chunk;
+    return (unsigned)(((units + 7) / 8) * 8);
+}
+
+template <int NB, int MB, int WAVES, bool DIREFT>
+void launch_mfma(const ApplyArgs &a, int64_t S, hipStream_t stream)
+{
+    constexpr int R = 16 * MB * WAVES;
+    hipLaunchKernelGGL((mfma_tile_kernel<NB, MB, WAVES, DIREFT>), dim3(tile_grid(a.T, S, CHUNK_ROWS / R)),
+                       dim3(WAVES * 64), 0, stream, a);
+}
+
+template <int NB, bool DIREFT>
+void launch_mfma_shape(const ApplyArgs &a, int64_t S, int mb, int waves, hipStream_t stream)
+{
+    if (mb == 2) {
+        if (waves == 4)      launch_mfma<NB, 2, 4, DIREFT>(a, S, stream);
+        else if (waves == 2) launch_mfma<NB, 2, 2, DIREFT>(a, S, stream);
+        else                 launch_mfma<NB, 2, 1, DIREFT>(a, S, stream);
+    } else {
+        if (waves == 4)      launch_mfma<NB, 1, 4, DIREFT>(a, S, stream);
+        else if (waves == 2) launch_mfma<NB, 1, 2, DIREFT>(a, S, stream);
+        else                 launch_mfma<NB, 1, 1, DIREFT>(a, S, stream);
+    }
+}
+
+template <bool DIREFT>
+void launch_mfma_rank(const ApplyArgs &a, int64_t S, hipStream_t stream)
+{
+    const int nb = (a.rank + 15) / 16;
+    int mb = g_rowblocks ? g_rowblocks : (nb >= 2 ? 2 : 1);
+    int waves = g_waves;
+    if (!waves) {
+        // enough tiles to spread evenly over 256 compute units, else shorter tiles
+        waves = 4;
+        while (waves > 1 && (int64_t)a.T / (16 * mb * waves) < 2048) waves >>= 1;
+    }
+    if (nb <= 1)      launch_mfma_shape<1, DIREFT>(a, S, mb, waves, stream);
+    else if (nb <= 2) launch_mfma_shape<2, DIREFT>(a, S, mb, waves, stream);
+    else if (nb <= 4) launch_mfma_shape<4, DIREFT>(a, S, mb, waves, stream);
+    else              launch_mfma_shape<8, DIREFT>(a, S, mb, waves, stream);
+}
+
+template <int RANK, bool DIREFT>
+void launch_valu(const ApplyArgs &a, int64_t S, hipStream_t stream)
+{
+    constexpr int RB = RANK <= 4 ? 4 : 2;
+    int waves = g_waves ? g_waves : 4;
+    if (waves == 4)
+        hipLaunchKernelGGL((valu_tile_kernel<RANK, RB, 4, DIREFT>), dim3(tile_grid(a.T, S, CHUNK_ROWS / (RB * 4))),
+                           dim3(256), 0, stream, a);
+    else if (waves == 2)
+        hipLaunchKernelGGL((valu_tile_kernel<RANK, RB, 2, DIREFT>), dim3(tile_grid(a.T, S, CHUNK_ROWS / (RB * 2))),
+                           dim3(128), 0, stream, a);
+    else
+        hipLaunchKernelGGL((valu_tile_kernel<RANK, RB, 1, DIREFT>), dim3(tile_grid(a.T, S, CHUNK_ROWS / RB)),
+                           dim3(64), 0, stream, a);
+}
+
+template <bool DIREFT>
+void launch_valu_rank(const ApplyArgs &a, int64_t S, hipStream_t stream)
+{
+    switch (a.rank) {
+    case 1: launch_valu<1, DIREFT>(a, S, stream); break;
+    case 2: launch_valu<2, DIREFT>(a, S, stream); break;
+    case 3: launch_valu<3, DIREFT>(a, S, stream); break;
+    case 4: launch_valu<4, DIREFT>(a, S, stream); break;
+    case 5: launch_valu<5, DIREFT>(a, S, stream); break;
+    case 6: launch_valu<6, DIREFT>(a, S, stream); break;
+    case 7: launch_valu<7, DIREFT>(a, S, stream); break;
+    default: launch_valu<8, DIREFT>(a, S, stream); break;
+    }
+}
+
+template <typename E, bool DIREFT>
+void launch_rows(const ApplyArgs &a, int64_t S, bool chunks_too, hipStream_t stream)
+{
+    if (chunks_too) {
+        constexpr int SPLIT = 8;
+        hipLaunchKernelGGL((row_kernel_chunks<E, DIREFT>), dim3((unsigned)(chunk_capacity(a.T, S) * SPLIT)),
+                           dim3(ROW_THREADS), 0, stream, a, SPLIT);
+    }
+    int64_t g = short_capacity(a.T, S);
+    if (g > 4096) g = 4096;
+    hipLaunchKernelGGL((row_kernel_short<E, DIREFT>), dim3((unsigned)g), dim3(ROW_THREADS), 0, stream, a);
+}
+
+enum class Path { Rows, Valu, Mfma };
+
+Path choose_path(int dtype, int rank)
+{
+    if (dtype != PREFT_BF16 || g_variant == 1) return Path::Rows;
+    const bool valu_ok = rank <= 8, mfma_ok = (rank % 4) == 0;
+    if (g_variant == 2 && valu_ok) return Path::Valu;
+    if (g_variant == 3 && mfma_ok) return Path::Mfma;
+    if (mfma_ok) return Path::Mfma;
+    if (valu_ok) return Path::Valu;
+    return Path::Rows;
+}
+
+template <bool DIREFT>
+int launch_apply(const ApplyArgs &a, int64_t S, int dtype, hipStream_t stream)
+{
+    switch (choose_path(dtype, a.rank)) {
+    case Path::Mfma:
+        launch_mfma_rank<DIREFT>(a, S, stream);
+        launch_rows<bf16_tag, DIREFT>(a, S, false, stream);
+        break;
+    case Path::Valu:
+        launch_valu_rank<DIREFT>(a, S, stream);
+        launch_rows<bf16_tag, DIREFT>(a, S, false, stream);
+        break;
+    default:
+        if (dtype == PREFT_BF16) launch_rows<bf16_tag, DIREFT>(a, S, true, stream);
+        else                     launch_rows<float, DIREFT>(a, S, true, stream);
+        break;
+    }
+    return check_launch();
+}
+
+int check_matrix(const void *p, int64_t ld, int32_t width, int dtype)
+{
+    const int per16 = dtype == PREFT_BF16 ? 8 : 4;
+    if (!p || width <= 0 || ld < width) return PREFT_EINVAL;
+    if (!aligned16(p) || (width % per16) != 0 || (ld % per16) != 0) return PREFT_EALIGN;
+    return PREFT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t preft_workspace_bytes(int32_t T, int32_t S)
+{
+    if (T < 0 || S < 0) return 0;
+    return workspace_bytes(T, S);
+}
+
+int preft_schedule(void *workspace, size_t bytes, const int32_t *seg_start, const int32_t *seg_adapter,
+                   const int32_t *seg_prefill_len, int32_t S, int32_t T, int32_t N, int mode, void *stream)
+{
+    if (mode & PREFT_SCHEDULE_READY) return PREFT_EINVAL;
+    int rc = check_tables(workspace, bytes, seg_start, seg_adapter, seg_prefill_len, S, T, N, mode);
+    if (rc != PREFT_OK || T == 0 || S == 0) return rc;
+    return launch_schedule(workspace, seg_start, seg_adapter, seg_prefill_len, S, T, N, mode,
+                           reinterpret_cast<hipStream_t>(stream));
+}
+
+int preft_lora_apply(void *y, int64_t ldy, const void *x, int64_t ldx, int32_t T, int32_t d_in, int32_t d_out,
+                     const int32_t *seg_start, const int32_t *seg_adapter, const int32_t *seg_prefill_len,
+                     int32_t S, const void *const *A_pool, const void *const *B_pool, int32_t N, int32_t rank,
+                     float scale, int dtype, int mode, void *workspace, size_t bytes, void *stream)
+{
+    if (dtype != PREFT_F32 && dtype != PREFT_BF16) return PREFT_EINVAL;
+    int rc = check_tables(workspace, bytes, seg_start, seg_adapter, seg_prefill_len, S, T, N, mode);
+    if (rc != PREFT_OK) return rc;
+    if (rank < 1 || rank > PREFT_MAX_RANK) return PREFT_EUNSUPPORTED;
+    if (T == 0 || S == 0) return PREFT_OK;
+    if ((rc = check_matrix(y, ldy, d_out, dtype)) != PREFT_OK) return rc;
+    if ((rc = check_matrix(x, ldx, d_in, dtype)) != PREFT_OK) return rc;
+    if (!A_pool || !B_pool) return PREFT_EINVAL;
+    {   // x and y must not overlap
+        const size_t es = dtype == PREFT_BF16 ? 2 : 4;
+        const char *y0 = reinterpret_cast<const char *>(y), *x0 = reinterpret_cast<const char *>(x);
+        const char *y1 = y0 + ((size_t)(T - 1) * ldy + d_out) * es, *x1 = x0 + ((size_t)(T - 1) * ldx + d_in) * es;
+        if (y0 < x1 && x0 < y1) return PREFT_EINVAL;
+    }
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (!(mode & PREFT_SCHEDULE_READY)) {
+        rc = launch_schedule(workspace, seg_start, seg_adapter, seg_prefill_len, S, T, N, mode, st);
+        if (rc != PREFT_OK) return rc;
+    }
+    ScheduleView v = view_of(workspace, T, S);
+    ApplyArgs a;
+    a.y = y; a.x = x; a.ldy = ldy; a.ldx = ldx; a.T = T; a.d_in = d_in; a.d_out = d_out;
+    a.A_pool = A_pool; a.Bt_pool = B_pool; a.bias_pool = nullptr; a.N = N; a.rank = rank; a.scale = scale;
+    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts;
+    return launch_apply<false>(a, S, dtype, st);
+}
+
+int preft_direft_apply(void *h, int64_t ldh, int32_t T, int32_t d, const int32_t *seg_start,
+                       const int32_t *seg_adapter, const int32_t *seg_prefill_len, int32_t S,
+                       const void *const *W1_pool, const void *const *W2t_pool, const void *const *b_pool,
+                       int32_t N, int32_t rank, float scale, int dtype, int mode, void *workspace, size_t bytes,
+                       void *stream)
+{
+    if (dtype != PREFT_F32 && dtype != PREFT_BF16) return PREFT_EINVAL;
+    int rc = check_tables(workspace, bytes, seg_start, seg_adapter, seg_prefill_len, S, T, N, mode);
+    if (rc != PREFT_OK) return rc;
+    if (rank < 1 || rank > PREFT_MAX_RANK) return PREFT_EUNSUPPORTED;
+    if (T == 0 || S == 0) return PREFT_OK;
+    if ((rc = check_matrix(h, ldh, d, dtype)) != PREFT_OK) return rc;
+    if (!W1_pool || !W2t_pool) return PREFT_EINVAL;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (!(mode & PREFT_SCHEDULE_READY)) {
+        rc = launch_schedule(workspace, seg_start, seg_adapter, seg_prefill_len, S, T, N, mode, st);
+        if (rc != PREFT_OK) return rc;
+    }
+    ScheduleView v = view_of(workspace, T, S);
+    ApplyArgs a;
+    a.y = h; a.x = h; a.ldy = ldh; a.ldx = ldh; a.T = T; a.d_in = d; a.d_out = d;
+    a.A_pool = W1_pool; a.Bt_pool = W2t_pool; a.bias_pool = b_pool; a.N = N; a.rank = rank; a.scale = scale;
+    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts;
+    return launch_apply<true>(a, S, dtype, st);
+}
+
+int preft_schedule_counts(const void *workspace, int32_t *counts, void *stream)
+{
+    if (!workspace || !counts) return PREFT_EINVAL;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(counts, workspace, 3 * sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess)
+        return PREFT_EHIP;
+    return hipStreamSynchronize(st) == hipSuccess ? PREFT_OK : PREFT_EHIP;
+}
+
+int preft_set_knob(int knob, int value)
+{
+    int *slot = nullptr;
+    switch (knob) {
+    case PREFT_KNOB_VARIANT:   if (value < 0 || value > 3) return PREFT_EINVAL; slot = &g_variant; break;
+    case PREFT_KNOB_WAVES:     if (value != 0 && value != 1 && value != 2 && value != 4) return PREFT_EINVAL; slot = &g_waves; break;
+    case PREFT_KNOB_ROWBLOCKS: if (value < 0 || value > 2) return PREFT_EINVAL; slot = &g_rowblocks; break;
+    default: return PREFT_EINVAL;
+    }
+    const int prev = *slot;
+    *slot = value;
+    return prev;
+}
+
+const char *preft_strerror(int code)
+{
+    switch (code) {
+    case PREFT_OK:           return "ok";
+    case PREFT_EINVAL:       return "invalid argument (null pointer, negative size, bad enum, overlapping x and y, or row stride below the width)";
+    case PREFT_EUNSUPPORTED: return "unsupported rank (must be 1..128)";
+    case PREFT_EALIGN:       return "pointer, width or row stride not a multiple of 16 bytes";
+    case PREFT_EWORKSPACE:   return "workspace missing, misaligned or smaller than preft_workspace_bytes(T, S)";
+    case PREFT_EHIP:         return "HIP runtime error at launch";
+    default:                 return "unknown preft error code";
+    }
+}
+
+int preft_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,125 @@
+// Token-segment scheduler: segment tables -> list of work units over active rows only.
+//
+// Position sets follow the paper's Eq. 1 and Eq. 4: in prefill-only mode the first
+// seg_prefill_len[s] rows of segment s are active, in all-token mode every row is; a
+// segment without a valid adapter has no active row.  Inactive rows appear in no unit, so
+// the apply kernels never touch them.
+#pragma once
+#include "common.hpp"
+
+namespace preft {
+
+constexpr int SCHED_THREADS = 1024;
+
+struct SegInfo { int32_t adapter, row0, n_act; };
+
+__device__ __forceinline__ SegInfo seg_info(const int32_t *seg_start, const int32_t *seg_adapter,
+                                             const int32_t *seg_prefill_len, int32_t s, int32_t T,
+                                             int32_t N, bool all_tokens)
+{
+    SegInfo r;
+    int32_t lo = seg_start[s], hi = seg_start[s + 1];
+    lo = max(0, min(lo, T));
+    hi = max(lo, min(hi, T));
+    int32_t len = hi - lo;
+    int32_t a = seg_adapter[s];
+    int32_t n = all_tokens ? len : max(0, min(seg_prefill_len[s], len));
+    if (a < 0 || a >= N) n = 0;
+    r.adapter = a;
+    r.row0 = lo;
+    r.n_act = n;
+    return r;
+}
+
+// Exclusive scan of one int per thread over the block; returns the block total through *total.
+__device__ __forceinline__ int32_t block_exclusive_scan(int32_t v, int32_t *lds /* >= 32 ints */, int32_t *total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
+    int32_t incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        int32_t up = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += up;
+    }
+    __syncthreads();                         // lds may still be read from a previous scan
+    if (lane == 63) lds[wave] = incl;
+    __syncthreads();
+    int32_t base = 0, sum = 0;
+    for (int w = 0; w < n_waves; ++w) {
+        int32_t t = lds[w];
+        if (w < wave) base += t;
+        sum += t;
+    }
+    *total = sum;
+    return base + incl - v;
+}
+
+// One workgroup.  Thread i owns the contiguous slice of segments [i*per, (i+1)*per), so the
+// emitted lists keep segment order (consecutive chunks of one segment share an adapter, which
+// the tile kernels exploit for cache locality).
+__global__ __launch_bounds__(SCHED_THREADS) void schedule_kernel(
+    const int32_t *__restrict__ seg_start, const int32_t *__restrict__ seg_adapter,
+    const int32_t *__restrict__ seg_prefill_len, int32_t S, int32_t T, int32_t N, int all_tokens,
+    ScheduleView out)
+{
+    __shared__ int32_t lds[32];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int32_t per = (S + SCHED_THREADS - 1) / SCHED_THREADS;
+    const int32_t s0 = min((int64_t)tid * per, (int64_t)S);
+    const int32_t s1 = min((int64_t)s0 + per, (int64_t)S);
+
+    int32_t my_chunks = 0, my_short = 0, my_act = 0;
+    for (int32_t s = s0; s < s1; ++s) {
+        SegInfo g = seg_info(seg_start, seg_adapter, seg_prefill_len, s, T, N, all_tokens != 0);
+        my_act += g.n_act;
+        if (g.n_act == 0) continue;
+        if (g.n_act <= SHORT_ROWS) my_short += g.n_act;
+        else my_chunks += (g.n_act + CHUNK_ROWS - 1) / CHUNK_ROWS;
+    }
+    int32_t tot_chunks, tot_short, tot_act;
+    int32_t chunk_off = block_exclusive_scan(my_chunks, lds, &tot_chunks);
+    int32_t short_off = block_exclusive_scan(my_short, lds, &tot_short);
+    (void)block_exclusive_scan(my_act, lds, &tot_act);
+
+    if (tid == 0) {
+        out.header[0] = min(tot_chunks, out.chunk_cap);
+        out.header[1] = min(tot_short, out.short_cap);
+        out.header[2] = tot_act;
+        out.header[3] = all_tokens;
+    }
+
+    // Emission.  All lanes of a wave run the same number of iterations; a segment with many
+    // chunks is written by the whole wave.
+    for (int32_t i = 0; i < per; ++i) {
+        const int32_t s = s0 + i;
+        SegInfo g = {-1, 0, 0};
+        if (s < s1) g = seg_info(seg_start, seg_adapter, seg_prefill_len, s, T, N, all_tokens != 0);
+        int32_t n_ch = 0;
+        if (g.n_act > 0 && g.n_act <= SHORT_ROWS) {
+            for (int32_t j = 0; j < g.n_act; ++j)
+                if (short_off + j < out.short_cap) out.shorts[short_off + j] = make_int2(g.adapter, g.row0 + j);
+            short_off += g.n_act;
+        } else if (g.n_act > SHORT_ROWS) {
+            n_ch = (g.n_act + CHUNK_ROWS - 1) / CHUNK_ROWS;
+        }
+        unsigned long long pending = __ballot(n_ch > 0);
+        while (pending) {
+            const int src = __ffsll((long long)pending) - 1;
+            pending &= pending - 1;
+            const int32_t b_off = __shfl(chunk_off, src, 64);
+            const int32_t b_n   = __shfl(g.n_act, src, 64);
+            const int32_t b_row = __shfl(g.row0, src, 64);
+            const int32_t b_a   = __shfl(g.adapter, src, 64);
+            const int32_t b_s   = __shfl(s, src, 64);
+            const int32_t b_ch  = (b_n + CHUNK_ROWS - 1) / CHUNK_ROWS;
+            for (int32_t c = lane; c < b_ch; c += 64) {
+                if (b_off + c < out.chunk_cap)
+                    out.chunks[b_off + c] = make_int4(b_a, b_row + c * CHUNK_ROWS,
+                                                      min(CHUNK_ROWS, b_n - c * CHUNK_ROWS), b_s);
+            }
+        }
+        chunk_off += n_ch;
+    }
+}
+
+}  // namespace preft

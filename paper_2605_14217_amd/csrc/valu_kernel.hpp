@@ -1,0 +1,143 @@
+// Vector-ALU tile kernel for small ranks (bf16 storage, fp32 accumulation, rank 1..8).
+//
+// At rank <= 8 the contraction is too thin for the matrix cores to matter: the pass is a
+// pure stream over the activations with r multiply-adds per element.  One wavefront owns
+// RB rows at a time and sweeps them with 16-byte loads, 64 lanes side by side:
+//
+//   shrink (Eq. 2: z = A x;  Eq. 3: z = A h + b): every lane keeps RB x r partial sums over
+//           its columns (packed bf16 dot products, fp32 accumulate); one wavefront
+//           reduction per (row, rank) finishes z.  The adapter's factor is loaded once per
+//           RB rows.
+//   expand (Eq. 2: y += s B z;  Eq. 3: h += s B^T z): a lane owns 8 consecutive output
+//           columns; their 8 x r factors are contiguous in the [d_out, r] layout and are
+//           converted once per RB rows.
+//
+// A workgroup of WAVES wavefronts owns a tile of RB * WAVES consecutive rows of a chunk;
+// wavefronts never exchange data.
+#pragma once
+#include "common.hpp"
+#include "mfma_kernel.hpp"   // xcd_unit
+
+namespace preft {
+
+template <int RANK, int RB, int WAVES, bool DIREFT>
+__global__ __launch_bounds__(WAVES * 64) void valu_tile_kernel(ApplyArgs p)
+{
+    constexpr int R = RB * WAVES;
+    constexpr int TPC = CHUNK_ROWS / R;
+    static_assert(CHUNK_ROWS % R == 0, "tile height must divide the chunk height");
+
+    const int unit = xcd_unit(p.header[0] * TPC);
+    if (unit < 0) return;
+    const int4 ch = p.chunks[unit / TPC];
+    const int tile_row0 = (unit % TPC) * R;
+    if (tile_row0 >= ch.z) return;
+    const int adapter = ch.x;
+    const int n_rows = min(R, ch.z - tile_row0);
+
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave_row0 = wave * RB;
+    if (wave_row0 >= n_rows) return;
+
+    const char *A  = reinterpret_cast<const char *>(p.A_pool[adapter]);
+    const char *Bt = reinterpret_cast<const char *>(p.Bt_pool[adapter]);
+    const int64_t ldx_b = p.ldx * 2, ldy_b = p.ldy * 2;
+
+    bool row_ok[RB];
+    const char *xp[RB];
+    char *yp[RB];
+#pragma unroll
+    for (int i = 0; i < RB; ++i) {
+        const int t = wave_row0 + i;
+        row_ok[i] = t < n_rows;
+        const int64_t row = (int64_t)ch.y + tile_row0 + min(t, n_rows - 1);   // idle rows alias the last one
+        xp[i] = reinterpret_cast<const char *>(p.x) + row * ldx_b;
+        yp[i] = reinterpret_cast<char *>(p.y) + row * ldy_b;
+    }
+
+    // ---------------------------------------------------------------- shrink
+    float z[RB][RANK];
+#pragma unroll
+    for (int i = 0; i < RB; ++i)
+#pragma unroll
+        for (int k = 0; k < RANK; ++k) z[i][k] = 0.f;
+
+    const int nvec_in = p.d_in >> 3;                          // 16-byte vectors per row
+    auto shrink_step = [&](const u32x4_t (&xv)[RB], const u32x4_t (&av)[RANK]) {
+#pragma unroll
+        for (int k = 0; k < RANK; ++k)
+#pragma unroll
+            for (int i = 0; i < RB; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    z[i][k] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, xv[i][q]),
+                                                              __builtin_bit_cast(bf16x2_t, av[k][q]),
+                                                              z[i][k], false);
+    };
+    int c = lane;
+    for (; c + 64 < nvec_in; c += 128) {                      // two sweeps in flight
+        u32x4_t xv0[RB], xv1[RB], av0[RANK], av1[RANK];
+#pragma unroll
+        for (int i = 0; i < RB; ++i) {
+            xv0[i] = ld16(xp[i] + (int64_t)c * 16);
+            xv1[i] = ld16(xp[i] + (int64_t)(c + 64) * 16);
+        }
+#pragma unroll
+        for (int k = 0; k < RANK; ++k) {
+            av0[k] = ld16(A + ((int64_t)k * p.d_in + (int64_t)c * 8) * 2);
+            av1[k] = ld16(A + ((int64_t)k * p.d_in + (int64_t)(c + 64) * 8) * 2);
+        }
+        shrink_step(xv0, av0);
+        shrink_step(xv1, av1);
+    }
+    for (; c < nvec_in; c += 64) {
+        u32x4_t xv[RB], av[RANK];
+#pragma unroll
+        for (int i = 0; i < RB; ++i) xv[i] = ld16(xp[i] + (int64_t)c * 16);
+#pragma unroll
+        for (int k = 0; k < RANK; ++k) av[k] = ld16(A + ((int64_t)k * p.d_in + (int64_t)c * 8) * 2);
+        shrink_step(xv, av);
+    }
+#pragma unroll
+    for (int k = 0; k < RANK; ++k) {
+        float bias = 0.f;
+        if (DIREFT && p.bias_pool) bias = Elem<bf16_tag>::load1(p.bias_pool[adapter], k);
+#pragma unroll
+        for (int i = 0; i < RB; ++i) z[i][k] = (wave_sum(z[i][k]) + bias) * p.scale;
+    }
+
+    // ---------------------------------------------------------------- expand
+    const int nvec_out = p.d_out >> 3;
+    for (int c = lane; c < nvec_out; c += 64) {
+        // 8 columns x RANK factors, contiguous: RANK 16-byte vectors
+        float w[8 * RANK];
+        const char *wp = Bt + (int64_t)c * 8 * RANK * 2;
+#pragma unroll
+        for (int j = 0; j < RANK; ++j) {
+            const u32x4_t raw = ld16(wp + j * 16);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                w[j * 8 + 2 * q] = bf16_lo(raw[q]);
+                w[j * 8 + 2 * q + 1] = bf16_hi(raw[q]);
+            }
+        }
+        u32x4_t yv[RB];
+#pragma unroll
+        for (int i = 0; i < RB; ++i) yv[i] = ld16(yp[i] + (int64_t)c * 16);
+#pragma unroll
+        for (int i = 0; i < RB; ++i) {
+            float out[8];
+            Elem<bf16_tag>::unpack(yv[i], out);
+#pragma unroll
+            for (int col = 0; col < 8; ++col) {
+                float d = 0.f;
+#pragma unroll
+                for (int k = 0; k < RANK; ++k) d = fmaf(w[col * RANK + k], z[i][k], d);
+                out[col] += d;
+            }
+            if (row_ok[i]) st16(yp[i] + (int64_t)c * 16, Elem<bf16_tag>::pack(out));
+        }
+    }
+}
+
+}  // namespace preft

@@ -1,0 +1,173 @@
+"""Shared plumbing of the GPU parity tests: run the HIP path through the C ABI binding, run
+the CPU oracle on the very same tensors, compare.
+
+Bar (stated here once, used by every parity test):
+  * rows outside the position set: bit-identical to the input (compared on the raw bits);
+  * active rows: row-wise max-norm relative error  max_t |g_t - o_t|_inf / |o_t|_inf
+    <= 1e-2 for bf16 storage with fp32 accumulation, <= 1e-5 for fp32;
+  * padding beyond the row width (ld > width) and guard rows around the buffer: untouched.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2605_14217_amd as preft
+from oracle import preft_oracle as ora
+from paper_2605_14217_amd import workloads as wl
+
+TOL = {"bf16": 1e-2, "f32": 1e-5}
+GUARD_ROWS = 3
+
+
+def dev_tables(tab: wl.SegmentTable, device="cuda"):
+    return (torch.from_numpy(tab.seg_start.copy()).to(device),
+            torch.from_numpy(tab.seg_adapter.copy()).to(device),
+            torch.from_numpy(tab.seg_prefill_len.copy()).to(device))
+
+
+def padded(t: torch.Tensor, pad_cols: int, sentinel: float):
+    """Copy of t inside a larger buffer: GUARD_ROWS sentinel rows above and below, pad_cols
+    sentinel columns to the right.  Returns (buffer, view)."""
+    T, d = t.shape
+    buf = torch.full((T + 2 * GUARD_ROWS, d + pad_cols), sentinel, dtype=t.dtype, device=t.device)
+    view = buf[GUARD_ROWS:GUARD_ROWS + T, :d]
+    view.copy_(t)
+    return buf, view
+
+
+def bits(t: torch.Tensor) -> torch.Tensor:
+    return t.contiguous().view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32)
+
+
+def check_guards(buf: torch.Tensor, T: int, d: int, sentinel: float):
+    ref = torch.full_like(buf, sentinel)
+    assert torch.equal(bits(buf[:GUARD_ROWS]), bits(ref[:GUARD_ROWS])), "guard rows above were written"
+    assert torch.equal(bits(buf[GUARD_ROWS + T:]), bits(ref[GUARD_ROWS + T:])), "guard rows below were written"
+    if buf.shape[1] > d:
+        assert torch.equal(bits(buf[:, d:]), bits(ref[:, d:])), "row padding was written"
+
+
+def compare(got: torch.Tensor, before: torch.Tensor, want64: np.ndarray, row_adapter: np.ndarray,
+            dtype: str, rows=None):
+    """got/before: device tensors [T,d] (after / before the call); want64: oracle output for
+    `rows` (all rows if None).  Checks every inactive row bitwise (on the device) and the
+    selected active rows against the oracle; returns the worst row-wise relative error."""
+    T = got.shape[0]
+    active = row_adapter >= 0
+    inactive = torch.from_numpy(~active).to(got.device)
+    if bool(inactive.any()):
+        assert torch.equal(bits(got)[inactive], bits(before)[inactive]), \
+            "a row outside the position set was modified"
+    if rows is None:
+        rows = np.arange(T)
+    rows = np.asarray(rows)
+    sel_active = active[rows]
+    if not sel_active.any():
+        return 0.0
+    g = got[torch.from_numpy(rows[sel_active]).to(got.device)].double().cpu().numpy()
+    o = want64[sel_active]
+    err = np.max(np.abs(g - o), axis=1) / np.maximum(np.max(np.abs(o), axis=1), 1e-30)
+    worst = float(err.max())
+    assert worst <= TOL[dtype], f"row-wise relative error {worst:.3e} exceeds {TOL[dtype]:.0e}"
+    return worst
+
+
+def lora_pools_to_device(pool: wl.LoraPool, perm=None):
+    """Pointer tables for the C ABI.  LoRA's A [r,m] and B [n,r] are already in the ABI layout.
+    `perm` scatters the slots in memory so that nothing can rely on slot i sitting at base+i*size."""
+    N = pool.N
+    order = list(range(N)) if perm is None else list(perm)
+    A_store = [None] * N
+    B_store = [None] * N
+    for slot in order:                       # allocate in permuted order
+        A_store[slot] = pool.A[slot].clone()
+        B_store[slot] = pool.B[slot].clone()
+    return preft.pointer_table(A_store), preft.pointer_table(B_store), (A_store, B_store)
+
+
+def direft_pools_to_device(pool: wl.DireftPool, perm=None, bias=True):
+    """W1 = paper's A [r,d]; W2t = transpose of the paper's B -> [d,r]; b [r]."""
+    N = pool.N
+    order = list(range(N)) if perm is None else list(perm)
+    W1, W2t, b = [None] * N, [None] * N, [None] * N
+    for slot in order:
+        W1[slot] = pool.A[slot].clone()
+        W2t[slot] = pool.B[slot].t().contiguous()
+        b[slot] = pool.b[slot].clone()
+    return (preft.pointer_table(W1), preft.pointer_table(W2t),
+            preft.pointer_table(b) if bias else None, (W1, W2t, b))
+
+
+def run_lora_case(tab: wl.SegmentTable, pool: wl.LoraPool, x: torch.Tensor, y0: torch.Tensor, dtype: str,
+                  scale: float, all_tokens: bool, pad_cols=0, rows=None, perm=None, reuse_schedule=False):
+    """Tensors live on the GPU; returns (worst error, schedule counts)."""
+    N, r = pool.N, pool.r
+    T = tab.T
+    mode = preft.PREFT_ALL_TOKENS if all_tokens else preft.PREFT_PREFILL_ONLY
+    ss, sa, sp = dev_tables(tab)
+    Ap, Bp, keep = lora_pools_to_device(pool, perm)
+    ybuf, y = padded(y0, pad_cols, 7.0)
+    xbuf, xv = padded(x, pad_cols, -3.0)
+    ws = preft.new_workspace(T, tab.S)
+    if reuse_schedule:
+        preft.preft_schedule(ws, ss, sa, sp, T, N, mode)
+        preft.preft_lora_apply(y, xv, ss, sa, sp, Ap, Bp, r, scale, mode | preft.PREFT_SCHEDULE_READY, ws)
+    else:
+        preft.preft_lora_apply(y, xv, ss, sa, sp, Ap, Bp, r, scale, mode, ws)
+    torch.cuda.synchronize()
+    counts = preft.preft_schedule_counts(ws)
+    check_guards(ybuf, T, y0.shape[1], 7.0)
+    assert torch.equal(bits(xv), bits(x)), "x was modified"
+    pos = ora.ALL_POSITIONS if all_tokens else ora.PROMPT_ONLY
+    row_adapter = ora.positions(T, tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, N, pos)
+    needed = set(np.unique(row_adapter[row_adapter >= 0] if rows is None else
+                           row_adapter[np.asarray(rows)][row_adapter[np.asarray(rows)] >= 0]).tolist())
+    A_cpu = [pool.A[i].cpu() if i in needed else None for i in range(N)]
+    B_cpu = [pool.B[i].cpu() if i in needed else None for i in range(N)]
+    if rows is None:
+        want = ora.lora(y0.cpu(), x.cpu(), tab.seg_start, tab.seg_adapter, tab.seg_prefill_len,
+                        A_cpu, B_cpu, r, scale, pos)
+    else:                                    # large batches: only the sampled rows leave the GPU
+        idx = torch.from_numpy(np.asarray(rows)).to(x.device)
+        want = ora.lora(y0[idx].cpu(), x[idx].cpu(), tab.seg_start, tab.seg_adapter, tab.seg_prefill_len,
+                        A_cpu, B_cpu, r, scale, pos, rows=rows, gathered=True)
+    worst = compare(y, y0, want, row_adapter, dtype, rows=rows)
+    assert counts[2] == int((row_adapter >= 0).sum()), "scheduler's active-row count differs from the oracle's"
+    return worst, counts
+
+
+def run_direft_case(tab: wl.SegmentTable, pool: wl.DireftPool, h0: torch.Tensor, dtype: str, scale: float,
+                    all_tokens: bool, pad_cols=0, rows=None, perm=None, bias=True, reuse_schedule=False):
+    N, r = pool.N, pool.r
+    T = tab.T
+    mode = preft.PREFT_ALL_TOKENS if all_tokens else preft.PREFT_PREFILL_ONLY
+    ss, sa, sp = dev_tables(tab)
+    W1p, W2tp, bp, keep = direft_pools_to_device(pool, perm, bias)
+    hbuf, h = padded(h0, pad_cols, 7.0)
+    ws = preft.new_workspace(T, tab.S)
+    if reuse_schedule:
+        preft.preft_schedule(ws, ss, sa, sp, T, N, mode)
+        preft.preft_direft_apply(h, ss, sa, sp, W1p, W2tp, bp, r, scale, mode | preft.PREFT_SCHEDULE_READY, ws)
+    else:
+        preft.preft_direft_apply(h, ss, sa, sp, W1p, W2tp, bp, r, scale, mode, ws)
+    torch.cuda.synchronize()
+    counts = preft.preft_schedule_counts(ws)
+    check_guards(hbuf, T, h0.shape[1], 7.0)
+    pos = ora.ALL_POSITIONS if all_tokens else ora.PROMPT_ONLY
+    row_adapter = ora.positions(T, tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, N, pos)
+    sel = row_adapter if rows is None else row_adapter[np.asarray(rows)]
+    needed = set(np.unique(sel[sel >= 0]).tolist())
+    A_cpu = [pool.A[i].cpu() if i in needed else None for i in range(N)]
+    B_cpu = [pool.B[i].cpu() if i in needed else None for i in range(N)]
+    b_cpu = [pool.b[i].cpu() if i in needed else None for i in range(N)] if bias else None
+    if rows is None:
+        want = ora.direft(h0.cpu(), tab.seg_start, tab.seg_adapter, tab.seg_prefill_len,
+                          A_cpu, B_cpu, b_cpu, r, scale, pos)
+    else:
+        idx = torch.from_numpy(np.asarray(rows)).to(h0.device)
+        want = ora.direft(h0[idx].cpu(), tab.seg_start, tab.seg_adapter, tab.seg_prefill_len,
+                          A_cpu, B_cpu, b_cpu, r, scale, pos, rows=rows, gathered=True)
+    worst = compare(h, h0, want, row_adapter, dtype, rows=rows)
+    assert counts[2] == int((row_adapter >= 0).sum())
+    return worst, counts

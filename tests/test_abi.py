@@ -1,0 +1,113 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the header declares,
+and rejects bad arguments before touching the GPU."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2605_14217_amd as preft
+from paper_2605_14217_amd import binding
+from paper_2605_14217_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2605_14217_amd.build import build_library
+        build_library()
+    return preft.load_library()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "preft.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(preft_[a-z_]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree_and_every_symbol_is_exported(lib):
+    declared = _declared_functions()
+    assert declared == sorted(binding.ABI_SYMBOLS)
+    for name in declared:
+        assert hasattr(lib, name), f"{name} is declared in preft.h but not exported"
+
+
+def test_missing_library_fails_loudly(tmp_path):
+    with pytest.raises(FileNotFoundError):
+        preft.load_library(str(tmp_path / "libpreft.so"))
+
+
+def test_version_and_error_strings(lib):
+    assert preft.preft_version() >= 100
+    for code in (0, -1, -2, -3, -4, -5):
+        assert preft.preft_strerror(code)
+    assert "unknown" in preft.preft_strerror(-99)
+
+
+def test_knob_validation(lib):
+    assert lib.preft_set_knob(99, 0) == -1
+    assert lib.preft_set_knob(preft.PREFT_KNOB_VARIANT, 7) == -1
+    assert lib.preft_set_knob(preft.PREFT_KNOB_WAVES, 3) == -1
+    prev = preft.preft_set_knob(preft.PREFT_KNOB_VARIANT, 1)
+    assert preft.preft_set_knob(preft.PREFT_KNOB_VARIANT, prev) == 1
+
+
+def test_workspace_is_large_enough_for_any_table(lib):
+    """Host-side capacity rule: chunks of <=128 rows for segments with more than 4 active rows,
+    one entry per row otherwise; the byte count must cover header + both lists."""
+    rng = np.random.Generator(np.random.PCG64(0))
+    assert preft.preft_workspace_bytes(-1, 3) == 0
+    for trial in range(200):
+        S = int(rng.integers(1, 60))
+        tab = wl.random_segments(rng, S, 4, int(rng.integers(1, 700)), p_none=0.0, p_empty=0.05)
+        lens = tab.seg_len
+        long_ = lens[lens > 4]
+        chunks = int(np.sum((long_ + 127) // 128))
+        shorts = int(np.sum(lens[lens <= 4]))
+        need = 64 + 16 * chunks + 8 * shorts
+        assert preft.preft_workspace_bytes(tab.T, tab.S) >= need
+
+
+def test_bad_arguments_are_rejected_before_any_launch(lib):
+    fake = ctypes.c_void_p(0x7f0000001000)        # never dereferenced: every call must fail first
+    odd = ctypes.c_void_p(0x7f0000001004)
+    ws_bytes = preft.preft_workspace_bytes(64, 4)
+
+    def lora(y=fake, ldy=64, x=ctypes.c_void_p(0x7f0000100000), ldx=64, T=64, d_in=64, d_out=64, S=4, N=2,
+             rank=4, dtype=preft.PREFT_BF16, mode=0, ws=fake, wsb=ws_bytes, A=fake, B=fake, tables=fake):
+        return lib.preft_lora_apply(y, ldy, x, ldx, T, d_in, d_out, tables, tables, tables, S, A, B, N, rank,
+                                    1.0, dtype, mode, ws, wsb, None)
+
+    assert lora(T=-1) == -1
+    assert lora(dtype=5) == -1
+    assert lora(mode=2) == -1
+    assert lora(rank=0) == -2
+    assert lora(rank=129) == -2
+    assert lora(tables=None) == -1
+    assert lora(ws=None) == -4
+    assert lora(wsb=8) == -4
+    assert lora(ws=odd) == -4
+    assert lora(y=odd) == -3
+    assert lora(d_in=60) == -3            # 60 bf16 = 120 bytes: not a multiple of 16
+    assert lora(ldy=68) == -3
+    assert lora(ldx=32) == -1             # row stride below the width
+    assert lora(A=None) == -1
+    assert lora(x=fake) == -1             # x overlaps y
+    assert lora(T=0) == 0 and lora(S=0) == 0
+
+    def direft(h=fake, ldh=64, T=64, d=64, S=4, N=2, rank=4, dtype=preft.PREFT_F32, mode=1, ws=fake,
+               wsb=ws_bytes, W1=fake, W2=fake, tables=fake):
+        return lib.preft_direft_apply(h, ldh, T, d, tables, tables, tables, S, W1, W2, None, N, rank, 1.0,
+                                      dtype, mode, ws, wsb, None)
+
+    assert direft(S=-2) == -1
+    assert direft(rank=200) == -2
+    assert direft(d=6) == -3              # 6 fp32 = 24 bytes
+    assert direft(h=None) == -1
+    assert direft(W2=None) == -1
+    assert direft(wsb=0) == -4
+    assert lib.preft_schedule(fake, ws_bytes, fake, fake, fake, 4, 64, 2, preft.PREFT_SCHEDULE_READY, None) == -1
+    assert lib.preft_schedule(fake, 8, fake, fake, fake, 4, 64, 2, 0, None) == -4

@@ -1,0 +1,297 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the same
+seeded inputs (see parity_util for the bar).  Sizes are chosen so that the oracle finishes in
+seconds while the batch still spans several tiles, ragged tails and every segment kind."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_14217_amd as preft
+from paper_2605_14217_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+VARIANT_AUTO, VARIANT_ROW, VARIANT_VALU, VARIANT_MFMA = 0, 1, 2, 3
+
+
+@pytest.fixture(autouse=True)
+def _announce_and_reset(request):
+    print(f"\n[case] {request.node.name}", flush=True)
+    sys.stdout.flush()
+    yield
+    preft.preft_set_knob(preft.PREFT_KNOB_VARIANT, 0)
+    preft.preft_set_knob(preft.PREFT_KNOB_WAVES, 0)
+    preft.preft_set_knob(preft.PREFT_KNOB_ROWBLOCKS, 0)
+
+
+def _set(variant=0, waves=0, rowblocks=0):
+    preft.preft_set_knob(preft.PREFT_KNOB_VARIANT, variant)
+    preft.preft_set_knob(preft.PREFT_KNOB_WAVES, waves)
+    preft.preft_set_knob(preft.PREFT_KNOB_ROWBLOCKS, rowblocks)
+
+
+def _mixed_table(seed, N, n_prompts=6, max_len=300, n_decode=10):
+    """Prompt chunks of ragged length (several tiles + tails), decode rows, a sequence whose
+    prompt ends inside the segment, an empty segment, an adapter-less prompt, an id >= N."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    lens = list(rng.integers(5, max_len + 1, size=n_prompts)) + [129, 128, 17, 4, 3, 0, 200, 64]
+    ids = list(rng.integers(0, N, size=n_prompts)) + [0, N - 1, 1, 0, 1, 0, -1, N + 3]
+    pre = list(lens[:n_prompts]) + [129, 128, 9, 4, 2, 0, 200, 64]
+    lens += [1] * n_decode
+    ids += list(rng.integers(0, N, size=n_decode))
+    pre += [0] * n_decode
+    order = rng.permutation(len(lens))
+    return wl.from_lengths(np.asarray(lens)[order], np.asarray(ids)[order], np.asarray(pre)[order])
+
+
+# ---------------------------------------------------------------------------------------
+# Tiny configuration, fp32, exactly as specified (hidden 512, 4 adapters, rank 4, scale 2)
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("all_tokens", [False, True])
+def test_tiny_fp32_lora_and_direft(all_tokens):
+    from parity_util import run_direft_case, run_lora_case
+    tab = wl.make_segments("tiny", seed=0)
+    assert tab.T == 8 * 64 + 8 and tab.S == 16
+    pool = wl.lora_pool(4, 4, 512, 512, "f32", device="cuda", seed=0)
+    x = wl.activations(tab.T, 512, "f32", device="cuda", seed=1)
+    y0 = wl.activations(tab.T, 512, "f32", device="cuda", seed=2)
+    worst, counts = run_lora_case(tab, pool, x, y0, "f32", 2.0, all_tokens)
+    print(f"  lora worst rel err {worst:.2e} counts {counts}")
+    assert counts[2] == (520 if all_tokens else 512)
+    dp = wl.direft_pool(4, 4, 512, "f32", device="cuda", seed=0)
+    worst, counts = run_direft_case(tab, dp, x, "f32", 0.5, all_tokens)
+    print(f"  direft worst rel err {worst:.2e} counts {counts}")
+
+
+# ---------------------------------------------------------------------------------------
+# bf16: every kernel variant x rank x mode on a mixed batch with ragged tiles
+# ---------------------------------------------------------------------------------------
+LORA_CASES = [
+    # (variant, rank, d_in, d_out, waves, rowblocks)
+    (VARIANT_ROW, 1, 256, 128, 0, 0), (VARIANT_ROW, 6, 264, 136, 0, 0), (VARIANT_ROW, 16, 512, 256, 0, 0),
+    (VARIANT_ROW, 12, 128, 520, 0, 0), (VARIANT_ROW, 100, 128, 64, 0, 0),
+    (VARIANT_VALU, 1, 1024, 512, 0, 0), (VARIANT_VALU, 2, 520, 264, 2, 0), (VARIANT_VALU, 3, 512, 1032, 1, 0),
+    (VARIANT_VALU, 4, 1024, 256, 0, 0), (VARIANT_VALU, 5, 136, 128, 0, 0), (VARIANT_VALU, 7, 256, 520, 2, 0),
+    (VARIANT_VALU, 8, 1024, 1024, 0, 0),
+    (VARIANT_MFMA, 4, 512, 512, 4, 1), (VARIANT_MFMA, 8, 1024, 520, 2, 1), (VARIANT_MFMA, 16, 1024, 1024, 1, 1),
+    (VARIANT_MFMA, 16, 520, 264, 4, 2), (VARIANT_MFMA, 32, 512, 1024, 2, 2), (VARIANT_MFMA, 64, 1024, 512, 4, 2),
+    (VARIANT_MFMA, 64, 264, 136, 1, 1), (VARIANT_MFMA, 128, 256, 256, 4, 1), (VARIANT_MFMA, 24, 512, 256, 2, 2),
+    (VARIANT_MFMA, 20, 136, 72, 1, 2), (VARIANT_MFMA, 128, 128, 136, 2, 2),
+    (VARIANT_AUTO, 1, 2048, 512, 0, 0), (VARIANT_AUTO, 8, 512, 2048, 0, 0), (VARIANT_AUTO, 16, 2048, 2048, 0, 0),
+    (VARIANT_AUTO, 9, 256, 256, 0, 0), (VARIANT_AUTO, 64, 1024, 1024, 0, 0),
+]
+
+
+@pytest.mark.parametrize("variant,rank,d_in,d_out,waves,rowblocks", LORA_CASES)
+def test_bf16_lora_variants(variant, rank, d_in, d_out, waves, rowblocks):
+    from parity_util import run_lora_case
+    N = 5
+    tab = _mixed_table(rank * 1000 + d_in, N)
+    pool = wl.lora_pool(N, rank, d_in, d_out, "bf16", device="cuda", seed=rank)
+    x = wl.activations(tab.T, d_in, "bf16", device="cuda", seed=11)
+    y0 = wl.activations(tab.T, d_out, "bf16", device="cuda", seed=12)
+    for all_tokens in (False, True):
+        _set(variant, waves, rowblocks)
+        worst, counts = run_lora_case(tab, pool, x, y0, "bf16", 2.0, all_tokens, pad_cols=8 if rank % 2 else 0,
+                                      perm=[3, 0, 4, 1, 2])
+        print(f"  all_tokens={all_tokens} worst rel err {worst:.2e} counts {counts}")
+
+
+DIREFT_CASES = [
+    (VARIANT_ROW, 4, 256, 0, 0), (VARIANT_ROW, 7, 136, 0, 0),
+    (VARIANT_VALU, 1, 512, 0, 0), (VARIANT_VALU, 4, 1032, 2, 0), (VARIANT_VALU, 8, 512, 1, 0),
+    (VARIANT_MFMA, 8, 1024, 4, 1), (VARIANT_MFMA, 16, 520, 2, 2), (VARIANT_MFMA, 32, 2048, 1, 2),
+    (VARIANT_MFMA, 64, 256, 4, 1), (VARIANT_AUTO, 16, 4096, 0, 0), (VARIANT_AUTO, 2, 1024, 0, 0),
+]
+
+
+@pytest.mark.parametrize("variant,rank,d,waves,rowblocks", DIREFT_CASES)
+def test_bf16_direft_variants(variant, rank, d, waves, rowblocks):
+    from parity_util import run_direft_case
+    N = 5
+    tab = _mixed_table(rank * 77 + d, N, max_len=200 if d >= 2048 else 300)
+    pool = wl.direft_pool(N, rank, d, "bf16", device="cuda", seed=rank)
+    h = wl.activations(tab.T, d, "bf16", device="cuda", seed=13)
+    for all_tokens, scale, bias in ((False, 1.0, True), (True, 1.0 / np.sqrt(rank), True), (False, 0.75, False)):
+        _set(variant, waves, rowblocks)
+        worst, counts = run_direft_case(tab, pool, h, "bf16", scale, all_tokens, pad_cols=8, perm=[2, 4, 0, 3, 1],
+                                        bias=bias)
+        print(f"  all_tokens={all_tokens} bias={bias} worst rel err {worst:.2e} counts {counts}")
+
+
+@pytest.mark.parametrize("rank,d", [(3, 132), (8, 64), (17, 260)])
+def test_fp32_generic_path(rank, d):
+    from parity_util import run_direft_case, run_lora_case
+    N = 4
+    tab = _mixed_table(rank + d, N, max_len=150)
+    pool = wl.lora_pool(N, rank, d, d + 4, "f32", device="cuda", seed=rank)
+    x = wl.activations(tab.T, d, "f32", device="cuda", seed=21)
+    y0 = wl.activations(tab.T, d + 4, "f32", device="cuda", seed=22)
+    worst, _ = run_lora_case(tab, pool, x, y0, "f32", 2.0, True, pad_cols=4)
+    print(f"  lora worst rel err {worst:.2e}")
+    dp = wl.direft_pool(N, rank, d, "f32", device="cuda", seed=rank)
+    worst, _ = run_direft_case(tab, dp, x, "f32", 1.0, False)
+    print(f"  direft worst rel err {worst:.2e}")
+
+
+# ---------------------------------------------------------------------------------------
+# the five batch structures, shrunk so that the oracle finishes in seconds
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("config,scale_down,rank,d_in,d_out", [
+    ("llama8b_lora", 8, 16, 1024, 1024), ("llama8b_lora", 8, 1, 1024, 256),
+    ("llama70b_lora", 16, 64, 1024, 512), ("skewed70b", 32, 32, 512, 512),
+])
+def test_scaled_down_config_lora(config, scale_down, rank, d_in, d_out):
+    from parity_util import run_lora_case
+    cfg = wl.CONFIGS[config]
+    tab = wl.make_segments(config, seed=0, scale_down=scale_down)
+    pool = wl.lora_pool(cfg["N"], rank, d_in, d_out, "bf16", device="cuda", seed=3)
+    x = wl.activations(tab.T, d_in, "bf16", device="cuda", seed=31)
+    y0 = wl.activations(tab.T, d_out, "bf16", device="cuda", seed=32)
+    rows = wl.sample_rows(tab, 3, max_rows=1500)
+    for all_tokens in (False, True):
+        worst, counts = run_lora_case(tab, pool, x, y0, "bf16", cfg["lora_scale"], all_tokens, rows=rows,
+                                      reuse_schedule=all_tokens)
+        print(f"  T={tab.T} S={tab.S} all_tokens={all_tokens} worst {worst:.2e} counts {counts}")
+
+
+@pytest.mark.parametrize("config,scale_down,rank,d", [("llama8b_direft", 8, 8, 1024), ("skewed70b", 32, 32, 1024)])
+def test_scaled_down_config_direft(config, scale_down, rank, d):
+    from parity_util import run_direft_case
+    cfg = wl.CONFIGS[config]
+    tab = wl.make_segments(config, seed=0, scale_down=scale_down)
+    pool = wl.direft_pool(cfg["N"], rank, d, "bf16", device="cuda", seed=4)
+    h = wl.activations(tab.T, d, "bf16", device="cuda", seed=33)
+    rows = wl.sample_rows(tab, 3, max_rows=1500)
+    for all_tokens in (False, True):
+        worst, counts = run_direft_case(tab, pool, h, "bf16", 1.0, all_tokens, rows=rows, reuse_schedule=not all_tokens)
+        print(f"  T={tab.T} S={tab.S} all_tokens={all_tokens} worst {worst:.2e} counts {counts}")
+
+
+# ---------------------------------------------------------------------------------------
+# scheduler and degenerate cases
+# ---------------------------------------------------------------------------------------
+def test_schedule_counts_match_the_tables():
+    from parity_util import dev_tables
+    rng = np.random.Generator(np.random.PCG64(5))
+    for trial in range(6):
+        N = 7
+        S = int(rng.integers(1, 3000))
+        tab = wl.random_segments(rng, S, N + 2, int(rng.integers(1, 600)))
+        if tab.T == 0:
+            continue
+        ss, sa, sp = dev_tables(tab)
+        ws = preft.new_workspace(tab.T, tab.S)
+        for mode in (preft.PREFT_PREFILL_ONLY, preft.PREFT_ALL_TOKENS):
+            ws.fill_(0xAB)
+            preft.preft_schedule(ws, ss, sa, sp, tab.T, N, mode)
+            got = preft.preft_schedule_counts(ws)
+            has = (tab.seg_adapter >= 0) & (tab.seg_adapter < N)
+            n = np.where(has, tab.seg_len if mode else np.minimum(tab.seg_prefill_len, tab.seg_len), 0)
+            want = (int(np.sum((n[n > 4] + 127) // 128)), int(np.sum(n[n <= 4])), int(n.sum()))
+            assert got == want
+            # the lists cover exactly the active rows, each once
+            hdr = ws[:64].view(torch.int32).cpu().numpy()
+            chunks = ws[64:64 + 16 * hdr[0]].view(torch.int32).view(-1, 4).cpu().numpy()
+            cap = (preft.preft_workspace_bytes(tab.T, tab.S) - 64)
+            chunk_cap = tab.T // 128 + min(tab.S, tab.T // 5) + 1
+            shorts = ws[64 + 16 * chunk_cap:64 + 16 * chunk_cap + 8 * hdr[1]].view(torch.int32).view(-1, 2).cpu().numpy()
+            covered = np.zeros(tab.T, dtype=np.int32)
+            owner = np.full(tab.T, -1, dtype=np.int32)
+            for a, row0, nrows, seg in chunks:
+                assert 1 <= nrows <= 128
+                covered[row0:row0 + nrows] += 1
+                owner[row0:row0 + nrows] = a
+            for a, row in shorts:
+                covered[row] += 1
+                owner[row] = a
+            from oracle import preft_oracle as ora
+            want_owner = ora.positions(tab.T, tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, N,
+                                       ora.ALL_POSITIONS if mode else ora.PROMPT_ONLY)
+            assert np.array_equal(covered, (want_owner >= 0).astype(np.int32))
+            assert np.array_equal(owner, want_owner)
+            assert cap > 0
+
+
+def test_all_decode_batch_is_skipped_in_prefill_only_mode():
+    from parity_util import bits, dev_tables, lora_pools_to_device
+    N, S, d = 8, 300, 512
+    rng = np.random.Generator(np.random.PCG64(6))
+    tab = wl.from_lengths(np.ones(S), rng.integers(0, N, size=S), np.zeros(S))
+    pool = wl.lora_pool(N, 16, d, d, "bf16", device="cuda", seed=6)
+    x = wl.activations(S, d, "bf16", device="cuda", seed=61)
+    y0 = wl.activations(S, d, "bf16", device="cuda", seed=62)
+    y = y0.clone()
+    ss, sa, sp = dev_tables(tab)
+    Ap, Bp, keep = lora_pools_to_device(pool)
+    ws = preft.new_workspace(tab.T, tab.S)
+    preft.preft_lora_apply(y, x, ss, sa, sp, Ap, Bp, 16, 2.0, preft.PREFT_PREFILL_ONLY, ws)
+    torch.cuda.synchronize()
+    assert preft.preft_schedule_counts(ws) == (0, 0, 0)
+    assert torch.equal(bits(y), bits(y0))
+    preft.preft_lora_apply(y, x, ss, sa, sp, Ap, Bp, 16, 2.0, preft.PREFT_ALL_TOKENS, ws)
+    torch.cuda.synchronize()
+    assert preft.preft_schedule_counts(ws) == (0, S, S)
+    assert not torch.equal(bits(y), bits(y0))
+
+
+def test_zero_adapters_and_zero_scale_leave_values_unchanged():
+    from parity_util import dev_tables, lora_pools_to_device
+    N, d, r = 3, 256, 16
+    tab = _mixed_table(9, N)
+    pool = wl.lora_pool(N, r, d, d, "bf16", device="cuda", seed=9)
+    zero_B = wl.LoraPool(pool.A, torch.zeros_like(pool.B))
+    x = wl.activations(tab.T, d, "bf16", device="cuda", seed=91)
+    y0 = wl.activations(tab.T, d, "bf16", device="cuda", seed=92)
+    ss, sa, sp = dev_tables(tab)
+    ws = preft.new_workspace(tab.T, tab.S)
+    for p, scale in ((zero_B, 2.0), (pool, 0.0)):
+        Ap, Bp, keep = lora_pools_to_device(p)
+        y = y0.clone()
+        preft.preft_lora_apply(y, x, ss, sa, sp, Ap, Bp, r, scale, preft.PREFT_ALL_TOKENS, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(y, y0)     # value equality (a zero delta may rewrite -0.0 as itself)
+
+
+def test_results_are_deterministic_and_schedule_reuse_matches():
+    from parity_util import dev_tables, lora_pools_to_device
+    N, d, r = 6, 1024, 16
+    tab = wl.make_segments("llama8b_lora", seed=1, scale_down=8)
+    pool = wl.lora_pool(64, r, d, d, "bf16", device="cuda", seed=10)
+    x = wl.activations(tab.T, d, "bf16", device="cuda", seed=101)
+    y0 = wl.activations(tab.T, d, "bf16", device="cuda", seed=102)
+    ss, sa, sp = dev_tables(tab)
+    Ap, Bp, keep = lora_pools_to_device(pool)
+    ws = preft.new_workspace(tab.T, tab.S)
+    outs = []
+    for i in range(3):
+        y = y0.clone()
+        mode = preft.PREFT_PREFILL_ONLY
+        if i == 2:
+            mode |= preft.PREFT_SCHEDULE_READY        # schedule left in ws by the previous call
+        preft.preft_lora_apply(y, x, ss, sa, sp, Ap, Bp, r, 2.0, mode, ws)
+        torch.cuda.synchronize()
+        outs.append(y)
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+
+
+def test_gpu_side_error_codes():
+    N, d = 2, 64
+    tab = wl.from_lengths([8], [0], [8])
+    from parity_util import dev_tables, lora_pools_to_device
+    ss, sa, sp = dev_tables(tab)
+    pool = wl.lora_pool(N, 4, d, d, "bf16", device="cuda", seed=1)
+    Ap, Bp, keep = lora_pools_to_device(pool)
+    x = wl.activations(8, d, "bf16", device="cuda", seed=1)
+    y = wl.activations(8, d, "bf16", device="cuda", seed=2)
+    ws = preft.new_workspace(8, 1)
+    with pytest.raises(preft.PreftError) as e:
+        preft.preft_lora_apply(y, y, ss, sa, sp, Ap, Bp, 4, 1.0, 0, ws)          # x aliases y
+    assert e.value.code == -1
+    with pytest.raises(preft.PreftError) as e:
+        preft.preft_lora_apply(y, x, ss, sa, sp, Ap, Bp, 4, 1.0, 0, ws[:32])     # workspace too small
+    assert e.value.code == -4
+    with pytest.raises(preft.PreftError) as e:
+        preft.preft_lora_apply(y[:, 4:], x[:, 4:], ss, sa, sp, Ap, Bp, 4, 1.0, 0, ws)   # misaligned base
+    assert e.value.code == -3

@@ -345,10 +345,17 @@ def test_row_selection_matches_full_run():
     full = _lora(tab, pool, x, y0)
     rows = wl.sample_rows(tab, 2)
     assert np.array_equal(_lora(tab, pool, x, y0, rows=rows), full[rows])
+    idx = torch.from_numpy(rows)
+    got = ora.lora(y0[idx], x[idx], tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, list(pool.A),
+                   list(pool.B), pool.r, 2.0, ora.PROMPT_ONLY, rows=rows, gathered=True)
+    assert np.array_equal(got, full[rows])
     tab, dp, h = _rand_direft_case(20, S=20)
     full = _direft(tab, dp, h)
     rows = wl.sample_rows(tab, 2)
     assert np.array_equal(_direft(tab, dp, h, rows=rows), full[rows])
+    got = ora.direft(h[torch.from_numpy(rows)], tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, list(dp.A),
+                     list(dp.B), list(dp.b), dp.r, 1.0, ora.PROMPT_ONLY, rows=rows, gathered=True)
+    assert np.array_equal(got, full[rows])
 
 
 # ---------------------------------------------------------------------------------------
