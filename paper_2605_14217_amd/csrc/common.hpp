@@ -72,9 +72,21 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// 16-byte global accesses
-__device__ __forceinline__ u32x4_t ld16(const void *p) { return *reinterpret_cast<const u32x4_t *>(p); }
-__device__ __forceinline__ void st16(void *p, u32x4_t v) { *reinterpret_cast<u32x4_t *>(p) = v; }
+// Pointers read from a pool table are generic; every buffer this library touches lives in
+// global memory, so they are cast to the global address space (global_load / global_store
+// instead of flat accesses).
+#define PREFT_GLOBAL __attribute__((address_space(1)))
+typedef const PREFT_GLOBAL char *gcptr_t;
+typedef PREFT_GLOBAL char *gptr_t;
+__device__ __forceinline__ gcptr_t as_global(const void *p) { return (gcptr_t)p; }
+__device__ __forceinline__ gptr_t as_global(void *p) { return (gptr_t)p; }
+
+// 16-, 8- and 4-byte global accesses
+__device__ __forceinline__ u32x4_t ld16(gcptr_t p) { return *reinterpret_cast<const PREFT_GLOBAL u32x4_t *>(p); }
+__device__ __forceinline__ u32x4_t ld16(gptr_t p) { return *reinterpret_cast<const PREFT_GLOBAL u32x4_t *>(p); }
+__device__ __forceinline__ u32x2_t ld8(gcptr_t p) { return *reinterpret_cast<const PREFT_GLOBAL u32x2_t *>(p); }
+__device__ __forceinline__ uint32_t ld4(gcptr_t p) { return *reinterpret_cast<const PREFT_GLOBAL uint32_t *>(p); }
+__device__ __forceinline__ void st16(gptr_t p, u32x4_t v) { *reinterpret_cast<PREFT_GLOBAL u32x4_t *>(p) = v; }
 
 // Element traits: V = elements per 16-byte vector
 template <typename T> struct Elem;
@@ -93,8 +105,9 @@ template <> struct Elem<float> {
         for (int i = 0; i < 4; ++i) r[i] = __float_as_uint(f[i]);
         return r;
     }
-    __device__ static __forceinline__ float load1(const void *p, int64_t i) { return reinterpret_cast<const float *>(p)[i]; }
-    __device__ static __forceinline__ void store1(void *p, int64_t i, float v) { reinterpret_cast<float *>(p)[i] = v; }
+    __device__ static __forceinline__ float load1(gcptr_t p, int64_t i) { return reinterpret_cast<const PREFT_GLOBAL float *>(p)[i]; }
+    __device__ static __forceinline__ float load1(gptr_t p, int64_t i) { return reinterpret_cast<const PREFT_GLOBAL float *>(p)[i]; }
+    __device__ static __forceinline__ void store1(gptr_t p, int64_t i, float v) { reinterpret_cast<PREFT_GLOBAL float *>(p)[i] = v; }
 };
 struct bf16_tag {};
 template <> struct Elem<bf16_tag> {
@@ -112,13 +125,14 @@ template <> struct Elem<bf16_tag> {
         for (int i = 0; i < 4; ++i) r[i] = pack_bf16(f[2 * i], f[2 * i + 1]);
         return r;
     }
-    __device__ static __forceinline__ float load1(const void *p, int64_t i)
+    __device__ static __forceinline__ float load1(gcptr_t p, int64_t i)
     {
-        return __uint_as_float((uint32_t) reinterpret_cast<const uint16_t *>(p)[i] << 16);
+        return __uint_as_float((uint32_t) reinterpret_cast<const PREFT_GLOBAL uint16_t *>(p)[i] << 16);
     }
-    __device__ static __forceinline__ void store1(void *p, int64_t i, float v)
+    __device__ static __forceinline__ float load1(gptr_t p, int64_t i) { return load1((gcptr_t)p, i); }
+    __device__ static __forceinline__ void store1(gptr_t p, int64_t i, float v)
     {
-        reinterpret_cast<uint16_t *>(p)[i] = (uint16_t)(pack_bf16(v, 0.0f) & 0xffffu);
+        reinterpret_cast<PREFT_GLOBAL uint16_t *>(p)[i] = (uint16_t)(pack_bf16(v, 0.0f) & 0xffffu);
     }
 };
 

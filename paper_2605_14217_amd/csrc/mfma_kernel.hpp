@@ -64,21 +64,20 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_tile_kernel(ApplyArgs p)
 
     const int r = p.rank;
     const int64_t ldx_b = p.ldx * 2, ldy_b = p.ldy * 2;
-    const char *A  = reinterpret_cast<const char *>(p.A_pool[adapter]);
-    const char *Bt = reinterpret_cast<const char *>(p.Bt_pool[adapter]);
+    gcptr_t A  = as_global(p.A_pool[adapter]);
+    gcptr_t Bt = as_global(p.Bt_pool[adapter]);
 
-    // Rows past the end of the tile alias its last row: their loads coalesce with that
-    // row's and their results are never stored.
-    bool row_ok[MB];
-    const char *xp[MB];
-    char *yp[MB];
+    // Row slots past the end of the tile alias its last row (which this wavefront owns): they
+    // load the same bytes, compute the same values and store the same bits, so no access in
+    // the sweeps below depends on the row.
+    gcptr_t xp[MB];
+    gptr_t yp[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         const int t = wave_row0 + mb * 16 + rl;
-        row_ok[mb] = t < n_rows;
         const int64_t row = (int64_t)ch.y + tile_row0 + min(t, n_rows - 1);
-        xp[mb] = reinterpret_cast<const char *>(p.x) + row * ldx_b + g * 16;
-        yp[mb] = reinterpret_cast<char *>(p.y) + row * ldy_b + g * 16;
+        xp[mb] = as_global(p.x) + row * ldx_b + g * 16;
+        yp[mb] = as_global(p.y) + row * ldy_b + g * 16;
     }
 
     // ---------------------------------------------------------------- shrink
@@ -89,7 +88,7 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_tile_kernel(ApplyArgs p)
         for (int mb = 0; mb < MB; ++mb) acc[b][mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
     // Ranks past r alias rank r-1; their z entries are zeroed below.
-    const char *ap[NB];
+    gcptr_t ap[NB];
 #pragma unroll
     for (int b = 0; b < NB; ++b) ap[b] = A + ((int64_t)min(16 * b + rl, r - 1) * p.d_in + g * 8) * 2;
 
@@ -151,7 +150,7 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_tile_kernel(ApplyArgs p)
         const bool rank_ok = rank0 < r;                       // r % 4 == 0: all four or none
         float bias[4] = {0.f, 0.f, 0.f, 0.f};
         if (DIREFT && p.bias_pool && rank_ok) {
-            const void *bp_ = p.bias_pool[adapter];
+            gcptr_t bp_ = as_global(p.bias_pool[adapter]);
 #pragma unroll
             for (int v = 0; v < 4; ++v) bias[v] = Elem<bf16_tag>::load1(bp_, rank0 + v);
         }
@@ -177,7 +176,7 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_tile_kernel(ApplyArgs p)
     // ---------------------------------------------------------------- expand
     // Weight pointer of MFMA e, rank block b: column 8(rl/4) + 4e + rl%4 of the current
     // 32-column step, ranks 16b + 4g .. +3 (padding ranks alias rank 0; their z is zero).
-    const char *bp[2][NB];
+    gcptr_t bp[2][NB];
 #pragma unroll
     for (int e = 0; e < 2; ++e)
 #pragma unroll
@@ -201,7 +200,7 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_tile_kernel(ApplyArgs p)
             for (int e = 0; e < 2; ++e)
 #pragma unroll
                 for (int b = 0; b < NB; ++b)
-                    wv[u][e][b] = *reinterpret_cast<const u32x2_t *>(bp[e][b] + (cs + u) * w_step);
+                    wv[u][e][b] = ld8(bp[e][b] + (cs + u) * w_step);
         }
 #pragma unroll
         for (int u = 0; u < UE; ++u) {
@@ -229,7 +228,7 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_tile_kernel(ApplyArgs p)
             }
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
-                if (row_ok[mb]) st16(yp[mb] + (int64_t)(cs + u) * 64, Elem<bf16_tag>::pack(out[mb]));
+                st16(yp[mb] + (int64_t)(cs + u) * 64, Elem<bf16_tag>::pack(out[mb]));
         }
     }
     for (; cs < c_full; ++cs) {
@@ -244,7 +243,7 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_tile_kernel(ApplyArgs p)
             for (int mb = 0; mb < MB; ++mb) d[mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                const u32x2_t w = *reinterpret_cast<const u32x2_t *>(bp[e][b] + cs * w_step);
+                const u32x2_t w = ld8(bp[e][b] + cs * w_step);
                 const bf16x8_t wop = as_bf16x8(u32x4_t{w[0], w[1], w[0], w[1]});
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
@@ -260,7 +259,7 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_tile_kernel(ApplyArgs p)
         }
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
-            if (row_ok[mb]) st16(yp[mb] + (int64_t)cs * 64, Elem<bf16_tag>::pack(out[mb]));
+            st16(yp[mb] + (int64_t)cs * 64, Elem<bf16_tag>::pack(out[mb]));
     }
     if (p.d_out & 31) {                                       // last, partial step (d_out % 8 == 0)
         const int c0 = c_full * 32;
@@ -281,7 +280,7 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_tile_kernel(ApplyArgs p)
             const int64_t back = col < p.d_out ? 0 : (int64_t)(col - (p.d_out - 1)) * r * 2;
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                const u32x2_t w = *reinterpret_cast<const u32x2_t *>(bp[e][b] + c_full * w_step - back);
+                const u32x2_t w = ld8(bp[e][b] + c_full * w_step - back);
                 const bf16x8_t wop = as_bf16x8(u32x4_t{w[0], w[1], w[0], w[1]});
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
@@ -297,7 +296,7 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_tile_kernel(ApplyArgs p)
         }
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
-            if (row_ok[mb] && col_ok) st16(yp[mb] + (int64_t)c_full * 64, Elem<bf16_tag>::pack(out[mb]));
+            if (col_ok) st16(yp[mb] + (int64_t)c_full * 64, Elem<bf16_tag>::pack(out[mb]));
     }
 }
 

@@ -18,14 +18,14 @@ namespace preft {
 constexpr int ROW_THREADS = 256;
 
 template <typename E, int WB /* bytes per weight load */>
-__device__ __forceinline__ void row_expand(const ApplyArgs &p, const char *Bt, char *yrow, const float *z)
+__device__ __forceinline__ void row_expand(const ApplyArgs &p, gcptr_t Bt, gptr_t yrow, const float *z)
 {
     constexpr int BYTES = Elem<E>::BYTES;
     constexpr int PER = WB / BYTES;                       // weights per load
     const int r = p.rank;
     const int row_bytes = r * BYTES;
     for (int n = threadIdx.x; n < p.d_out; n += ROW_THREADS) {
-        const char *w = Bt + (int64_t)n * row_bytes;
+        gcptr_t w = Bt + (int64_t)n * row_bytes;
         float acc = 0.f;
         for (int o = 0; o < row_bytes; o += WB) {
             const int k = o / BYTES;
@@ -35,7 +35,7 @@ __device__ __forceinline__ void row_expand(const ApplyArgs &p, const char *Bt, c
 #pragma unroll
                 for (int e = 0; e < PER; ++e) acc = fmaf(f[e], z[k + e], acc);
             } else if constexpr (WB == 8) {
-                u32x2_t raw = *reinterpret_cast<const u32x2_t *>(w + o);
+                u32x2_t raw = ld8(w + o);
                 if constexpr (BYTES == 2) {
                     acc = fmaf(bf16_lo(raw[0]), z[k], acc);
                     acc = fmaf(bf16_hi(raw[0]), z[k + 1], acc);
@@ -46,7 +46,7 @@ __device__ __forceinline__ void row_expand(const ApplyArgs &p, const char *Bt, c
                     acc = fmaf(__uint_as_float(raw[1]), z[k + 1], acc);
                 }
             } else if constexpr (WB == 4) {
-                uint32_t raw = *reinterpret_cast<const uint32_t *>(w + o);
+                uint32_t raw = ld4(w + o);
                 if constexpr (BYTES == 2) {
                     acc = fmaf(bf16_lo(raw), z[k], acc);
                     acc = fmaf(bf16_hi(raw), z[k + 1], acc);
@@ -70,15 +70,15 @@ __device__ __forceinline__ void row_apply(const ApplyArgs &p, int adapter, int r
     constexpr int BYTES = Elem<E>::BYTES;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = p.rank;
-    const char *A  = reinterpret_cast<const char *>(p.A_pool[adapter]);
-    const char *Bt = reinterpret_cast<const char *>(p.Bt_pool[adapter]);
-    const char *bias = (DIREFT && p.bias_pool) ? reinterpret_cast<const char *>(p.bias_pool[adapter]) : nullptr;
-    const char *xrow = reinterpret_cast<const char *>(p.x) + (int64_t)row * p.ldx * BYTES;
-    char *yrow = reinterpret_cast<char *>(p.y) + (int64_t)row * p.ldy * BYTES;
+    gcptr_t A  = as_global(p.A_pool[adapter]);
+    gcptr_t Bt = as_global(p.Bt_pool[adapter]);
+    gcptr_t bias = (DIREFT && p.bias_pool) ? as_global(p.bias_pool[adapter]) : nullptr;
+    gcptr_t xrow = as_global(p.x) + (int64_t)row * p.ldx * BYTES;
+    gptr_t yrow = as_global(p.y) + (int64_t)row * p.ldy * BYTES;
 
     const int nvec = p.d_in / V;
     for (int k = wave; k < r; k += ROW_THREADS / 64) {
-        const char *Ak = A + (int64_t)k * p.d_in * BYTES;
+        gcptr_t Ak = A + (int64_t)k * p.d_in * BYTES;
         float acc = 0.f;
         for (int c = lane; c < nvec; c += 64) {
             float xv[V], av[V];

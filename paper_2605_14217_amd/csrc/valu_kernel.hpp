@@ -20,6 +20,14 @@
 
 namespace preft {
 
+// acc + a.lo * b.lo + a.hi * b.hi on packed bf16 pairs, fp32 accumulate (v_dot2c_f32_bf16).
+// The operands are taken by value: a bit cast applied directly to a vector-element lvalue
+// reads element 0 of the vector.
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), acc, false);
+}
+
 template <int RANK, int RB, int WAVES, bool DIREFT>
 __global__ __launch_bounds__(WAVES * 64) void valu_tile_kernel(ApplyArgs p)
 {
@@ -39,20 +47,20 @@ __global__ __launch_bounds__(WAVES * 64) void valu_tile_kernel(ApplyArgs p)
     const int wave_row0 = wave * RB;
     if (wave_row0 >= n_rows) return;
 
-    const char *A  = reinterpret_cast<const char *>(p.A_pool[adapter]);
-    const char *Bt = reinterpret_cast<const char *>(p.Bt_pool[adapter]);
+    gcptr_t A  = as_global(p.A_pool[adapter]);
+    gcptr_t Bt = as_global(p.Bt_pool[adapter]);
     const int64_t ldx_b = p.ldx * 2, ldy_b = p.ldy * 2;
 
-    bool row_ok[RB];
-    const char *xp[RB];
-    char *yp[RB];
+    // Row slots past the end of the tile alias its last row (which this wavefront owns): they
+    // load the same bytes, compute the same values and store the same bits, so no access in
+    // the sweeps below is conditional.
+    gcptr_t xp[RB];
+    gptr_t yp[RB];
 #pragma unroll
     for (int i = 0; i < RB; ++i) {
-        const int t = wave_row0 + i;
-        row_ok[i] = t < n_rows;
-        const int64_t row = (int64_t)ch.y + tile_row0 + min(t, n_rows - 1);   // idle rows alias the last one
-        xp[i] = reinterpret_cast<const char *>(p.x) + row * ldx_b;
-        yp[i] = reinterpret_cast<char *>(p.y) + row * ldy_b;
+        const int64_t row = (int64_t)ch.y + tile_row0 + min(wave_row0 + i, n_rows - 1);
+        xp[i] = as_global(p.x) + row * ldx_b;
+        yp[i] = as_global(p.y) + row * ldy_b;
     }
 
     // ---------------------------------------------------------------- shrink
@@ -70,9 +78,7 @@ __global__ __launch_bounds__(WAVES * 64) void valu_tile_kernel(ApplyArgs p)
             for (int i = 0; i < RB; ++i)
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
-                    z[i][k] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, xv[i][q]),
-                                                              __builtin_bit_cast(bf16x2_t, av[k][q]),
-                                                              z[i][k], false);
+                    z[i][k] = dot2_bf16(xv[i][q], av[k][q], z[i][k]);
     };
     int c = lane;
     for (; c + 64 < nvec_in; c += 128) {                      // two sweeps in flight
@@ -101,7 +107,7 @@ __global__ __launch_bounds__(WAVES * 64) void valu_tile_kernel(ApplyArgs p)
 #pragma unroll
     for (int k = 0; k < RANK; ++k) {
         float bias = 0.f;
-        if (DIREFT && p.bias_pool) bias = Elem<bf16_tag>::load1(p.bias_pool[adapter], k);
+        if (DIREFT && p.bias_pool) bias = Elem<bf16_tag>::load1(as_global(p.bias_pool[adapter]), k);
 #pragma unroll
         for (int i = 0; i < RB; ++i) z[i][k] = (wave_sum(z[i][k]) + bias) * p.scale;
     }
@@ -111,7 +117,7 @@ __global__ __launch_bounds__(WAVES * 64) void valu_tile_kernel(ApplyArgs p)
     for (int c = lane; c < nvec_out; c += 64) {
         // 8 columns x RANK factors, contiguous: RANK 16-byte vectors
         float w[8 * RANK];
-        const char *wp = Bt + (int64_t)c * 8 * RANK * 2;
+        gcptr_t wp = Bt + (int64_t)c * 8 * RANK * 2;
 #pragma unroll
         for (int j = 0; j < RANK; ++j) {
             const u32x4_t raw = ld16(wp + j * 16);
@@ -135,7 +141,7 @@ __global__ __launch_bounds__(WAVES * 64) void valu_tile_kernel(ApplyArgs p)
                 for (int k = 0; k < RANK; ++k) d = fmaf(w[col * RANK + k], z[i][k], d);
                 out[col] += d;
             }
-            if (row_ok[i]) st16(yp[i] + (int64_t)c * 16, Elem<bf16_tag>::pack(out));
+            st16(yp[i] + (int64_t)c * 16, Elem<bf16_tag>::pack(out));
         }
     }
 }

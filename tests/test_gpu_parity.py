@@ -83,7 +83,11 @@ LORA_CASES = [
 ]
 
 
-@pytest.mark.parametrize("variant,rank,d_in,d_out,waves,rowblocks", LORA_CASES)
+_VNAME = {0: "auto", 1: "rowk", 2: "valu", 3: "mfma"}
+
+
+@pytest.mark.parametrize("variant,rank,d_in,d_out,waves,rowblocks", LORA_CASES,
+                         ids=[f"{_VNAME[c[0]]}-r{c[1]}-{c[2]}x{c[3]}-w{c[4]}-mb{c[5]}" for c in LORA_CASES])
 def test_bf16_lora_variants(variant, rank, d_in, d_out, waves, rowblocks):
     from parity_util import run_lora_case
     N = 5
@@ -106,7 +110,8 @@ DIREFT_CASES = [
 ]
 
 
-@pytest.mark.parametrize("variant,rank,d,waves,rowblocks", DIREFT_CASES)
+@pytest.mark.parametrize("variant,rank,d,waves,rowblocks", DIREFT_CASES,
+                         ids=[f"{_VNAME[c[0]]}-r{c[1]}-d{c[2]}-w{c[3]}-mb{c[4]}" for c in DIREFT_CASES])
 def test_bf16_direft_variants(variant, rank, d, waves, rowblocks):
     from parity_util import run_direft_case
     N = 5
