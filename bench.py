@@ -56,6 +56,8 @@ def main():
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--waves", type=int, default=0)
     ap.add_argument("--rowblocks", type=int, default=0)
+    ap.add_argument("--ldpad", type=int, default=0, help="experiment: extra elements of row stride on every buffer")
+    ap.add_argument("--only", default="", help="experiment: comma-separated subset of projections")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -91,20 +93,29 @@ def main():
 
     # ---- buffers and pools --------------------------------------------------------------
     projs = []
+    def act(T_, d_, seed_):
+        t = wl.activations(T_, d_, "bf16", device=dev, seed=seed_)
+        if args.ldpad:
+            buf = torch.empty((T_, d_ + args.ldpad), dtype=t.dtype, device=dev)
+            buf[:, :d_].copy_(t)
+            return buf[:, :d_]
+        return t
+
     for i, (name, (d_in, d_out)) in enumerate(cfg["lora_shapes"].items()):
+        if args.only and name not in args.only.split(","):
+            continue
         pool = wl.lora_pool(N, r, d_in, d_out, "bf16", device=dev, seed=args.seed + 10 + i)
         A = [pool.A[j] for j in range(N)]
         B = [pool.B[j] for j in range(N)]
         projs.append(dict(name=name, d_in=d_in, d_out=d_out, pool=pool,
                           Ap=preft.pointer_table(A), Bp=preft.pointer_table(B),
-                          x=wl.activations(T, d_in, "bf16", device=dev, seed=args.seed + 100 + i),
-                          y=wl.activations(T, d_out, "bf16", device=dev, seed=args.seed + 200 + i)))
+                          x=act(T, d_in, args.seed + 100 + i), y=act(T, d_out, args.seed + 200 + i)))
     dpool = wl.direft_pool(N, r, d_res, "bf16", device=dev, seed=args.seed + 50)
     W1 = [dpool.A[j] for j in range(N)]
     W2t = [dpool.B[j].t().contiguous() for j in range(N)]
     bb = [dpool.b[j] for j in range(N)]
     W1p, W2tp, bp = preft.pointer_table(W1), preft.pointer_table(W2t), preft.pointer_table(bb)
-    h = wl.activations(T, d_res, "bf16", device=dev, seed=args.seed + 300)
+    h = act(T, d_res, args.seed + 300)
     direft_scale = 1.0
 
     def step(mode, tables=(ss, sa, sp), T_=T, events=None):
@@ -183,7 +194,8 @@ def main():
     }
 
     # ---- practical ceiling: a plain device copy ------------------------------------------------
-    src, dst = projs[-1]["x"], torch.empty_like(projs[-1]["x"])
+    src = wl.activations(T, 14336, "bf16", device=dev, seed=1)
+    dst = torch.empty_like(src)
     ms = timed(lambda: dst.copy_(src), 20, 3)
     out["copy_GBps"] = round(2 * src.numel() * 2 / ms / 1e6, 1)
     del dst

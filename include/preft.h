@@ -163,8 +163,11 @@ int preft_schedule_counts(const void *workspace, int32_t *counts, void *stream);
  *                        1 = per-row kernel everywhere
  *                        2 = vector-ALU tile kernel where it applies (bf16, rank <= 8)
  *                        3 = MFMA tile kernel where it applies (bf16, rank % 4 == 0)
- *   PREFT_KNOB_WAVES     wavefronts per tile workgroup: 0 = automatic, else 1, 2 or 4
- *   PREFT_KNOB_ROWBLOCKS MFMA kernel: 16-row blocks per wavefront: 0 = automatic, 1 or 2
+ *   PREFT_KNOB_WAVES     wavefronts per tile workgroup: 0 = automatic, else 1, 2, 4 or 8
+ *                        (a value a kernel does not offer selects its nearest shape; any
+ *                        non-zero value also makes DiReFT stream its tile instead of
+ *                        holding it in registers)
+ *   PREFT_KNOB_ROWBLOCKS MFMA kernel: 16-row blocks per tile: 0 = automatic, 1 or 2
  */
 enum { PREFT_KNOB_VARIANT = 0, PREFT_KNOB_WAVES = 1, PREFT_KNOB_ROWBLOCKS = 2 };
 int preft_set_knob(int knob, int value);

@@ -1,31 +1,50 @@
 // MFMA tile kernel (bf16 storage, fp32 accumulation), rank a multiple of 4 up to 128.
 //
-// One workgroup owns a tile of R = 16 * MB * WAVES consecutive active rows of one segment;
-// each wavefront owns 16 * MB of them for the whole pass, so no data crosses wavefronts:
+// One workgroup of WAVES wavefronts owns a tile of R = 16 * MB consecutive active rows of
+// one segment.  The wavefronts split the *columns* in units of 128 (256 bytes per row):
+// wavefront w takes units w, w + WAVES, ... of both sweeps, so the workgroup walks the
+// same rows side by side and each wavefront has 1/WAVES of the dependent round trips.
 //
+// Memory side.  Every activation access is one instruction over 4 rows x 256 contiguous
+// bytes (lane l': row l'/16, bytes 16 (l'%16) ..), which is what HBM and the texture path
+// want: measured on this chip, 64-byte row pieces stream at ~4.8 TB/s at best, 256-byte
+// pieces at ~5.4 TB/s.  The matrix cores want the opposite order (lane l: row l%16), so a
+// unit is turned through a wavefront-private LDS buffer (4 x ds_write_b128, 4 x
+// ds_read_b128 per 16 rows x 128 columns, padded rows, no bank conflicts, no barrier:
+// the LDS executes one wavefront's operations in order).  The adapter factors come from
+// L2; they are loaded in 64-byte row pieces (4 neighbouring lanes per piece) and turned
+// with ds_bpermute.
+//
+// Compute side.
 //   shrink (Eq. 2: z = A x;  Eq. 3: z = A h + b), per 32 columns of the row:
 //       v_mfma_f32_16x16x32_bf16 with  A-operand = 16 ranks x 32 columns of the adapter's
-//       [r, d_in] factor, B-operand = 32 columns x 16 rows of activations.  Lane (l%16, l/16)
-//       loads 16 contiguous bytes of "its" row for both operands, straight from global
-//       memory into the operand registers.  The accumulator leaves lane (row, g) holding
-//       z[row][16b + 4g .. 16b + 4g + 3] for rank block b.
+//       [r, d_in] factor, B-operand = 32 columns x 16 rows of activations.  The accumulator
+//       leaves lane (row, g) holding the wavefront's partial z[row][16b + 4g .. + 3] for
+//       rank block b.
+//   reduce: the WAVES partial sums meet in LDS; every wavefront adds them in the same
+//       order, so all hold the same z.
 //   expand (Eq. 2: y += s B z;  Eq. 3: h += s B^T z), per 32 columns of the output row:
 //       two MFMAs per rank block with  A-operand = 16 output columns x (16 ranks, twice) of
 //       the [d_out, r] factor, B-operand = z split into a bf16 head and a bf16 remainder
 //       (k index 8g + j: j < 4 the head of rank 16b + 4g + j, j >= 4 the remainder of rank
 //       16b + 4g + j - 4), so the fp32 intermediate is not rounded to bf16.  The 16 columns
 //       of MFMA e are c0 + 8(m/4) + 4e + m%4, which leaves lane (row, g) holding the 8
-//       consecutive outputs y[row][c0 + 8g .. c0 + 8g + 7]: one 16-byte load and one 16-byte
-//       store per lane, the same ownership as the activation operand of the shrink.
+//       consecutive outputs y[row][c0 + 8g .. c0 + 8g + 7] -- the same (row, column)
+//       ownership as the activation operand of the shrink.
 //
-// The rank-r intermediate therefore never leaves the register file (the LDS is not needed:
-// the accumulator layout of the shrink is already the operand layout of the expand).
+// Because of that shared ownership the DiReFT variant (HUNITS > 0) keeps its share of the
+// h tile in registers between the two sweeps: h is read from HBM once and written once.
+//
+// Both sweeps are software-pipelined by hand: the loads of unit u+1 are issued before the
+// MFMAs of unit u.  Widths that are not a multiple of 128 finish with up to four single
+// 32-column steps (64-byte row pieces, ds_bpermute).
 #pragma once
 #include "common.hpp"
 
 namespace preft {
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(u32x4_t v) { return __builtin_bit_cast(bf16x8_t, v); }
+__device__ __forceinline__ u32x4_t as_u32x4(bf16x8_t v) { return __builtin_bit_cast(u32x4_t, v); }
 
 // XCD-aware unit index: workgroup ids are dealt round-robin to the 8 XCDs, so the units
 // are cut into 8 contiguous runs and XCD x walks run x in order.  Consecutive units (same
@@ -39,46 +58,91 @@ __device__ __forceinline__ int xcd_unit(int n_units)
     return v < n_units ? v : -1;
 }
 
-template <int NB, int MB, int WAVES, bool DIREFT>
+constexpr int MFMA_TRS = 17;      // LDS row stride of the turn buffer in 16-byte vectors (256 B + 16 B pad)
+
+template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT>
 __global__ __launch_bounds__(WAVES * 64) void mfma_tile_kernel(ApplyArgs p)
 {
-    constexpr int R = 16 * MB * WAVES;
+    constexpr int R = 16 * MB;
     constexpr int TPC = CHUNK_ROWS / R;
+    constexpr bool PREFETCH_A = (NB * MB <= 2);               // register budget
     static_assert(CHUNK_ROWS % R == 0, "tile height must divide the chunk height");
-    // 32-column steps whose loads are in flight together (about 4 KB of activations a wave)
-    constexpr int US = (NB * MB >= 8) ? 2 : 4;
-    constexpr int UE = (NB * MB >= 8) ? 1 : (NB * MB >= 4 ? 2 : 4);
+    static_assert(HUNITS == 0 || DIREFT, "only the in-place variant keeps its tile in registers");
+    static_assert(WAVES >= 4, "the tail steps are dealt one per wavefront");
+
+    __shared__ float red[WAVES * NB * MB * 4 * 64];           // cross-wavefront reduction of z
+    __shared__ u32x4_t turn[WAVES][MB * 16 * MFMA_TRS];       // wavefront-private turn buffers
 
     const int unit = xcd_unit(p.header[0] * TPC);
     if (unit < 0) return;
     const int4 ch = p.chunks[unit / TPC];
     const int tile_row0 = (unit % TPC) * R;
-    if (tile_row0 >= ch.z) return;
+    if (tile_row0 >= ch.z) return;                            // uniform over the workgroup
     const int adapter = ch.x;
     const int n_rows = min(R, ch.z - tile_row0);              // rows of this tile
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int rl = lane & 15, g = lane >> 4;
-    const int wave_row0 = wave * 16 * MB;
-    if (wave_row0 >= n_rows) return;                          // whole wavefront idle
+    const int rl = lane & 15, g = lane >> 4;                  // MFMA order: row rl, 16-byte group g
+    const int q = lane >> 4, c16 = lane & 15;                 // unit load order: row 4i + q, 16-byte chunk c16
+    const int ld_row = lane >> 2, ld_chunk = lane & 3;        // step load order: row, 16-byte chunk
 
     const int r = p.rank;
     const int64_t ldx_b = p.ldx * 2, ldy_b = p.ldy * 2;
     gcptr_t A  = as_global(p.A_pool[adapter]);
     gcptr_t Bt = as_global(p.Bt_pool[adapter]);
+    u32x4_t *tr = turn[wave];
 
-    // Row slots past the end of the tile alias its last row (which this wavefront owns): they
-    // load the same bytes, compute the same values and store the same bits, so no access in
-    // the sweeps below depends on the row.
-    gcptr_t xp[MB];
-    gptr_t yp[MB];
+    // ---- lane permutations for single 32-column steps (factors, tails) ----------------
+    const int gather_addr  = (4 * (lane & 15) + (lane >> 4)) << 2;    // MFMA lane <- step-load lane
+    const int scatter_addr = ((lane >> 2) + 16 * (lane & 3)) << 2;    // step-store lane <- MFMA lane
+    auto step_to_mfma = [&](u32x4_t raw) -> bf16x8_t {
+        u32x4_t o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = (uint32_t)__builtin_amdgcn_ds_bpermute(gather_addr, (int)raw[i]);
+        return as_bf16x8(o);
+    };
+    auto mfma_to_step = [&](u32x4_t v) -> u32x4_t {
+        u32x4_t o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = (uint32_t)__builtin_amdgcn_ds_bpermute(scatter_addr, (int)v[i]);
+        return o;
+    };
+
+    // ---- row pointers.  Row slots past the end of the tile alias its last row: they load the
+    // same bytes, compute the same values and store the same bits, so no access below depends
+    // on the row.
+    gcptr_t xu[MB][4];            // unit order: instruction i covers rows 4i .. 4i+3
+    gptr_t yu[MB][4];
+    gcptr_t xs[MB];               // step order
+    gptr_t ys[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
-        const int t = wave_row0 + mb * 16 + rl;
-        const int64_t row = (int64_t)ch.y + tile_row0 + min(t, n_rows - 1);
-        xp[mb] = as_global(p.x) + row * ldx_b + g * 16;
-        yp[mb] = as_global(p.y) + row * ldy_b + g * 16;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int64_t row = (int64_t)ch.y + tile_row0 + min(mb * 16 + 4 * i + q, n_rows - 1);
+            xu[mb][i] = as_global(p.x) + row * ldx_b + c16 * 16;
+            yu[mb][i] = as_global(p.y) + row * ldy_b + c16 * 16;
+        }
+        const int64_t row = (int64_t)ch.y + tile_row0 + min(mb * 16 + ld_row, n_rows - 1);
+        xs[mb] = as_global(p.x) + row * ldx_b + ld_chunk * 16;
+        ys[mb] = as_global(p.y) + row * ldy_b + ld_chunk * 16;
     }
+    // factor pointers, step order (ranks past r alias rank r-1; their z entries are zeroed below)
+    gcptr_t ap[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) ap[b] = A + ((int64_t)min(16 * b + ld_row, r - 1) * p.d_in + ld_chunk * 8) * 2;
+
+    // one unit (16 MB rows x 128 columns) from load order to MFMA order, through LDS
+    auto unit_to_mfma = [&](const u32x4_t (&raw)[MB][4], u32x4_t (&op)[MB][4]) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) tr[(mb * 16 + 4 * i + q) * MFMA_TRS + c16] = raw[mb][i];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) op[mb][s] = tr[(mb * 16 + rl) * MFMA_TRS + 4 * s + g];
+    };
 
     // ---------------------------------------------------------------- shrink
     f32x4_t acc[NB][MB];
@@ -87,57 +151,127 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_tile_kernel(ApplyArgs p)
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) acc[b][mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    // Ranks past r alias rank r-1; their z entries are zeroed below.
-    gcptr_t ap[NB];
-#pragma unroll
-    for (int b = 0; b < NB; ++b) ap[b] = A + ((int64_t)min(16 * b + rl, r - 1) * p.d_in + g * 8) * 2;
+    const int k_units = p.d_in >> 7;                          // whole 128-column units
+    const int my_ku = k_units > wave ? (k_units - wave + WAVES - 1) / WAVES : 0;
+    const int k_steps = (p.d_in + 31) >> 5;                   // 32-column steps, the last may be partial
+    const int k_tail_step = k_units * 4 + wave;               // this wavefront's tail step, if < k_steps
 
-    const int k_full = p.d_in >> 5;                           // whole 32-column steps
-    int ks = 0;
-    // US steps per trip: all loads of a trip are issued before its first MFMA
-    for (; ks + US <= k_full; ks += US) {
-        bf16x8_t xv[US][MB], av[US][NB];
-#pragma unroll
-        for (int u = 0; u < US; ++u) {
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) xv[u][mb] = as_bf16x8(ld16(xp[mb] + (int64_t)(ks + u) * 64));
-#pragma unroll
-            for (int b = 0; b < NB; ++b) av[u][b] = as_bf16x8(ld16(ap[b] + (int64_t)(ks + u) * 64));
-        }
-#pragma unroll
-        for (int u = 0; u < US; ++u)
-#pragma unroll
-            for (int b = 0; b < NB; ++b)
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
-                    acc[b][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[u][b], xv[u][mb], acc[b][mb], 0, 0, 0);
-    }
-    for (; ks < k_full; ++ks) {
-        bf16x8_t xv[MB];
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) xv[mb] = as_bf16x8(ld16(xp[mb] + (int64_t)ks * 64));
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const bf16x8_t av = as_bf16x8(ld16(ap[b] + (int64_t)ks * 64));
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-                acc[b][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, xv[mb], acc[b][mb], 0, 0, 0);
-        }
-    }
-    if (p.d_in & 31) {                                        // last, partial step (d_in % 8 == 0)
-        const bool col_ok = (k_full * 32 + g * 8) < p.d_in;
-        const u32x4_t zero = {0u, 0u, 0u, 0u};
-        bf16x8_t xv[MB];
+    u32x4_t hreg[HUNITS > 0 ? HUNITS : 1][MB][4];             // DiReFT: this wavefront's units, MFMA order
+    u32x4_t htail[MB];                                        // DiReFT: its tail step, MFMA order
+
+    auto load_x_unit = [&](u32x4_t (&raw)[MB][4], int u) {
+        const int64_t off = (int64_t)(wave + u * WAVES) * 256;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
-            xv[mb] = as_bf16x8(col_ok ? ld16(xp[mb] + (int64_t)k_full * 64) : zero);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) raw[mb][i] = ld16(xu[mb][i] + off);
+    };
+    auto load_a_unit = [&](u32x4_t (&araw)[4][NB], int u) {
+        const int64_t off = (int64_t)(wave + u * WAVES) * 256;
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int b = 0; b < NB; ++b) araw[s][b] = ld16(ap[b] + off + s * 64);
+    };
+    auto mfma_unit = [&](const u32x4_t (&op)[MB][4], const u32x4_t (&araw)[4][NB]) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const u32x4_t t = araw[s][b];
+                const bf16x8_t ao = step_to_mfma(t);
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    const u32x4_t xo = op[mb][s];
+                    acc[b][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ao, as_bf16x8(xo), acc[b][mb], 0, 0, 0);
+                }
+            }
+    };
+
+    if constexpr (HUNITS > 0) {
+        // DiReFT, tile resident: issue every load of the wavefront's share, then turn and multiply
+        u32x4_t raw[HUNITS][MB][4];
+#pragma unroll
+        for (int u = 0; u < HUNITS; ++u)
+            if (u < my_ku) load_x_unit(raw[u], u);
+#pragma unroll
+        for (int u = 0; u < HUNITS; ++u)
+            if (u < my_ku) {
+                u32x4_t araw[4][NB];
+                load_a_unit(araw, u);
+                unit_to_mfma(raw[u], hreg[u]);
+                mfma_unit(hreg[u], araw);
+            }
+    } else {
+        if (my_ku > 0) {
+            u32x4_t x0[MB][4], x1[MB][4], a0[4][NB], a1[4][NB], op[MB][4];
+            auto stage_load = [&](u32x4_t (&xr)[MB][4], u32x4_t (&ar)[4][NB], int u) {
+                load_x_unit(xr, u);
+                if constexpr (PREFETCH_A) load_a_unit(ar, u);
+            };
+            auto stage_compute = [&](const u32x4_t (&xr)[MB][4], u32x4_t (&ar)[4][NB], int u) {
+                if constexpr (!PREFETCH_A) load_a_unit(ar, u);
+                unit_to_mfma(xr, op);
+                mfma_unit(op, ar);
+            };
+            stage_load(x0, a0, 0);
+            int u = 0;
+            while (u + 2 < my_ku) {
+                stage_load(x1, a1, u + 1);
+                stage_compute(x0, a0, u);
+                stage_load(x0, a0, u + 2);
+                stage_compute(x1, a1, u + 1);
+                u += 2;
+            }
+            if (my_ku - u == 2) {
+                stage_load(x1, a1, u + 1);
+                stage_compute(x0, a0, u);
+                stage_compute(x1, a1, u + 1);
+            } else {
+                stage_compute(x0, a0, u);
+            }
+        }
+    }
+    // tail: at most one 32-column step per wavefront (width not a multiple of 128)
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) htail[mb] = u32x4_t{0u, 0u, 0u, 0u};
+    if (k_tail_step < k_steps) {
+        const bool col_ok = (k_tail_step * 32 + ld_chunk * 8) < p.d_in;   // step-load lane order
+        const u32x4_t zero = {0u, 0u, 0u, 0u};
+        const int64_t off = (int64_t)k_tail_step * 64;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) htail[mb] = as_u32x4(step_to_mfma(col_ok ? ld16(xs[mb] + off) : zero));
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-            const bf16x8_t av = as_bf16x8(col_ok ? ld16(ap[b] + (int64_t)k_full * 64) : zero);
+            const bf16x8_t av = step_to_mfma(col_ok ? ld16(ap[b] + off) : zero);
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
-                acc[b][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, xv[mb], acc[b][mb], 0, 0, 0);
+                acc[b][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(htail[mb]), acc[b][mb], 0, 0, 0);
         }
+    }
+
+    // ---------------------------------------------------------------- reduce over wavefronts
+    {
+        constexpr int PER = NB * MB * 4;
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    red[(wave * PER + (b * MB + mb) * 4 + v) * 64 + lane] = acc[b][mb][v];
+        __syncthreads();          // also: every read of the tile precedes every write (in-place use)
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int w = 0; w < WAVES; ++w) s += red[(w * PER + (b * MB + mb) * 4 + v) * 64 + lane];
+                    acc[b][mb][v] = s;
+                }
     }
 
     // ---------------------------------------------------------------- z -> expand operand
@@ -150,9 +284,9 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_tile_kernel(ApplyArgs p)
         const bool rank_ok = rank0 < r;                       // r % 4 == 0: all four or none
         float bias[4] = {0.f, 0.f, 0.f, 0.f};
         if (DIREFT && p.bias_pool && rank_ok) {
-            gcptr_t bp_ = as_global(p.bias_pool[adapter]);
+            gcptr_t bias_p = as_global(p.bias_pool[adapter]);
 #pragma unroll
-            for (int v = 0; v < 4; ++v) bias[v] = Elem<bf16_tag>::load1(bp_, rank0 + v);
+            for (int v = 0; v < 4; ++v) bias[v] = Elem<bf16_tag>::load1(bias_p, rank0 + v);
         }
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
@@ -187,116 +321,130 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_tile_kernel(ApplyArgs p)
         }
     const int64_t w_step = (int64_t)32 * r * 2;               // bytes per 32 output columns
 
-    const int c_full = p.d_out >> 5;
-    int cs = 0;
-    for (; cs + UE <= c_full; cs += UE) {
-        u32x4_t yv[UE][MB];
-        u32x2_t wv[UE][2][NB];
+    // out = y + delta for one 32-column step and one row block; y and the result in MFMA order
+    auto expand_step = [&](const u32x4_t yv, const u32x2_t (&wv)[2][NB], int mb) -> u32x4_t {
+        float out[8];
 #pragma unroll
-        for (int u = 0; u < UE; ++u) {
+        for (int e = 0; e < 2; ++e) {
+            f32x4_t d = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) yv[u][mb] = ld16(yp[mb] + (int64_t)(cs + u) * 64);
+            for (int b = 0; b < NB; ++b) {
+                const u32x2_t w = wv[e][b];
+                const bf16x8_t wop = as_bf16x8(u32x4_t{w[0], w[1], w[0], w[1]});
+                d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wop, zop[b][mb], d, 0, 0, 0);
+            }
+            const uint32_t y01 = yv[2 * e], y23 = yv[2 * e + 1];
+            out[4 * e + 0] = bf16_lo(y01) + d[0];
+            out[4 * e + 1] = bf16_hi(y01) + d[1];
+            out[4 * e + 2] = bf16_lo(y23) + d[2];
+            out[4 * e + 3] = bf16_hi(y23) + d[3];
+        }
+        return Elem<bf16_tag>::pack(out);
+    };
+    auto load_w_unit = [&](u32x2_t (&wv)[4][2][NB], int u) {
+        const int cs0 = (wave + u * WAVES) * 4;
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
 #pragma unroll
             for (int e = 0; e < 2; ++e)
 #pragma unroll
-                for (int b = 0; b < NB; ++b)
-                    wv[u][e][b] = ld8(bp[e][b] + (cs + u) * w_step);
-        }
+                for (int b = 0; b < NB; ++b) wv[s][e][b] = ld8(bp[e][b] + (cs0 + s) * w_step);
+    };
+    auto load_y_unit = [&](u32x4_t (&raw)[MB][4], int u) {
+        const int64_t off = (int64_t)(wave + u * WAVES) * 256;
 #pragma unroll
-        for (int u = 0; u < UE; ++u) {
-            float out[MB][8];
+        for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                f32x4_t d[MB];
+            for (int i = 0; i < 4; ++i) raw[mb][i] = ld16(yu[mb][i] + off);
+    };
+    // a whole unit: y (MFMA order) -> out, turned back to load order through LDS and stored
+    auto finish_unit = [&](const u32x4_t (&yop)[MB][4], const u32x2_t (&wv)[4][2][NB], int u) {
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) d[mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int b = 0; b < NB; ++b) {
-                    const u32x2_t w = wv[u][e][b];
-                    const bf16x8_t wop = as_bf16x8(u32x4_t{w[0], w[1], w[0], w[1]});
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
-                        d[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wop, zop[b][mb], d[mb], 0, 0, 0);
-                }
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    out[mb][4 * e + 0] = bf16_lo(yv[u][mb][2 * e]) + d[mb][0];
-                    out[mb][4 * e + 1] = bf16_hi(yv[u][mb][2 * e]) + d[mb][1];
-                    out[mb][4 * e + 2] = bf16_lo(yv[u][mb][2 * e + 1]) + d[mb][2];
-                    out[mb][4 * e + 3] = bf16_hi(yv[u][mb][2 * e + 1]) + d[mb][3];
-                }
-            }
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-                st16(yp[mb] + (int64_t)(cs + u) * 64, Elem<bf16_tag>::pack(out[mb]));
-        }
-    }
-    for (; cs < c_full; ++cs) {
-        u32x4_t yv[MB];
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) yv[mb] = ld16(yp[mb] + (int64_t)cs * 64);
-        float out[MB][8];
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            f32x4_t d[MB];
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) d[mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                const u32x2_t w = ld8(bp[e][b] + cs * w_step);
-                const bf16x8_t wop = as_bf16x8(u32x4_t{w[0], w[1], w[0], w[1]});
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
-                    d[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wop, zop[b][mb], d[mb], 0, 0, 0);
-            }
+        for (int s = 0; s < 4; ++s)
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
-                out[mb][4 * e + 0] = bf16_lo(yv[mb][2 * e]) + d[mb][0];
-                out[mb][4 * e + 1] = bf16_hi(yv[mb][2 * e]) + d[mb][1];
-                out[mb][4 * e + 2] = bf16_lo(yv[mb][2 * e + 1]) + d[mb][2];
-                out[mb][4 * e + 3] = bf16_hi(yv[mb][2 * e + 1]) + d[mb][3];
+                const u32x4_t yv = yop[mb][s];
+                tr[(mb * 16 + rl) * MFMA_TRS + 4 * s + g] = expand_step(yv, wv[s], mb);
+            }
+        const int64_t off = (int64_t)(wave + u * WAVES) * 256;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) st16(yu[mb][i] + off, tr[(mb * 16 + 4 * i + q) * MFMA_TRS + c16]);
+    };
+
+    const int c_units = p.d_out >> 7;
+    const int my_cu = c_units > wave ? (c_units - wave + WAVES - 1) / WAVES : 0;
+    const int c_steps = (p.d_out + 31) >> 5;
+    const int c_tail_step = c_units * 4 + wave;
+
+    if constexpr (HUNITS > 0) {
+        // d_in == d_out: the units of the expand are the units held in hreg
+#pragma unroll
+        for (int u = 0; u < HUNITS; ++u)
+            if (u < my_cu) {
+                u32x2_t wv[4][2][NB];
+                load_w_unit(wv, u);
+                finish_unit(hreg[u], wv, u);
+            }
+    } else {
+        if (my_cu > 0) {
+            u32x4_t y0[MB][4], y1[MB][4], yop[MB][4];
+            u32x2_t w0[4][2][NB], w1[4][2][NB];
+            auto stage_load = [&](u32x4_t (&yr)[MB][4], u32x2_t (&wr)[4][2][NB], int u) {
+                load_y_unit(yr, u);
+                if constexpr (PREFETCH_A) load_w_unit(wr, u);
+            };
+            auto stage_compute = [&](const u32x4_t (&yr)[MB][4], u32x2_t (&wr)[4][2][NB], int u) {
+                if constexpr (!PREFETCH_A) load_w_unit(wr, u);
+                unit_to_mfma(yr, yop);
+                finish_unit(yop, wr, u);
+            };
+            stage_load(y0, w0, 0);
+            int u = 0;
+            while (u + 2 < my_cu) {
+                stage_load(y1, w1, u + 1);
+                stage_compute(y0, w0, u);
+                stage_load(y0, w0, u + 2);
+                stage_compute(y1, w1, u + 1);
+                u += 2;
+            }
+            if (my_cu - u == 2) {
+                stage_load(y1, w1, u + 1);
+                stage_compute(y0, w0, u);
+                stage_compute(y1, w1, u + 1);
+            } else {
+                stage_compute(y0, w0, u);
             }
         }
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-            st16(yp[mb] + (int64_t)cs * 64, Elem<bf16_tag>::pack(out[mb]));
     }
-    if (p.d_out & 31) {                                       // last, partial step (d_out % 8 == 0)
-        const int c0 = c_full * 32;
-        const bool col_ok = (c0 + g * 8) < p.d_out;
-        u32x4_t yv[MB];
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-            yv[mb] = col_ok ? ld16(yp[mb] + (int64_t)c_full * 64) : u32x4_t{0u, 0u, 0u, 0u};
-        float out[MB][8];
+    // tail step of this wavefront (DiReFT: it still holds those activations in htail)
+    if (c_tail_step < c_steps) {
+        const int c0 = c_tail_step * 32;
+        const bool col_ok = (c0 + ld_chunk * 8) < p.d_out;              // step-load lane order
+        const int64_t off = (int64_t)c_tail_step * 64;
+        u32x2_t wv[2][NB];
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
-            f32x4_t d[MB];
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) d[mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
             // this lane's weight column may lie past d_out: alias the last column (its
             // products land in outputs that are not stored)
             const int col = c0 + 8 * (rl >> 2) + 4 * e + (rl & 3);
             const int64_t back = col < p.d_out ? 0 : (int64_t)(col - (p.d_out - 1)) * r * 2;
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                const u32x2_t w = ld8(bp[e][b] + c_full * w_step - back);
-                const bf16x8_t wop = as_bf16x8(u32x4_t{w[0], w[1], w[0], w[1]});
+            for (int b = 0; b < NB; ++b) wv[e][b] = ld8(bp[e][b] + c_tail_step * w_step - back);
+        }
+        // every load before the first store: row slots of different blocks may alias one row
+        u32x4_t yv[MB];
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
-                    d[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wop, zop[b][mb], d[mb], 0, 0, 0);
-            }
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                out[mb][4 * e + 0] = bf16_lo(yv[mb][2 * e]) + d[mb][0];
-                out[mb][4 * e + 1] = bf16_hi(yv[mb][2 * e]) + d[mb][1];
-                out[mb][4 * e + 2] = bf16_lo(yv[mb][2 * e + 1]) + d[mb][2];
-                out[mb][4 * e + 3] = bf16_hi(yv[mb][2 * e + 1]) + d[mb][3];
-            }
+        for (int mb = 0; mb < MB; ++mb) {
+            if constexpr (HUNITS > 0) yv[mb] = htail[mb];
+            else yv[mb] = as_u32x4(step_to_mfma(col_ok ? ld16(ys[mb] + off) : u32x4_t{0u, 0u, 0u, 0u}));
         }
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-            if (col_ok) st16(yp[mb] + (int64_t)c_full * 64, Elem<bf16_tag>::pack(out[mb]));
+        for (int mb = 0; mb < MB; ++mb) {
+            const u32x4_t o = mfma_to_step(expand_step(yv[mb], wv, mb));
+            if (col_ok) st16(ys[mb] + off, o);
+        }
     }
 }
 

@@ -73,43 +73,73 @@ inline unsigned tile_grid(int64_t T, int64_t S, int tiles_per_chunk)
     return (unsigned)(((units + 7) / 8) * 8);
 }
 
-template <int NB, int MB, int WAVES, bool DIREFT>
+template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT>
 void launch_mfma(const ApplyArgs &a, int64_t S, hipStream_t stream)
 {
-    constexpr int R = 16 * MB * WAVES;
-    hipLaunchKernelGGL((mfma_tile_kernel<NB, MB, WAVES, DIREFT>), dim3(tile_grid(a.T, S, CHUNK_ROWS / R)),
+    constexpr int R = 16 * MB;
+    hipLaunchKernelGGL((mfma_tile_kernel<NB, MB, WAVES, HUNITS, DIREFT>), dim3(tile_grid(a.T, S, CHUNK_ROWS / R)),
                        dim3(WAVES * 64), 0, stream, a);
 }
 
+// streaming variant (activations read in both sweeps): LoRA, and DiReFT rows too wide to hold
 template <int NB, bool DIREFT>
-void launch_mfma_shape(const ApplyArgs &a, int64_t S, int mb, int waves, hipStream_t stream)
+void launch_mfma_stream(const ApplyArgs &a, int64_t S, int mb, int waves, hipStream_t stream)
 {
-    if (mb == 2) {
-        if (waves == 4)      launch_mfma<NB, 2, 4, DIREFT>(a, S, stream);
-        else if (waves == 2) launch_mfma<NB, 2, 2, DIREFT>(a, S, stream);
-        else                 launch_mfma<NB, 2, 1, DIREFT>(a, S, stream);
-    } else {
-        if (waves == 4)      launch_mfma<NB, 1, 4, DIREFT>(a, S, stream);
-        else if (waves == 2) launch_mfma<NB, 1, 2, DIREFT>(a, S, stream);
-        else                 launch_mfma<NB, 1, 1, DIREFT>(a, S, stream);
+    if constexpr (NB < 8) {                                // LDS / register budget
+        if (waves == 8) {
+            launch_mfma<NB, 1, 8, 0, DIREFT>(a, S, stream);
+            return;
+        }
+        if (mb == 2) {
+            launch_mfma<NB, 2, 4, 0, DIREFT>(a, S, stream);
+            return;
+        }
     }
+    launch_mfma<NB, 1, 4, 0, DIREFT>(a, S, stream);
+}
+
+// DiReFT with the tile held in registers between the sweeps: 8 wavefronts, HUNITS units of 128
+// columns each (register budget: 16 VGPRs per unit)
+template <int NB>
+bool launch_mfma_resident(const ApplyArgs &a, int64_t S, hipStream_t stream)
+{
+    if constexpr (NB > 4) {
+        return false;
+    } else {
+        const int units = ((a.d_in >> 7) + 7) / 8;        // whole units per wavefront
+        if (units <= 4) {
+            launch_mfma<NB, 1, 8, 4, true>(a, S, stream);
+            return true;
+        }
+        if constexpr (NB <= 2) {
+            if (units <= 8) {
+                launch_mfma<NB, 1, 8, 8, true>(a, S, stream);
+                return true;
+            }
+        }
+        return false;
+    }
+}
+
+template <int NB, bool DIREFT>
+void launch_mfma_nb(const ApplyArgs &a, int64_t S, hipStream_t stream)
+{
+    int mb = g_rowblocks ? g_rowblocks : 1;
+    int waves = (g_waves == 8) ? 8 : 4;
+    if constexpr (DIREFT) {
+        if (g_waves == 0 && launch_mfma_resident<NB>(a, S, stream)) return;
+    }
+    launch_mfma_stream<NB, DIREFT>(a, S, mb, waves, stream);
 }
 
 template <bool DIREFT>
 void launch_mfma_rank(const ApplyArgs &a, int64_t S, hipStream_t stream)
 {
     const int nb = (a.rank + 15) / 16;
-    int mb = g_rowblocks ? g_rowblocks : (nb >= 2 ? 2 : 1);
-    int waves = g_waves;
-    if (!waves) {
-        // enough tiles to spread evenly over 256 compute units, else shorter tiles
-        waves = 4;
-        while (waves > 1 && (int64_t)a.T / (16 * mb * waves) < 2048) waves >>= 1;
-    }
-    if (nb <= 1)      launch_mfma_shape<1, DIREFT>(a, S, mb, waves, stream);
-    else if (nb <= 2) launch_mfma_shape<2, DIREFT>(a, S, mb, waves, stream);
-    else if (nb <= 4) launch_mfma_shape<4, DIREFT>(a, S, mb, waves, stream);
-    else              launch_mfma_shape<8, DIREFT>(a, S, mb, waves, stream);
+    if (nb <= 1)      launch_mfma_nb<1, DIREFT>(a, S, stream);
+    else if (nb <= 2) launch_mfma_nb<2, DIREFT>(a, S, stream);
+    else if (nb <= 4) launch_mfma_nb<4, DIREFT>(a, S, stream);
+    else              launch_mfma_nb<8, DIREFT>(a, S, stream);
 }
 
 template <int RANK, bool DIREFT>
@@ -289,7 +319,7 @@ int preft_set_knob(int knob, int value)
     int *slot = nullptr;
     switch (knob) {
     case PREFT_KNOB_VARIANT:   if (value < 0 || value > 3) return PREFT_EINVAL; slot = &g_variant; break;
-    case PREFT_KNOB_WAVES:     if (value != 0 && value != 1 && value != 2 && value != 4) return PREFT_EINVAL; slot = &g_waves; break;
+    case PREFT_KNOB_WAVES:     if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return PREFT_EINVAL; slot = &g_waves; break;
     case PREFT_KNOB_ROWBLOCKS: if (value < 0 || value > 2) return PREFT_EINVAL; slot = &g_rowblocks; break;
     default: return PREFT_EINVAL;
     }

@@ -74,10 +74,11 @@ LORA_CASES = [
     (VARIANT_VALU, 1, 1024, 512, 0, 0), (VARIANT_VALU, 2, 520, 264, 2, 0), (VARIANT_VALU, 3, 512, 1032, 1, 0),
     (VARIANT_VALU, 4, 1024, 256, 0, 0), (VARIANT_VALU, 5, 136, 128, 0, 0), (VARIANT_VALU, 7, 256, 520, 2, 0),
     (VARIANT_VALU, 8, 1024, 1024, 0, 0),
-    (VARIANT_MFMA, 4, 512, 512, 4, 1), (VARIANT_MFMA, 8, 1024, 520, 2, 1), (VARIANT_MFMA, 16, 1024, 1024, 1, 1),
+    (VARIANT_MFMA, 4, 512, 512, 4, 1), (VARIANT_MFMA, 8, 1024, 520, 2, 1), (VARIANT_MFMA, 16, 1024, 1024, 8, 1),
     (VARIANT_MFMA, 16, 520, 264, 4, 2), (VARIANT_MFMA, 32, 512, 1024, 2, 2), (VARIANT_MFMA, 64, 1024, 512, 4, 2),
-    (VARIANT_MFMA, 64, 264, 136, 1, 1), (VARIANT_MFMA, 128, 256, 256, 4, 1), (VARIANT_MFMA, 24, 512, 256, 2, 2),
-    (VARIANT_MFMA, 20, 136, 72, 1, 2), (VARIANT_MFMA, 128, 128, 136, 2, 2),
+    (VARIANT_MFMA, 64, 264, 136, 8, 1), (VARIANT_MFMA, 128, 256, 256, 4, 1), (VARIANT_MFMA, 24, 512, 256, 8, 2),
+    (VARIANT_MFMA, 20, 136, 72, 2, 2), (VARIANT_MFMA, 128, 128, 136, 2, 2), (VARIANT_MFMA, 16, 40, 24, 4, 1),
+    (VARIANT_MFMA, 16, 4096, 1024, 0, 0), (VARIANT_MFMA, 32, 96, 4104, 0, 0),
     (VARIANT_AUTO, 1, 2048, 512, 0, 0), (VARIANT_AUTO, 8, 512, 2048, 0, 0), (VARIANT_AUTO, 16, 2048, 2048, 0, 0),
     (VARIANT_AUTO, 9, 256, 256, 0, 0), (VARIANT_AUTO, 64, 1024, 1024, 0, 0),
 ]
@@ -105,8 +106,12 @@ def test_bf16_lora_variants(variant, rank, d_in, d_out, waves, rowblocks):
 DIREFT_CASES = [
     (VARIANT_ROW, 4, 256, 0, 0), (VARIANT_ROW, 7, 136, 0, 0),
     (VARIANT_VALU, 1, 512, 0, 0), (VARIANT_VALU, 4, 1032, 2, 0), (VARIANT_VALU, 8, 512, 1, 0),
-    (VARIANT_MFMA, 8, 1024, 4, 1), (VARIANT_MFMA, 16, 520, 2, 2), (VARIANT_MFMA, 32, 2048, 1, 2),
+    (VARIANT_MFMA, 8, 1024, 4, 1), (VARIANT_MFMA, 16, 520, 2, 2), (VARIANT_MFMA, 32, 2048, 8, 2),
     (VARIANT_MFMA, 64, 256, 4, 1), (VARIANT_AUTO, 16, 4096, 0, 0), (VARIANT_AUTO, 2, 1024, 0, 0),
+    # tile held in registers (automatic shape): 16 and 32 steps per wavefront, ragged widths
+    (VARIANT_MFMA, 16, 4096, 0, 2), (VARIANT_MFMA, 8, 520, 0, 0), (VARIANT_MFMA, 32, 8192, 0, 0),
+    (VARIANT_MFMA, 64, 4104, 0, 0), (VARIANT_MFMA, 16, 8200, 0, 0), (VARIANT_MFMA, 64, 8192, 0, 0),
+    (VARIANT_MFMA, 128, 1024, 0, 0), (VARIANT_MFMA, 32, 16384, 0, 0),
 ]
 
 
@@ -115,7 +120,7 @@ DIREFT_CASES = [
 def test_bf16_direft_variants(variant, rank, d, waves, rowblocks):
     from parity_util import run_direft_case
     N = 5
-    tab = _mixed_table(rank * 77 + d, N, max_len=200 if d >= 2048 else 300)
+    tab = _mixed_table(rank * 77 + d, N, max_len=(40 if d > 4200 else 200) if d >= 2048 else 300, n_prompts=3 if d > 4200 else 6)
     pool = wl.direft_pool(N, rank, d, "bf16", device="cuda", seed=rank)
     h = wl.activations(tab.T, d, "bf16", device="cuda", seed=13)
     for all_tokens, scale, bias in ((False, 1.0, True), (True, 1.0 / np.sqrt(rank), True), (False, 0.75, False)):
