@@ -124,7 +124,8 @@ bool launch_mfma_resident(const ApplyArgs &a, int64_t S, hipStream_t stream)
 template <int NB, bool DIREFT>
 void launch_mfma_nb(const ApplyArgs &a, int64_t S, hipStream_t stream)
 {
-    int mb = g_rowblocks ? g_rowblocks : 1;
+    // rank >= 32: the factors outweigh a 16-row tile's activations, so two row blocks share them
+    int mb = g_rowblocks ? g_rowblocks : (NB >= 2 ? 2 : 1);
     int waves = (g_waves == 8) ? 8 : 4;
     if constexpr (DIREFT) {
         if (g_waves == 0 && launch_mfma_resident<NB>(a, S, stream)) return;
