@@ -1,0 +1,67 @@
+"""Full-size parity: the named configurations at their real shapes, in the launch configuration
+bench.py times (automatic kernel choice), checked on sampled rows the oracle computes one by one
+(every segment's first/last row and both sides of its prompt boundary, random rows, decode rows)
+plus a bitwise check of *all* inactive rows."""
+import gc
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_14217_amd as preft
+from paper_2605_14217_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _reset(request):
+    print(f"\n[case] {request.node.name}", flush=True)
+    for k in (preft.PREFT_KNOB_VARIANT, preft.PREFT_KNOB_WAVES, preft.PREFT_KNOB_ROWBLOCKS):
+        preft.preft_set_knob(k, 0)
+    yield
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+LORA = [
+    ("llama8b_lora", "q", 16, False), ("llama8b_lora", "q", 16, True), ("llama8b_lora", "down", 8, False),
+    ("llama8b_lora", "k", 1, False), ("llama8b_lora", "gate", 16, False),
+    ("llama70b_lora", "q", 64, False), ("llama70b_lora", "q", 64, True), ("llama70b_lora", "gate", 16, False),
+    ("llama70b_lora", "down", 1, False), ("llama70b_lora", "k", 16, True),
+    ("skewed70b", "res", 32, False), ("skewed70b", "res", 32, True),
+]
+
+
+@pytest.mark.parametrize("config,proj,rank,all_tokens", LORA,
+                         ids=[f"{c}-{p}-r{r}-{'all' if a else 'prefill'}" for c, p, r, a in LORA])
+def test_fullsize_lora(config, proj, rank, all_tokens):
+    from parity_util import run_lora_case
+    cfg = wl.CONFIGS[config]
+    d_in, d_out = cfg["lora_shapes"][proj]
+    tab = wl.make_segments(config, seed=0)
+    pool = wl.lora_pool(cfg["N"], rank, d_in, d_out, "bf16", device="cuda", seed=5)
+    x = wl.activations(tab.T, d_in, "bf16", device="cuda", seed=51)
+    y0 = wl.activations(tab.T, d_out, "bf16", device="cuda", seed=52)
+    rows = wl.sample_rows(tab, 2, max_rows=1200)
+    worst, counts = run_lora_case(tab, pool, x, y0, "bf16", cfg["lora_scale"], all_tokens, rows=rows)
+    print(f"  T={tab.T} S={tab.S} rows checked={len(rows)} worst {worst:.2e} counts {counts}")
+
+
+DIREFT = [("llama8b_direft", 8, False), ("llama8b_direft", 16, True), ("skewed70b", 32, False),
+          ("llama70b_lora", 64, False), ("tiny", 4, False)]
+
+
+@pytest.mark.parametrize("config,rank,all_tokens", DIREFT,
+                         ids=[f"{c}-r{r}-{'all' if a else 'prefill'}" for c, r, a in DIREFT])
+def test_fullsize_direft(config, rank, all_tokens):
+    from parity_util import run_direft_case
+    cfg = wl.CONFIGS[config]
+    d = cfg["direft_d"]
+    dtype = cfg["dtype"]
+    tab = wl.make_segments(config, seed=0)
+    pool = wl.direft_pool(cfg["N"], rank, d, dtype, device="cuda", seed=6)
+    h = wl.activations(tab.T, d, dtype, device="cuda", seed=61)
+    rows = wl.sample_rows(tab, 2, max_rows=1200)
+    worst, counts = run_direft_case(tab, pool, h, dtype, 1.0 / np.sqrt(rank), all_tokens, rows=rows)
+    print(f"  T={tab.T} S={tab.S} rows checked={len(rows)} worst {worst:.2e} counts {counts}")
