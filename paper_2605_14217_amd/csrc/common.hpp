@@ -9,16 +9,22 @@ namespace preft {
 // Schedule (written by schedule_kernel, read by every apply kernel)
 //
 //   header   int32[16]   [0] number of chunks  [1] number of short rows  [2] active rows
+//                        [3] mode  [4] number of short-row groups
 //   chunks   int4[]      {adapter, first row, rows (1..CHUNK_ROWS), segment}
-//   shorts   int2[]      {adapter, row}
+//   shorts   int2[]      {adapter, row}, sorted by adapter when the pool has <= SORT_MAX_N slots
+//   groups   int4[]      {adapter, first entry in shorts, entries (1..GROUP_ROWS), 0}
 //
 // A chunk is a run of at most CHUNK_ROWS consecutive active rows of one segment; a tile
 // kernel of height R (a divisor of CHUNK_ROWS) splits it into CHUNK_ROWS / R tiles.
 // Segments with at most SHORT_ROWS active rows (decode tokens, speculative tokens, the
-// last token of a chunked prompt) are listed row by row for the per-row kernel.
+// last token of a chunked prompt) are listed row by row; rows that share an adapter are
+// gathered into groups of at most GROUP_ROWS so that the per-row kernel reads that
+// adapter's factors once per group.
 // ---------------------------------------------------------------------------------------
 constexpr int CHUNK_ROWS  = 128;
 constexpr int SHORT_ROWS  = 4;
+constexpr int GROUP_ROWS  = 4;      // >= SHORT_ROWS: a short segment always fits one group
+constexpr int SORT_MAX_N  = 4096;   // pools up to this many slots get their short rows sorted by adapter
 constexpr int HEADER_INTS = 16;
 constexpr int PREFT_MAX_RANK_DEV = 128;   // must equal PREFT_MAX_RANK of the public header
 
@@ -26,6 +32,7 @@ struct ScheduleView {
     int32_t *header;
     int4    *chunks;
     int2    *shorts;
+    int4    *groups;        // capacity short_cap (a group holds at least one row)
     int32_t  chunk_cap;
     int32_t  short_cap;
 };
@@ -151,6 +158,7 @@ struct ApplyArgs {
     const int32_t      *header;
     const int4         *chunks;
     const int2         *shorts;
+    const int4         *groups;
 };
 
 }  // namespace preft

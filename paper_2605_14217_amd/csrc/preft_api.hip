@@ -23,7 +23,7 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 size_t workspace_bytes(int64_t T, int64_t S)
 {
     return (size_t)HEADER_INTS * 4 + (size_t)chunk_capacity(T, S) * sizeof(int4) +
-           (size_t)short_capacity(T, S) * sizeof(int2);
+           (size_t)short_capacity(T, S) * (sizeof(int4) + sizeof(int2));
 }
 
 ScheduleView view_of(void *workspace, int64_t T, int64_t S)
@@ -33,8 +33,10 @@ ScheduleView view_of(void *workspace, int64_t T, int64_t S)
     v.header = reinterpret_cast<int32_t *>(base);
     v.chunks = reinterpret_cast<int4 *>(base + HEADER_INTS * 4);
     v.chunk_cap = (int32_t)chunk_capacity(T, S);
-    v.shorts = reinterpret_cast<int2 *>(base + HEADER_INTS * 4 + (size_t)v.chunk_cap * sizeof(int4));
     v.short_cap = (int32_t)short_capacity(T, S);
+    char *after_chunks = base + HEADER_INTS * 4 + (size_t)v.chunk_cap * sizeof(int4);
+    v.groups = reinterpret_cast<int4 *>(after_chunks);                  // 16-byte aligned
+    v.shorts = reinterpret_cast<int2 *>(after_chunks + (size_t)v.short_cap * sizeof(int4));
     return v;
 }
 
@@ -178,11 +180,11 @@ template <typename E, bool DIREFT>
 void launch_rows(const ApplyArgs &a, int64_t S, bool chunks_too, hipStream_t stream)
 {
     if (chunks_too) {
-        constexpr int SPLIT = 8;
-        hipLaunchKernelGGL((row_kernel_chunks<E, DIREFT>), dim3((unsigned)(chunk_capacity(a.T, S) * SPLIT)),
-                           dim3(ROW_THREADS), 0, stream, a, SPLIT);
+        hipLaunchKernelGGL((row_kernel_chunks<E, DIREFT>),
+                           dim3((unsigned)(chunk_capacity(a.T, S) * (CHUNK_ROWS / GROUP_ROWS))),
+                           dim3(ROW_THREADS), 0, stream, a);
     }
-    int64_t g = short_capacity(a.T, S);
+    int64_t g = ((short_capacity(a.T, S) + 7) / 8) * 8;     // a multiple of 8: one share per XCD
     if (g > 4096) g = 4096;
     hipLaunchKernelGGL((row_kernel_short<E, DIREFT>), dim3((unsigned)g), dim3(ROW_THREADS), 0, stream, a);
 }
@@ -276,7 +278,7 @@ int preft_lora_apply(void *y, int64_t ldy, const void *x, int64_t ldx, int32_t T
     ApplyArgs a;
     a.y = y; a.x = x; a.ldy = ldy; a.ldx = ldx; a.T = T; a.d_in = d_in; a.d_out = d_out;
     a.A_pool = A_pool; a.Bt_pool = B_pool; a.bias_pool = nullptr; a.N = N; a.rank = rank; a.scale = scale;
-    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts;
+    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.groups = v.groups;
     return launch_apply<false>(a, S, dtype, st);
 }
 
@@ -302,7 +304,7 @@ int preft_direft_apply(void *h, int64_t ldh, int32_t T, int32_t d, const int32_t
     ApplyArgs a;
     a.y = h; a.x = h; a.ldy = ldh; a.ldx = ldh; a.T = T; a.d_in = d; a.d_out = d;
     a.A_pool = W1_pool; a.Bt_pool = W2t_pool; a.bias_pool = b_pool; a.N = N; a.rank = rank; a.scale = scale;
-    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts;
+    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.groups = v.groups;
     return launch_apply<true>(a, S, dtype, st);
 }
 

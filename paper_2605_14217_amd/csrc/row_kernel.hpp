@@ -1,58 +1,60 @@
-// Per-row ("batched gather matrix-vector") kernel: one workgroup applies one adapter to one row.
+// Per-row ("batched gather matrix-vector") kernel: one workgroup applies one adapter to a group
+// of at most GROUP_ROWS rows that share it.
 //
 // This is the path of the conventional all-position baseline for decode tokens -- every row
 // gathers its own adapter's factors, which is the memory-bound cost the paper's Sec. 3.2
 // attributes to per-request adapters at decode time -- and of any segment with at most
-// SHORT_ROWS active rows.  It is also the generic fallback for element types and ranks the
-// tile kernels do not cover (fp32, ranks that are neither <= 8 nor multiples of 4).
+// SHORT_ROWS active rows.  The scheduler sorts such rows by adapter, so an adapter's factors
+// are streamed once per group of rows rather than once per row.  The same code is the generic
+// fallback for element types and ranks the tile kernels do not cover (fp32; bf16 ranks that
+// are neither <= 8 nor multiples of 4), where a chunk is cut into groups of consecutive rows.
 //
-//   shrink  (Eq. 2: A x;  Eq. 3: A h + b):  wave w owns ranks w, w+4, ...; its 64 lanes sweep
-//           the row with 16-byte loads and finish each rank with one wavefront reduction.
-//   expand  (Eq. 2: y + s B z;  Eq. 3: h + s B^T z):  one output column per thread, the
-//           column's r factors are contiguous ([d_out, r] layout) and z sits in LDS.
+//   shrink  (Eq. 2: A x;  Eq. 3: A h + b):  wavefront w owns ranks w, w+4, ... (two at a time);
+//           its 64 lanes sweep the rows with 16-byte loads, every factor vector is used for all
+//           rows of the group, one wavefront reduction per (row, rank) finishes z (LDS).
+//   expand  (Eq. 2: y + s B z;  Eq. 3: h + s B^T z):  the [d_out, r] factor is read as one
+//           contiguous stream of 16-byte vectors; a vector holds part of one column (r >= 8
+//           elements per vector: the lanes of a column combine with xor-shuffles) or several
+//           whole columns (small r).  Ranks that fit neither pattern take one column per thread.
 #pragma once
 #include "common.hpp"
 
 namespace preft {
 
 constexpr int ROW_THREADS = 256;
+constexpr int ROW_KG = 2;                         // ranks per wavefront pass in the shrink
 
-template <typename E, int WB /* bytes per weight load */>
-__device__ __forceinline__ void row_expand(const ApplyArgs &p, gcptr_t Bt, gptr_t yrow, const float *z)
+template <typename E>
+__device__ __forceinline__ float dot_vec(u32x4_t a, u32x4_t b, float acc)
+{
+    if constexpr (Elem<E>::BYTES == 2) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t ua = a[q], ub = b[q];
+            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, ua), __builtin_bit_cast(bf16x2_t, ub), acc, false);
+        }
+    } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc = fmaf(__uint_as_float(a[q]), __uint_as_float(b[q]), acc);
+    }
+    return acc;
+}
+
+// One column per thread (any rank): WB = bytes per factor load.
+template <typename E, int WB>
+__device__ __forceinline__ void expand_by_column(const ApplyArgs &p, gcptr_t Bt, gptr_t yrow, const float *z)
 {
     constexpr int BYTES = Elem<E>::BYTES;
-    constexpr int PER = WB / BYTES;                       // weights per load
-    const int r = p.rank;
-    const int row_bytes = r * BYTES;
+    const int row_bytes = p.rank * BYTES;
     for (int n = threadIdx.x; n < p.d_out; n += ROW_THREADS) {
         gcptr_t w = Bt + (int64_t)n * row_bytes;
         float acc = 0.f;
         for (int o = 0; o < row_bytes; o += WB) {
             const int k = o / BYTES;
-            if constexpr (WB == 16) {
-                float f[Elem<E>::V];
-                Elem<E>::unpack(ld16(w + o), f);
-#pragma unroll
-                for (int e = 0; e < PER; ++e) acc = fmaf(f[e], z[k + e], acc);
-            } else if constexpr (WB == 8) {
-                u32x2_t raw = ld8(w + o);
-                if constexpr (BYTES == 2) {
-                    acc = fmaf(bf16_lo(raw[0]), z[k], acc);
-                    acc = fmaf(bf16_hi(raw[0]), z[k + 1], acc);
-                    acc = fmaf(bf16_lo(raw[1]), z[k + 2], acc);
-                    acc = fmaf(bf16_hi(raw[1]), z[k + 3], acc);
-                } else {
-                    acc = fmaf(__uint_as_float(raw[0]), z[k], acc);
-                    acc = fmaf(__uint_as_float(raw[1]), z[k + 1], acc);
-                }
-            } else if constexpr (WB == 4) {
-                uint32_t raw = ld4(w + o);
-                if constexpr (BYTES == 2) {
-                    acc = fmaf(bf16_lo(raw), z[k], acc);
-                    acc = fmaf(bf16_hi(raw), z[k + 1], acc);
-                } else {
-                    acc = fmaf(__uint_as_float(raw), z[k], acc);
-                }
+            if constexpr (WB == 4 && BYTES == 2) {
+                const uint32_t raw = ld4(w + o);
+                acc = fmaf(bf16_lo(raw), z[k], acc);
+                acc = fmaf(bf16_hi(raw), z[k + 1], acc);
             } else {
                 acc = fmaf(Elem<E>::load1(w, k), z[k], acc);
             }
@@ -61,69 +63,209 @@ __device__ __forceinline__ void row_expand(const ApplyArgs &p, gcptr_t Bt, gptr_
     }
 }
 
-// Applies adapter `adapter` to row `row`.  z: LDS scratch of PREFT_MAX_RANK floats.
-// Must be called by all ROW_THREADS threads of the workgroup.
-template <typename E, bool DIREFT>
-__device__ __forceinline__ void row_apply(const ApplyArgs &p, int adapter, int row, float *z)
+// Small ranks: a 16-byte vector holds all R factors of V / R whole columns.
+template <typename E, int R>
+__device__ __forceinline__ void expand_whole_columns(const ApplyArgs &p, gcptr_t Bt, gptr_t (&yrow)[GROUP_ROWS], int count,
+                                                     const float *z)
 {
     constexpr int V = Elem<E>::V;
+    constexpr int CPL = V / R;                                  // columns per vector
+    static_assert(V % R == 0, "rank must divide the vector length");
+    const int n_vec = p.d_out / CPL;                            // d_out % V == 0
+    for (int jc = threadIdx.x; jc < n_vec; jc += ROW_THREADS) {
+        float wf[V];
+        Elem<E>::unpack(ld16(Bt + (int64_t)jc * 16), wf);
+        float yv[GROUP_ROWS][CPL];
+#pragma unroll
+        for (int j = 0; j < GROUP_ROWS; ++j)
+#pragma unroll
+            for (int cc = 0; cc < CPL; ++cc) yv[j][cc] = j < count ? Elem<E>::load1(yrow[j], jc * CPL + cc) : 0.f;
+#pragma unroll
+        for (int j = 0; j < GROUP_ROWS; ++j) {
+            if (j < count) {
+                const float *zj = z + j * PREFT_MAX_RANK_DEV;
+#pragma unroll
+                for (int cc = 0; cc < CPL; ++cc) {
+                    float d = 0.f;
+#pragma unroll
+                    for (int k = 0; k < R; ++k) d = fmaf(wf[cc * R + k], zj[k], d);
+                    Elem<E>::store1(yrow[j], jc * CPL + cc, yv[j][cc] + d);
+                }
+            }
+        }
+    }
+}
+
+// Applies adapter `adapter` to rows rows[0..count) (count <= GROUP_ROWS, rows distinct).
+// z: LDS scratch of GROUP_ROWS * PREFT_MAX_RANK floats.  Must be called by the whole workgroup.
+template <typename E, bool DIREFT>
+__device__ __forceinline__ void group_apply(const ApplyArgs &p, int adapter, const int (&rows)[GROUP_ROWS], int count,
+                                            float *z)
+{
+    constexpr int V = Elem<E>::V;                 // elements per 16-byte vector
     constexpr int BYTES = Elem<E>::BYTES;
+    constexpr int G = GROUP_ROWS;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = p.rank;
     gcptr_t A  = as_global(p.A_pool[adapter]);
     gcptr_t Bt = as_global(p.Bt_pool[adapter]);
     gcptr_t bias = (DIREFT && p.bias_pool) ? as_global(p.bias_pool[adapter]) : nullptr;
-    gcptr_t xrow = as_global(p.x) + (int64_t)row * p.ldx * BYTES;
-    gptr_t yrow = as_global(p.y) + (int64_t)row * p.ldy * BYTES;
-
-    const int nvec = p.d_in / V;
-    for (int k = wave; k < r; k += ROW_THREADS / 64) {
-        gcptr_t Ak = A + (int64_t)k * p.d_in * BYTES;
-        float acc = 0.f;
-        for (int c = lane; c < nvec; c += 64) {
-            float xv[V], av[V];
-            Elem<E>::unpack(ld16(xrow + (int64_t)c * 16), xv);
-            Elem<E>::unpack(ld16(Ak + (int64_t)c * 16), av);
+    gcptr_t xrow[G];
+    gptr_t yrow[G];
 #pragma unroll
-            for (int i = 0; i < V; ++i) acc = fmaf(xv[i], av[i], acc);
+    for (int j = 0; j < G; ++j) {
+        const int row = j < count ? rows[j] : rows[0];
+        xrow[j] = as_global(p.x) + (int64_t)row * p.ldx * BYTES;
+        yrow[j] = as_global(p.y) + (int64_t)row * p.ldy * BYTES;
+    }
+
+    // ---------------------------------------------------------------- shrink
+    const int nvec = p.d_in / V;
+    const int64_t a_row = (int64_t)p.d_in * BYTES;
+    for (int k0 = wave * ROW_KG; k0 < r; k0 += (ROW_THREADS / 64) * ROW_KG) {
+        float acc[G][ROW_KG];
+#pragma unroll
+        for (int j = 0; j < G; ++j)
+#pragma unroll
+            for (int kk = 0; kk < ROW_KG; ++kk) acc[j][kk] = 0.f;
+        const bool second = (k0 + 1) < r;                       // uniform over the wavefront
+        gcptr_t A0 = A + (int64_t)k0 * a_row;
+        gcptr_t A1 = A + (int64_t)(second ? k0 + 1 : k0) * a_row;
+        constexpr int UC = 4;                                   // vectors in flight per lane and stream
+        const u32x4_t zero = {0u, 0u, 0u, 0u};
+        for (int c0 = lane; c0 < nvec; c0 += 64 * UC) {
+            u32x4_t a0[UC], a1[UC], xv[UC][G];
+#pragma unroll
+            for (int u = 0; u < UC; ++u) {
+                const int c = c0 + 64 * u;
+                const bool ok = c < nvec;
+                a0[u] = ok ? ld16(A0 + (int64_t)c * 16) : zero;
+                a1[u] = ok ? ld16(A1 + (int64_t)c * 16) : zero;
+#pragma unroll
+                for (int j = 0; j < G; ++j) xv[u][j] = (ok && j < count) ? ld16(xrow[j] + (int64_t)c * 16) : zero;
+            }
+#pragma unroll
+            for (int u = 0; u < UC; ++u)
+#pragma unroll
+                for (int j = 0; j < G; ++j) {
+                    acc[j][0] = dot_vec<E>(xv[u][j], a0[u], acc[j][0]);
+                    acc[j][1] = dot_vec<E>(xv[u][j], a1[u], acc[j][1]);
+                }
         }
-        acc = wave_sum(acc);
-        if (lane == 0) {
-            if (bias) acc += Elem<E>::load1(bias, k);
-            z[k] = acc * p.scale;
+#pragma unroll
+        for (int j = 0; j < G; ++j)
+#pragma unroll
+            for (int kk = 0; kk < ROW_KG; ++kk) {
+                const float s = wave_sum(acc[j][kk]);
+                if (lane == 0 && k0 + kk < r) {
+                    const float b = bias ? Elem<E>::load1(bias, k0 + kk) : 0.f;
+                    z[j * PREFT_MAX_RANK_DEV + k0 + kk] = (s + b) * p.scale;
+                }
+            }
+    }
+    __syncthreads();          // z complete; for DiReFT also: every read of the rows precedes every write
+
+    // ---------------------------------------------------------------- expand
+    const int lpc = r / V;                                      // lanes per column when r % V == 0
+    const bool by_lanes = (r % V) == 0 && (lpc & (lpc - 1)) == 0 && lpc <= 64;
+    const bool by_cols = r < V && (V % r) == 0;
+    if (by_lanes) {
+        // vector jc holds elements k0 .. k0+V-1 of column jc / lpc
+        const int n_vec = p.d_out * lpc;
+        const int lpc_shift = __ffs(lpc) - 1;
+        constexpr int UE = 4;
+        const bool leader = (threadIdx.x & (lpc - 1)) == 0;
+        // a thread meets the same V ranks in every vector it takes (the stride is a multiple of lpc)
+        float zr[G][V];
+        {
+            const int k0 = (threadIdx.x & (lpc - 1)) * V;
+#pragma unroll
+            for (int j = 0; j < G; ++j)
+#pragma unroll
+                for (int i = 0; i < V; ++i) zr[j][i] = z[j * PREFT_MAX_RANK_DEV + k0 + i];
+        }
+        for (int jc0 = threadIdx.x; jc0 < n_vec; jc0 += ROW_THREADS * UE) {
+            u32x4_t wraw[UE];
+            float yv[UE][G];
+#pragma unroll
+            for (int u = 0; u < UE; ++u) {
+                const int jc = jc0 + ROW_THREADS * u;
+                const bool ok = jc < n_vec;                     // uniform over the lanes of a column
+                wraw[u] = ok ? ld16(Bt + (int64_t)jc * 16) : u32x4_t{0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int j = 0; j < G; ++j)
+                    yv[u][j] = (ok && leader && j < count) ? Elem<E>::load1(yrow[j], jc >> lpc_shift) : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < UE; ++u) {
+                const int jc = jc0 + ROW_THREADS * u;
+                const bool ok = jc < n_vec;
+                float wf[V];
+                Elem<E>::unpack(wraw[u], wf);
+#pragma unroll
+                for (int j = 0; j < G; ++j) {
+                    float part = 0.f;
+#pragma unroll
+                    for (int i = 0; i < V; ++i) part = fmaf(wf[i], zr[j][i], part);
+                    for (int o = 1; o < lpc; o <<= 1) part += __shfl_xor(part, o, 64);
+                    if (ok && leader && j < count) Elem<E>::store1(yrow[j], jc >> lpc_shift, yv[u][j] + part);
+                }
+            }
+        }
+    } else if (by_cols) {
+        switch (r) {
+        case 1: expand_whole_columns<E, 1>(p, Bt, yrow, count, z); break;
+        case 2: expand_whole_columns<E, 2>(p, Bt, yrow, count, z); break;
+        default: if constexpr (V == 8) expand_whole_columns<E, 4>(p, Bt, yrow, count, z); break;
+        }
+    } else {
+        for (int j = 0; j < count; ++j) {
+            if constexpr (BYTES == 2) {
+                if ((r & 1) == 0) expand_by_column<E, 4>(p, Bt, yrow[j], z + j * PREFT_MAX_RANK_DEV);
+                else              expand_by_column<E, 2>(p, Bt, yrow[j], z + j * PREFT_MAX_RANK_DEV);
+            } else {
+                expand_by_column<E, 4>(p, Bt, yrow[j], z + j * PREFT_MAX_RANK_DEV);
+            }
         }
     }
-    __syncthreads();          // z complete; for DiReFT also: every read of the row precedes every write
-
-    const int row_bytes = r * BYTES;
-    if ((row_bytes & 15) == 0)      row_expand<E, 16>(p, Bt, yrow, z);
-    else if ((row_bytes & 7) == 0)  row_expand<E, 8>(p, Bt, yrow, z);
-    else if ((row_bytes & 3) == 0)  row_expand<E, 4>(p, Bt, yrow, z);
-    else                            row_expand<E, BYTES>(p, Bt, yrow, z);
-    __syncthreads();          // z is reused by the next row
+    __syncthreads();          // z is reused by the next group
 }
 
-// Short rows: grid-stride over the schedule's row list.
+// Short rows: grid-stride over the schedule's groups (rows of one adapter, gathered by the scheduler).
 template <typename E, bool DIREFT>
 __global__ __launch_bounds__(ROW_THREADS) void row_kernel_short(ApplyArgs p)
 {
-    __shared__ float z[PREFT_MAX_RANK_DEV];
-    const int n = p.header[1];
-    for (int e = blockIdx.x; e < n; e += gridDim.x) {
-        const int2 s = p.shorts[e];
-        row_apply<E, DIREFT>(p, s.x, s.y, z);
+    __shared__ float z[GROUP_ROWS * PREFT_MAX_RANK_DEV];
+    // groups are sorted by adapter: deal contiguous runs to the 8 XCDs (workgroup ids go round-robin
+    // over them) so that the groups of one adapter meet in one L2
+    const int n = p.header[4];
+    const int per_xcd = (n + 7) >> 3;
+    const int first = (blockIdx.x & 7) * per_xcd, last = min(first + per_xcd, n);
+    for (int e = first + (blockIdx.x >> 3); e < last; e += gridDim.x >> 3) {
+        const int4 grp = p.groups[e];
+        int rows[GROUP_ROWS];
+#pragma unroll
+        for (int j = 0; j < GROUP_ROWS; ++j) rows[j] = p.shorts[grp.y + min(j, grp.z - 1)].y;
+        group_apply<E, DIREFT>(p, grp.x, rows, grp.z, z);
     }
 }
 
-// Generic fallback for chunks: `split` workgroups share one chunk and take its rows in turn.
+// Generic fallback for chunks: one workgroup per GROUP_ROWS consecutive rows of a chunk.
 template <typename E, bool DIREFT>
-__global__ __launch_bounds__(ROW_THREADS) void row_kernel_chunks(ApplyArgs p, int split)
+__global__ __launch_bounds__(ROW_THREADS) void row_kernel_chunks(ApplyArgs p)
 {
-    __shared__ float z[PREFT_MAX_RANK_DEV];
-    const int c = blockIdx.x / split;
+    __shared__ float z[GROUP_ROWS * PREFT_MAX_RANK_DEV];
+    constexpr int PER_CHUNK = CHUNK_ROWS / GROUP_ROWS;
+    const int c = blockIdx.x / PER_CHUNK;
     if (c >= p.header[0]) return;
     const int4 ch = p.chunks[c];
-    for (int i = blockIdx.x % split; i < ch.z; i += split) row_apply<E, DIREFT>(p, ch.x, ch.y + i, z);
+    const int first = (blockIdx.x % PER_CHUNK) * GROUP_ROWS;
+    if (first >= ch.z) return;
+    const int count = min(GROUP_ROWS, ch.z - first);
+    int rows[GROUP_ROWS];
+#pragma unroll
+    for (int j = 0; j < GROUP_ROWS; ++j) rows[j] = ch.y + first + min(j, count - 1);
+    group_apply<E, DIREFT>(p, ch.x, rows, count, z);
 }
 
 }  // namespace preft

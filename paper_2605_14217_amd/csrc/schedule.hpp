@@ -55,50 +55,106 @@ __device__ __forceinline__ int32_t block_exclusive_scan(int32_t v, int32_t *lds 
 }
 
 // One workgroup.  Thread i owns the contiguous slice of segments [i*per, (i+1)*per), so the
-// emitted lists keep segment order (consecutive chunks of one segment share an adapter, which
-// the tile kernels exploit for cache locality).
+// chunk list keeps segment order (consecutive chunks of one segment share an adapter, which
+// the tile kernels exploit for cache locality).  Short rows are counting-sorted by adapter
+// (LDS histogram) and cut into groups of at most GROUP_ROWS rows of one adapter.
 __global__ __launch_bounds__(SCHED_THREADS) void schedule_kernel(
     const int32_t *__restrict__ seg_start, const int32_t *__restrict__ seg_adapter,
     const int32_t *__restrict__ seg_prefill_len, int32_t S, int32_t T, int32_t N, int all_tokens,
     ScheduleView out)
 {
     __shared__ int32_t lds[32];
+    __shared__ int32_t bin_start[SORT_MAX_N + 1];   // first short-row entry of each adapter
+    __shared__ int32_t bin_cursor[SORT_MAX_N];      // running insertion point while scattering
     const int tid = threadIdx.x, lane = tid & 63;
+    const bool all = all_tokens != 0;
+    const bool sorted = N <= SORT_MAX_N;
     const int32_t per = (S + SCHED_THREADS - 1) / SCHED_THREADS;
-    const int32_t s0 = min((int64_t)tid * per, (int64_t)S);
-    const int32_t s1 = min((int64_t)s0 + per, (int64_t)S);
+    const int32_t s0 = (int32_t)min((int64_t)tid * per, (int64_t)S);
+    const int32_t s1 = (int32_t)min((int64_t)s0 + per, (int64_t)S);
 
-    int32_t my_chunks = 0, my_short = 0, my_act = 0;
+    if (sorted)
+        for (int32_t a = tid; a <= N; a += SCHED_THREADS) bin_start[a] = 0;
+    __syncthreads();
+
+    // ---- pass 1: counts
+    int32_t my_chunks = 0, my_short = 0, my_short_segs = 0, my_act = 0;
     for (int32_t s = s0; s < s1; ++s) {
-        SegInfo g = seg_info(seg_start, seg_adapter, seg_prefill_len, s, T, N, all_tokens != 0);
+        SegInfo g = seg_info(seg_start, seg_adapter, seg_prefill_len, s, T, N, all);
         my_act += g.n_act;
         if (g.n_act == 0) continue;
-        if (g.n_act <= SHORT_ROWS) my_short += g.n_act;
-        else my_chunks += (g.n_act + CHUNK_ROWS - 1) / CHUNK_ROWS;
+        if (g.n_act <= SHORT_ROWS) {
+            my_short += g.n_act;
+            my_short_segs += 1;
+            if (sorted) atomicAdd(&bin_start[g.adapter], g.n_act);
+        } else {
+            my_chunks += (g.n_act + CHUNK_ROWS - 1) / CHUNK_ROWS;
+        }
     }
-    int32_t tot_chunks, tot_short, tot_act;
+    int32_t tot_chunks, tot_short, tot_short_segs, tot_act;
     int32_t chunk_off = block_exclusive_scan(my_chunks, lds, &tot_chunks);
     int32_t short_off = block_exclusive_scan(my_short, lds, &tot_short);
+    int32_t seg_off   = block_exclusive_scan(my_short_segs, lds, &tot_short_segs);
     (void)block_exclusive_scan(my_act, lds, &tot_act);
+
+    // ---- sorted case: histogram -> first entry per adapter, group counts -> first group per adapter
+    const int32_t bins_per = (N + SCHED_THREADS) / SCHED_THREADS;      // covers bins 0..N-1
+    const int32_t b0 = min(tid * bins_per, N), b1 = min(b0 + bins_per, N);
+    int32_t tot_groups = tot_short_segs;
+    int32_t my_group_off = 0;
+    if (sorted) {
+        // few short rows: smaller groups, so that a decode-only step still fills the chip
+        const int32_t grows = max(1, min(GROUP_ROWS, tot_short / 512));
+        int32_t rows_here = 0, groups_here = 0;
+        for (int32_t a = b0; a < b1; ++a) {
+            const int32_t c = bin_start[a];
+            rows_here += c;
+            groups_here += (c + grows - 1) / grows;
+        }
+        int32_t dummy;
+        int32_t row_base = block_exclusive_scan(rows_here, lds, &dummy);
+        my_group_off = block_exclusive_scan(groups_here, lds, &tot_groups);
+        // the scans end with a barrier-protected read of lds, the histogram is final here
+        int32_t grp = my_group_off;
+        for (int32_t a = b0; a < b1; ++a) {
+            const int32_t c = bin_start[a];
+            bin_start[a] = row_base;
+            bin_cursor[a] = row_base;
+            for (int32_t i = 0; i * grows < c; ++i, ++grp)
+                if (grp < out.short_cap)
+                    out.groups[grp] = make_int4(a, row_base + i * grows, min(grows, c - i * grows), 0);
+            row_base += c;
+        }
+        __syncthreads();
+    }
 
     if (tid == 0) {
         out.header[0] = min(tot_chunks, out.chunk_cap);
         out.header[1] = min(tot_short, out.short_cap);
         out.header[2] = tot_act;
         out.header[3] = all_tokens;
+        out.header[4] = min(tot_groups, out.short_cap);
     }
 
-    // Emission.  All lanes of a wave run the same number of iterations; a segment with many
-    // chunks is written by the whole wave.
+    // ---- pass 2: emission.  All lanes of a wave run the same number of iterations; a segment
+    // with many chunks is written by the whole wave.
     for (int32_t i = 0; i < per; ++i) {
         const int32_t s = s0 + i;
         SegInfo g = {-1, 0, 0};
-        if (s < s1) g = seg_info(seg_start, seg_adapter, seg_prefill_len, s, T, N, all_tokens != 0);
+        if (s < s1) g = seg_info(seg_start, seg_adapter, seg_prefill_len, s, T, N, all);
         int32_t n_ch = 0;
         if (g.n_act > 0 && g.n_act <= SHORT_ROWS) {
+            int32_t pos;
+            if (sorted) {
+                pos = atomicAdd(&bin_cursor[g.adapter], g.n_act);
+            } else {
+                pos = short_off;
+                if (seg_off < out.short_cap) out.groups[seg_off] = make_int4(g.adapter, pos, g.n_act, 0);
+                short_off += g.n_act;
+                seg_off += 1;
+            }
             for (int32_t j = 0; j < g.n_act; ++j)
-                if (short_off + j < out.short_cap) out.shorts[short_off + j] = make_int2(g.adapter, g.row0 + j);
-            short_off += g.n_act;
+                if (pos + j < out.short_cap) out.shorts[pos + j] = make_int2(g.adapter, g.row0 + j);
         } else if (g.n_act > SHORT_ROWS) {
             n_ch = (g.n_act + CHUNK_ROWS - 1) / CHUNK_ROWS;
         }

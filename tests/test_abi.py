@@ -67,7 +67,7 @@ def test_workspace_is_large_enough_for_any_table(lib):
         long_ = lens[lens > 4]
         chunks = int(np.sum((long_ + 127) // 128))
         shorts = int(np.sum(lens[lens <= 4]))
-        need = 64 + 16 * chunks + 8 * shorts
+        need = 64 + 16 * chunks + (8 + 16) * shorts
         assert preft.preft_workspace_bytes(tab.T, tab.S) >= need
 
 
