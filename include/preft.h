@@ -162,7 +162,10 @@ int preft_schedule_counts(const void *workspace, int32_t *counts, void *stream);
  *   PREFT_KNOB_VARIANT   0 = automatic choice (default)
  *                        1 = per-row kernel everywhere
  *                        2 = vector-ALU tile kernel where it applies (bf16, rank <= 8)
- *                        3 = MFMA tile kernel where it applies (bf16, rank % 4 == 0)
+ *                        3 = MFMA tile kernel, column-split shape (bf16, rank % 4 == 0)
+ *                        4 = MFMA tile kernel, row-split shape with the factors shared through
+ *                            LDS where it applies (rank > 16, widths multiples of 128),
+ *                            and no register-resident DiReFT
  *   PREFT_KNOB_WAVES     wavefronts per tile workgroup: 0 = automatic, else 1, 2, 4 or 8
  *                        (a value a kernel does not offer selects its nearest shape; any
  *                        non-zero value also makes DiReFT stream its tile instead of

@@ -60,8 +60,15 @@ __device__ __forceinline__ int xcd_unit(int n_units)
 
 constexpr int MFMA_TRS = 17;      // LDS row stride of the turn buffer in 16-byte vectors (256 B + 16 B pad)
 
+// Wavefronts per SIMD the register allocation must leave room for: the register-resident DiReFT
+// shapes need two workgroups per compute unit so that one streams in while the other streams out.
+constexpr int mfma_min_waves(int NB, int MB, int WAVES, int HUNITS)
+{
+    return (HUNITS > 0 && WAVES == 8 && NB * MB == 1 && HUNITS <= 4) ? 4 : 1;
+}
+
 template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT>
-__global__ __launch_bounds__(WAVES * 64) void mfma_tile_kernel(ApplyArgs p)
+__global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) void mfma_tile_kernel(ApplyArgs p)
 {
     constexpr int R = 16 * MB;
     constexpr int TPC = CHUNK_ROWS / R;

@@ -4,6 +4,7 @@
 
 #include "common.hpp"
 #include "mfma_kernel.hpp"
+#include "mfma_wide_kernel.hpp"
 #include "row_kernel.hpp"
 #include "schedule.hpp"
 #include "valu_kernel.hpp"
@@ -123,15 +124,38 @@ bool launch_mfma_resident(const ApplyArgs &a, int64_t S, hipStream_t stream)
     }
 }
 
+// row-split kernel with the factors shared through LDS (rank >= 32, widths multiples of 128)
+template <int NB, bool DIREFT>
+bool launch_mfma_wide(const ApplyArgs &a, int64_t S, int mb, int waves, hipStream_t stream)
+{
+    if constexpr (NB < 2) {
+        return false;
+    } else {
+        if ((a.d_in & 127) || (a.d_out & 127)) return false;
+        if (mb == 1) {
+            if (waves == 8) hipLaunchKernelGGL((mfma_wide_kernel<NB, 1, 8, DIREFT>), dim3(tile_grid(a.T, S, 1)), dim3(512), 0, stream, a);
+            else            hipLaunchKernelGGL((mfma_wide_kernel<NB, 1, 4, DIREFT>), dim3(tile_grid(a.T, S, 2)), dim3(256), 0, stream, a);
+        } else {
+            if constexpr (NB <= 4)
+                hipLaunchKernelGGL((mfma_wide_kernel<NB, 2, 4, DIREFT>), dim3(tile_grid(a.T, S, 1)), dim3(256), 0, stream, a);
+            else
+                hipLaunchKernelGGL((mfma_wide_kernel<NB, 1, 8, DIREFT>), dim3(tile_grid(a.T, S, 1)), dim3(512), 0, stream, a);
+        }
+        return true;
+    }
+}
+
 template <int NB, bool DIREFT>
 void launch_mfma_nb(const ApplyArgs &a, int64_t S, hipStream_t stream)
 {
-    // rank >= 32: the factors outweigh a 16-row tile's activations, so two row blocks share them
-    int mb = g_rowblocks ? g_rowblocks : (NB >= 2 ? 2 : 1);
-    int waves = (g_waves == 8) ? 8 : 4;
+    // rank >= 32: the factors outweigh a 16-row tile's activations, so more rows share them:
+    // the row-split kernel with 8 wavefronts x 16 rows (a whole 128-row chunk per workgroup)
+    int mb = g_rowblocks ? g_rowblocks : 1;
+    int waves = g_waves ? (g_waves == 8 ? 8 : 4) : (NB >= 2 ? 8 : 4);
     if constexpr (DIREFT) {
-        if (g_waves == 0 && launch_mfma_resident<NB>(a, S, stream)) return;
+        if (g_waves == 0 && g_variant != 4 && launch_mfma_resident<NB>(a, S, stream)) return;
     }
+    if (g_variant != 3 && launch_mfma_wide<NB, DIREFT>(a, S, mb, waves, stream)) return;
     launch_mfma_stream<NB, DIREFT>(a, S, mb, waves, stream);
 }
 
@@ -196,7 +220,7 @@ Path choose_path(int dtype, int rank)
     if (dtype != PREFT_BF16 || g_variant == 1) return Path::Rows;
     const bool valu_ok = rank <= 8, mfma_ok = (rank % 4) == 0;
     if (g_variant == 2 && valu_ok) return Path::Valu;
-    if (g_variant == 3 && mfma_ok) return Path::Mfma;
+    if ((g_variant == 3 || g_variant == 4) && mfma_ok) return Path::Mfma;
     if (mfma_ok) return Path::Mfma;
     if (valu_ok) return Path::Valu;
     return Path::Rows;
@@ -321,7 +345,7 @@ int preft_set_knob(int knob, int value)
 {
     int *slot = nullptr;
     switch (knob) {
-    case PREFT_KNOB_VARIANT:   if (value < 0 || value > 3) return PREFT_EINVAL; slot = &g_variant; break;
+    case PREFT_KNOB_VARIANT:   if (value < 0 || value > 4) return PREFT_EINVAL; slot = &g_variant; break;
     case PREFT_KNOB_WAVES:     if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return PREFT_EINVAL; slot = &g_waves; break;
     case PREFT_KNOB_ROWBLOCKS: if (value < 0 || value > 2) return PREFT_EINVAL; slot = &g_rowblocks; break;
     default: return PREFT_EINVAL;

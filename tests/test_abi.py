@@ -50,6 +50,7 @@ def test_version_and_error_strings(lib):
 def test_knob_validation(lib):
     assert lib.preft_set_knob(99, 0) == -1
     assert lib.preft_set_knob(preft.PREFT_KNOB_VARIANT, 7) == -1
+    assert lib.preft_set_knob(preft.PREFT_KNOB_VARIANT, 5) == -1
     assert lib.preft_set_knob(preft.PREFT_KNOB_WAVES, 3) == -1
     prev = preft.preft_set_knob(preft.PREFT_KNOB_VARIANT, 1)
     assert preft.preft_set_knob(preft.PREFT_KNOB_VARIANT, prev) == 1

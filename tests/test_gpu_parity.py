@@ -12,7 +12,7 @@ from paper_2605_14217_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
-VARIANT_AUTO, VARIANT_ROW, VARIANT_VALU, VARIANT_MFMA = 0, 1, 2, 3
+VARIANT_AUTO, VARIANT_ROW, VARIANT_VALU, VARIANT_MFMA, VARIANT_WIDE = 0, 1, 2, 3, 4
 
 
 @pytest.fixture(autouse=True)
@@ -79,12 +79,17 @@ LORA_CASES = [
     (VARIANT_MFMA, 64, 264, 136, 8, 1), (VARIANT_MFMA, 128, 256, 256, 4, 1), (VARIANT_MFMA, 24, 512, 256, 8, 2),
     (VARIANT_MFMA, 20, 136, 72, 2, 2), (VARIANT_MFMA, 128, 128, 136, 2, 2), (VARIANT_MFMA, 16, 40, 24, 4, 1),
     (VARIANT_MFMA, 16, 4096, 1024, 0, 0), (VARIANT_MFMA, 32, 96, 4104, 0, 0),
+    # row-split shape, factors shared through LDS (rank > 16, widths multiples of 128)
+    (VARIANT_WIDE, 32, 512, 1024, 4, 1), (VARIANT_WIDE, 32, 512, 1024, 4, 2), (VARIANT_WIDE, 64, 1024, 512, 8, 1),
+    (VARIANT_WIDE, 64, 256, 384, 4, 2), (VARIANT_WIDE, 128, 256, 256, 4, 1), (VARIANT_WIDE, 128, 128, 256, 0, 0),
+    (VARIANT_WIDE, 24, 512, 256, 4, 2), (VARIANT_WIDE, 40, 384, 640, 8, 1), (VARIANT_WIDE, 20, 128, 128, 4, 1),
+    (VARIANT_WIDE, 32, 520, 256, 0, 0),
     (VARIANT_AUTO, 1, 2048, 512, 0, 0), (VARIANT_AUTO, 8, 512, 2048, 0, 0), (VARIANT_AUTO, 16, 2048, 2048, 0, 0),
     (VARIANT_AUTO, 9, 256, 256, 0, 0), (VARIANT_AUTO, 64, 1024, 1024, 0, 0),
 ]
 
 
-_VNAME = {0: "auto", 1: "rowk", 2: "valu", 3: "mfma"}
+_VNAME = {0: "auto", 1: "rowk", 2: "valu", 3: "mfma", 4: "wide"}
 
 
 @pytest.mark.parametrize("variant,rank,d_in,d_out,waves,rowblocks", LORA_CASES,
@@ -112,6 +117,7 @@ DIREFT_CASES = [
     (VARIANT_MFMA, 16, 4096, 0, 2), (VARIANT_MFMA, 8, 520, 0, 0), (VARIANT_MFMA, 32, 8192, 0, 0),
     (VARIANT_MFMA, 64, 4104, 0, 0), (VARIANT_MFMA, 16, 8200, 0, 0), (VARIANT_MFMA, 64, 8192, 0, 0),
     (VARIANT_MFMA, 128, 1024, 0, 0), (VARIANT_MFMA, 32, 16384, 0, 0),
+    (VARIANT_WIDE, 32, 2048, 4, 2), (VARIANT_WIDE, 64, 1024, 8, 1), (VARIANT_WIDE, 20, 512, 4, 1), (VARIANT_WIDE, 128, 256, 4, 2),
 ]
 
 
