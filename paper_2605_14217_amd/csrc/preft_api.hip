@@ -128,9 +128,8 @@ bool launch_mfma_resident(const ApplyArgs &a, int64_t S, hipStream_t stream)
 template <int NB, bool DIREFT>
 bool launch_mfma_wide(const ApplyArgs &a, int64_t S, int mb, int waves, hipStream_t stream)
 {
-    if constexpr (NB < 2) {
-        return false;
-    } else {
+    {
+        if (NB < 2 && g_variant != 4) return false;           // rank <= 16: only on request
         if ((a.d_in & 127) || (a.d_out & 127)) return false;
         if (mb == 1) {
             if (waves == 8) hipLaunchKernelGGL((mfma_wide_kernel<NB, 1, 8, DIREFT>), dim3(tile_grid(a.T, S, 1)), dim3(512), 0, stream, a);
@@ -151,7 +150,9 @@ void launch_mfma_nb(const ApplyArgs &a, int64_t S, hipStream_t stream)
     // rank >= 32: the factors outweigh a 16-row tile's activations, so more rows share them:
     // the row-split kernel with 8 wavefronts x 16 rows (a whole 128-row chunk per workgroup)
     int mb = g_rowblocks ? g_rowblocks : 1;
-    int waves = g_waves ? (g_waves == 8 ? 8 : 4) : (NB >= 2 ? 8 : 4);
+    // rank <= 16 (column-split kernel): 8 wavefronts per 16-row tile on small batches, where a
+    // shorter workgroup lifetime shortens the kernel's tail; 4 on large ones
+    int waves = g_waves ? (g_waves == 8 ? 8 : 4) : ((NB >= 2 || a.T <= 65536) ? 8 : 4);
     if constexpr (DIREFT) {
         if (g_waves == 0 && g_variant != 4 && launch_mfma_resident<NB>(a, S, stream)) return;
     }
