@@ -322,3 +322,52 @@ def test_gpu_side_error_codes():
     with pytest.raises(preft.PreftError) as e:
         preft.preft_lora_apply(y[:, 4:], x[:, 4:], ss, sa, sp, Ap, Bp, 4, 1.0, 0, ws)   # misaligned base
     assert e.value.code == -3
+
+
+def test_calls_are_graph_capturable_and_read_their_tables_on_the_device():
+    """The header promises: no allocation, no synchronisation, launch shapes from host-visible sizes
+    only.  Capture schedule + LoRA + DiReFT into one HIP graph, then replay it with the segment
+    tables rewritten in place between replays (same T and S): every replay must match an eager
+    run on the tables of that moment."""
+    from parity_util import bits, dev_tables, direft_pools_to_device, lora_pools_to_device
+    N, d, r = 6, 512, 16
+    rng = np.random.Generator(np.random.PCG64(77))
+    lens = np.array([300, 1, 129, 1, 1, 64, 200, 1, 5, 3])
+    tabs = []
+    for k in range(3):
+        ids = rng.integers(-1, N, size=len(lens))
+        pre = np.where(rng.random(len(lens)) < 0.5, lens, (lens * rng.random(len(lens))).astype(np.int64))
+        tabs.append(wl.from_lengths(lens, ids, pre))
+    T, S = tabs[0].T, tabs[0].S
+    pool = wl.lora_pool(N, r, d, d, "bf16", device="cuda", seed=7)
+    dpool = wl.direft_pool(N, r, d, "bf16", device="cuda", seed=8)
+    Ap, Bp, keep1 = lora_pools_to_device(pool)
+    W1p, W2tp, bp, keep2 = direft_pools_to_device(dpool)
+    x = wl.activations(T, d, "bf16", device="cuda", seed=71)
+    y0 = wl.activations(T, d, "bf16", device="cuda", seed=72)
+    ss, sa, sp = dev_tables(tabs[0])
+    ws = preft.new_workspace(T, S)
+    y = y0.clone()
+    mode = preft.PREFT_PREFILL_ONLY
+
+    def body():
+        y.copy_(y0)
+        preft.preft_schedule(ws, ss, sa, sp, T, N, mode)
+        preft.preft_lora_apply(y, x, ss, sa, sp, Ap, Bp, r, 2.0, mode | preft.PREFT_SCHEDULE_READY, ws)
+        preft.preft_direft_apply(y, ss, sa, sp, W1p, W2tp, bp, r, 0.5, mode | preft.PREFT_SCHEDULE_READY, ws)
+
+    body()                                        # warm-up outside capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        body()
+    for k in (1, 2, 0, 1):
+        sa.copy_(torch.from_numpy(tabs[k].seg_adapter.copy()))      # same buffers, new contents
+        sp.copy_(torch.from_numpy(tabs[k].seg_prefill_len.copy()))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = y.clone()
+        body()                                    # eager run on the same tables
+        torch.cuda.synchronize()
+        assert torch.equal(bits(got), bits(y)), f"graph replay differs from the eager run (table {k})"
+        assert not torch.equal(bits(got), bits(y0))
