@@ -9,21 +9,23 @@ namespace preft {
 // Schedule (written by schedule_kernel, read by every apply kernel)
 //
 //   header   int32[16]   [0] number of chunks  [1] number of short rows  [2] active rows
-//                        [3] mode  [4] number of short-row groups
+//                        [3] mode  [4] number of gathered tiles
 //   chunks   int4[]      {adapter, first row, rows (1..CHUNK_ROWS), segment}
 //   shorts   int2[]      {adapter, row}, sorted by adapter when the pool has <= SORT_MAX_N slots
-//   groups   int4[]      {adapter, first entry in shorts, entries (1..GROUP_ROWS), 0}
+//   gtiles   int4[]      {adapter, first entry in shorts, entries (1..GTILE_ROWS), 0}
 //
 // A chunk is a run of at most CHUNK_ROWS consecutive active rows of one segment; a tile
 // kernel of height R (a divisor of CHUNK_ROWS) splits it into CHUNK_ROWS / R tiles.
 // Segments with at most SHORT_ROWS active rows (decode tokens, speculative tokens, the
 // last token of a chunked prompt) are listed row by row; rows that share an adapter are
-// gathered into groups of at most GROUP_ROWS so that the per-row kernel reads that
-// adapter's factors once per group.
+// gathered into tiles of at most GTILE_ROWS rows, which the tile kernels process like a tile
+// of a chunk except that every row has its own address: an adapter's factors are read once
+// per gathered tile, not once per decode token.
 // ---------------------------------------------------------------------------------------
 constexpr int CHUNK_ROWS  = 128;
 constexpr int SHORT_ROWS  = 4;
-constexpr int GROUP_ROWS  = 4;      // >= SHORT_ROWS: a short segment always fits one group
+constexpr int GTILE_ROWS  = 16;     // >= SHORT_ROWS: a short segment always fits one gathered tile
+constexpr int GROUP_ROWS  = 4;      // rows the per-row kernel carries through one sweep of the factors
 constexpr int SORT_MAX_N  = 4096;   // pools up to this many slots get their short rows sorted by adapter
 constexpr int HEADER_INTS = 16;
 constexpr int PREFT_MAX_RANK_DEV = 128;   // must equal PREFT_MAX_RANK of the public header
@@ -32,7 +34,7 @@ struct ScheduleView {
     int32_t *header;
     int4    *chunks;
     int2    *shorts;
-    int4    *groups;        // capacity short_cap (a group holds at least one row)
+    int4    *gtiles;        // capacity short_cap (a gathered tile holds at least one row)
     int32_t  chunk_cap;
     int32_t  short_cap;
 };
@@ -48,6 +50,14 @@ __host__ __device__ inline int64_t short_capacity(int64_t T, int64_t S)
 {
     int64_t c = (int64_t)SHORT_ROWS * S;
     return (c < T ? c : T) + 1;
+}
+// Gathered tiles: sorted pools cut every adapter's rows into tiles (at most one partial tile per
+// adapter); unsorted pools get one tile per short segment.
+__host__ __device__ inline int64_t gtile_capacity(int64_t T, int64_t S, int64_t N)
+{
+    const int64_t rows = short_capacity(T, S);
+    const int64_t c = N <= SORT_MAX_N ? N + rows / GTILE_ROWS + 1 : S;
+    return c < rows ? c : rows;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -158,7 +168,59 @@ struct ApplyArgs {
     const int32_t      *header;
     const int4         *chunks;
     const int2         *shorts;
-    const int4         *groups;
+    const int4         *gtiles;
+    int32_t             gathered_only;   // tile kernels: skip the chunks (another launch covers them)
 };
+
+// The tile a workgroup of a tile kernel of height R works on: rows of one adapter, either
+// consecutive (a tile of a chunk) or listed one by one (a gathered tile).
+struct TileRows {
+    int32_t      adapter, n_rows;
+    int64_t      base;                   // first row, or first entry of the list
+    const int2  *list;                   // null: consecutive rows
+
+    // row of slot `slot`; slots past the end alias the last row
+    __device__ __forceinline__ int64_t row(int slot) const
+    {
+        slot = min(slot, n_rows - 1);
+        return list ? (int64_t)list[base + slot].y : base + slot;
+    }
+};
+
+// Maps tile number `unit` of a launch onto its rows.  Units 0 .. chunks * (CHUNK_ROWS / R) - 1
+// are the tiles of the chunks, the gathered tiles follow (a gathered tile takes GTILE_ROWS / R
+// units when R is smaller).  Returns false when the unit has no rows.
+template <int R>
+__device__ __forceinline__ bool tile_rows(const ApplyArgs &p, int unit, int n_chunk_units, TileRows &t)
+{
+    constexpr int TPC = CHUNK_ROWS / R;
+    constexpr int UPG = R >= GTILE_ROWS ? 1 : GTILE_ROWS / R;
+    if (unit < n_chunk_units) {
+        const int4 ch = p.chunks[unit / TPC];
+        const int row0 = (unit % TPC) * R;
+        t.adapter = ch.x;
+        t.n_rows = min(R, ch.z - row0);
+        t.base = (int64_t)ch.y + row0;
+        t.list = nullptr;
+    } else {
+        const int u = unit - n_chunk_units;
+        const int4 gt = p.gtiles[u / UPG];
+        const int first = (u % UPG) * R;
+        t.adapter = gt.x;
+        t.n_rows = min(R, gt.z - first);
+        t.base = (int64_t)gt.y + first;
+        t.list = p.shorts;
+    }
+    return t.n_rows > 0;
+}
+
+// Number of units of a tile-kernel launch of height R (see tile_rows).
+template <int R>
+__device__ __forceinline__ int tile_units(const ApplyArgs &p, int *n_chunk_units)
+{
+    constexpr int UPG = R >= GTILE_ROWS ? 1 : GTILE_ROWS / R;
+    *n_chunk_units = p.gathered_only ? 0 : p.header[0] * (CHUNK_ROWS / R);
+    return *n_chunk_units + p.header[4] * UPG;
+}
 
 }  // namespace preft

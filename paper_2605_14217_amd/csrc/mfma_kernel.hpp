@@ -80,13 +80,13 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
     __shared__ float red[WAVES * NB * MB * 4 * 64];           // cross-wavefront reduction of z
     __shared__ u32x4_t turn[WAVES][MB * 16 * MFMA_TRS];       // wavefront-private turn buffers
 
-    const int unit = xcd_unit(p.header[0] * TPC);
+    int n_chunk_units;
+    const int unit = xcd_unit(tile_units<R>(p, &n_chunk_units));
     if (unit < 0) return;
-    const int4 ch = p.chunks[unit / TPC];
-    const int tile_row0 = (unit % TPC) * R;
-    if (tile_row0 >= ch.z) return;                            // uniform over the workgroup
-    const int adapter = ch.x;
-    const int n_rows = min(R, ch.z - tile_row0);              // rows of this tile
+    TileRows tile;
+    if (!tile_rows<R>(p, unit, n_chunk_units, tile)) return;   // uniform over the workgroup
+    const int adapter = tile.adapter;
+    const int n_rows = tile.n_rows;
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int rl = lane & 15, g = lane >> 4;                  // MFMA order: row rl, 16-byte group g
@@ -126,11 +126,11 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
     for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int64_t row = (int64_t)ch.y + tile_row0 + min(mb * 16 + 4 * i + q, n_rows - 1);
+            const int64_t row = tile.row(mb * 16 + 4 * i + q);
             xu[mb][i] = as_global(p.x) + row * ldx_b + c16 * 16;
             yu[mb][i] = as_global(p.y) + row * ldy_b + c16 * 16;
         }
-        const int64_t row = (int64_t)ch.y + tile_row0 + min(mb * 16 + ld_row, n_rows - 1);
+        const int64_t row = tile.row(mb * 16 + ld_row);
         xs[mb] = as_global(p.x) + row * ldx_b + ld_chunk * 16;
         ys[mb] = as_global(p.y) + row * ldy_b + ld_chunk * 16;
     }

@@ -36,7 +36,7 @@ ScheduleView view_of(void *workspace, int64_t T, int64_t S)
     v.chunk_cap = (int32_t)chunk_capacity(T, S);
     v.short_cap = (int32_t)short_capacity(T, S);
     char *after_chunks = base + HEADER_INTS * 4 + (size_t)v.chunk_cap * sizeof(int4);
-    v.groups = reinterpret_cast<int4 *>(after_chunks);                  // 16-byte aligned
+    v.gtiles = reinterpret_cast<int4 *>(after_chunks);                  // 16-byte aligned
     v.shorts = reinterpret_cast<int2 *>(after_chunks + (size_t)v.short_cap * sizeof(int4));
     return v;
 }
@@ -70,9 +70,19 @@ int launch_schedule(void *workspace, const int32_t *seg_start, const int32_t *se
 // ------------------------------------------------------------------------------------
 // tile-kernel dispatch
 // ------------------------------------------------------------------------------------
-inline unsigned tile_grid(int64_t T, int64_t S, int tiles_per_chunk)
+// Upper bound of the units of a tile-kernel launch of height `rows`, from host-visible sizes,
+// rounded to the 8 XCDs.
+inline unsigned tile_grid(const ApplyArgs &a, int64_t S, int rows)
 {
-    const int64_t units = chunk_capacity(T, S) * tiles_per_chunk;
+    const int64_t per_gtile = rows >= GTILE_ROWS ? 1 : GTILE_ROWS / rows;
+    int64_t units = gtile_capacity(a.T, S, a.N) * per_gtile;
+    if (!a.gathered_only) units += chunk_capacity(a.T, S) * (CHUNK_ROWS / rows);
+    return (unsigned)(((units + 7) / 8) * 8);
+}
+// the row-split kernel takes whole chunks only
+inline unsigned chunk_grid(const ApplyArgs &a, int64_t S, int rows)
+{
+    const int64_t units = chunk_capacity(a.T, S) * (CHUNK_ROWS / rows);
     return (unsigned)(((units + 7) / 8) * 8);
 }
 
@@ -80,7 +90,7 @@ template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT>
 void launch_mfma(const ApplyArgs &a, int64_t S, hipStream_t stream)
 {
     constexpr int R = 16 * MB;
-    hipLaunchKernelGGL((mfma_tile_kernel<NB, MB, WAVES, HUNITS, DIREFT>), dim3(tile_grid(a.T, S, CHUNK_ROWS / R)),
+    hipLaunchKernelGGL((mfma_tile_kernel<NB, MB, WAVES, HUNITS, DIREFT>), dim3(tile_grid(a, S, R)),
                        dim3(WAVES * 64), 0, stream, a);
 }
 
@@ -132,13 +142,13 @@ bool launch_mfma_wide(const ApplyArgs &a, int64_t S, int mb, int waves, hipStrea
         if (NB < 2 && g_variant != 4) return false;           // rank <= 16: only on request
         if ((a.d_in & 127) || (a.d_out & 127)) return false;
         if (mb == 1) {
-            if (waves == 8) hipLaunchKernelGGL((mfma_wide_kernel<NB, 1, 8, DIREFT>), dim3(tile_grid(a.T, S, 1)), dim3(512), 0, stream, a);
-            else            hipLaunchKernelGGL((mfma_wide_kernel<NB, 1, 4, DIREFT>), dim3(tile_grid(a.T, S, 2)), dim3(256), 0, stream, a);
+            if (waves == 8) hipLaunchKernelGGL((mfma_wide_kernel<NB, 1, 8, DIREFT>), dim3(chunk_grid(a, S, 128)), dim3(512), 0, stream, a);
+            else            hipLaunchKernelGGL((mfma_wide_kernel<NB, 1, 4, DIREFT>), dim3(chunk_grid(a, S, 64)), dim3(256), 0, stream, a);
         } else {
             if constexpr (NB <= 4)
-                hipLaunchKernelGGL((mfma_wide_kernel<NB, 2, 4, DIREFT>), dim3(tile_grid(a.T, S, 1)), dim3(256), 0, stream, a);
+                hipLaunchKernelGGL((mfma_wide_kernel<NB, 2, 4, DIREFT>), dim3(chunk_grid(a, S, 128)), dim3(256), 0, stream, a);
             else
-                hipLaunchKernelGGL((mfma_wide_kernel<NB, 1, 8, DIREFT>), dim3(tile_grid(a.T, S, 1)), dim3(512), 0, stream, a);
+                hipLaunchKernelGGL((mfma_wide_kernel<NB, 1, 8, DIREFT>), dim3(chunk_grid(a, S, 128)), dim3(512), 0, stream, a);
         }
         return true;
     }
@@ -156,7 +166,14 @@ void launch_mfma_nb(const ApplyArgs &a, int64_t S, hipStream_t stream)
     if constexpr (DIREFT) {
         if (g_waves == 0 && g_variant != 4 && launch_mfma_resident<NB>(a, S, stream)) return;
     }
-    if (g_variant != 3 && launch_mfma_wide<NB, DIREFT>(a, S, mb, waves, stream)) return;
+    if (g_variant != 3 && launch_mfma_wide<NB, DIREFT>(a, S, mb, waves, stream)) {
+        // the row-split kernel shares one adapter's factors among the 128 rows of a chunk;
+        // gathered tiles (16 rows of an adapter) go to the column-split kernel
+        ApplyArgs g = a;
+        g.gathered_only = 1;
+        launch_mfma_stream<NB, DIREFT>(g, S, 1, NB >= 8 ? 4 : 8, stream);
+        return;
+    }
     launch_mfma_stream<NB, DIREFT>(a, S, mb, waves, stream);
 }
 
@@ -176,13 +193,13 @@ void launch_valu(const ApplyArgs &a, int64_t S, hipStream_t stream)
     constexpr int RB = RANK <= 4 ? 4 : 2;
     int waves = g_waves ? g_waves : 4;
     if (waves == 4)
-        hipLaunchKernelGGL((valu_tile_kernel<RANK, RB, 4, DIREFT>), dim3(tile_grid(a.T, S, CHUNK_ROWS / (RB * 4))),
+        hipLaunchKernelGGL((valu_tile_kernel<RANK, RB, 4, DIREFT>), dim3(tile_grid(a, S, RB * 4)),
                            dim3(256), 0, stream, a);
     else if (waves == 2)
-        hipLaunchKernelGGL((valu_tile_kernel<RANK, RB, 2, DIREFT>), dim3(tile_grid(a.T, S, CHUNK_ROWS / (RB * 2))),
+        hipLaunchKernelGGL((valu_tile_kernel<RANK, RB, 2, DIREFT>), dim3(tile_grid(a, S, RB * 2)),
                            dim3(128), 0, stream, a);
     else
-        hipLaunchKernelGGL((valu_tile_kernel<RANK, RB, 1, DIREFT>), dim3(tile_grid(a.T, S, CHUNK_ROWS / RB)),
+        hipLaunchKernelGGL((valu_tile_kernel<RANK, RB, 1, DIREFT>), dim3(tile_grid(a, S, RB)),
                            dim3(64), 0, stream, a);
 }
 
@@ -209,7 +226,7 @@ void launch_rows(const ApplyArgs &a, int64_t S, bool chunks_too, hipStream_t str
                            dim3((unsigned)(chunk_capacity(a.T, S) * (CHUNK_ROWS / GROUP_ROWS))),
                            dim3(ROW_THREADS), 0, stream, a);
     }
-    int64_t g = ((short_capacity(a.T, S) + 7) / 8) * 8;     // a multiple of 8: one share per XCD
+    int64_t g = ((gtile_capacity(a.T, S, a.N) * GTILE_ROWS + 7) / 8) * 8;     // a multiple of 8: one share per XCD
     if (g > 4096) g = 4096;
     hipLaunchKernelGGL((row_kernel_short<E, DIREFT>), dim3((unsigned)g), dim3(ROW_THREADS), 0, stream, a);
 }
@@ -231,13 +248,11 @@ template <bool DIREFT>
 int launch_apply(const ApplyArgs &a, int64_t S, int dtype, hipStream_t stream)
 {
     switch (choose_path(dtype, a.rank)) {
-    case Path::Mfma:
+    case Path::Mfma:                       // the tile kernels take chunks and gathered tiles alike
         launch_mfma_rank<DIREFT>(a, S, stream);
-        launch_rows<bf16_tag, DIREFT>(a, S, false, stream);
         break;
     case Path::Valu:
         launch_valu_rank<DIREFT>(a, S, stream);
-        launch_rows<bf16_tag, DIREFT>(a, S, false, stream);
         break;
     default:
         if (dtype == PREFT_BF16) launch_rows<bf16_tag, DIREFT>(a, S, true, stream);
@@ -303,7 +318,7 @@ int preft_lora_apply(void *y, int64_t ldy, const void *x, int64_t ldx, int32_t T
     ApplyArgs a;
     a.y = y; a.x = x; a.ldy = ldy; a.ldx = ldx; a.T = T; a.d_in = d_in; a.d_out = d_out;
     a.A_pool = A_pool; a.Bt_pool = B_pool; a.bias_pool = nullptr; a.N = N; a.rank = rank; a.scale = scale;
-    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.groups = v.groups;
+    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.gtiles = v.gtiles; a.gathered_only = 0;
     return launch_apply<false>(a, S, dtype, st);
 }
 
@@ -329,7 +344,7 @@ int preft_direft_apply(void *h, int64_t ldh, int32_t T, int32_t d, const int32_t
     ApplyArgs a;
     a.y = h; a.x = h; a.ldy = ldh; a.ldx = ldh; a.T = T; a.d_in = d; a.d_out = d;
     a.A_pool = W1_pool; a.Bt_pool = W2t_pool; a.bias_pool = b_pool; a.N = N; a.rank = rank; a.scale = scale;
-    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.groups = v.groups;
+    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.gtiles = v.gtiles; a.gathered_only = 0;
     return launch_apply<true>(a, S, dtype, st);
 }
 

@@ -231,22 +231,29 @@ __device__ __forceinline__ void group_apply(const ApplyArgs &p, int adapter, con
     __syncthreads();          // z is reused by the next group
 }
 
-// Short rows: grid-stride over the schedule's groups (rows of one adapter, gathered by the scheduler).
+// Short rows: the schedule's gathered tiles (rows of one adapter) are cut into groups of at most
+// GROUP_ROWS rows, fewer when the batch has few short rows so that a decode-only step still
+// fills the chip; grid-stride over the groups.
 template <typename E, bool DIREFT>
 __global__ __launch_bounds__(ROW_THREADS) void row_kernel_short(ApplyArgs p)
 {
     __shared__ float z[GROUP_ROWS * PREFT_MAX_RANK_DEV];
-    // groups are sorted by adapter: deal contiguous runs to the 8 XCDs (workgroup ids go round-robin
+    const int grows = max(1, min(GROUP_ROWS, p.header[1] / 512));
+    const int per_tile = (GTILE_ROWS + grows - 1) / grows;
+    // tiles are sorted by adapter: deal contiguous runs to the 8 XCDs (workgroup ids go round-robin
     // over them) so that the groups of one adapter meet in one L2
-    const int n = p.header[4];
+    const int n = p.header[4] * per_tile;
     const int per_xcd = (n + 7) >> 3;
     const int first = (blockIdx.x & 7) * per_xcd, last = min(first + per_xcd, n);
     for (int e = first + (blockIdx.x >> 3); e < last; e += gridDim.x >> 3) {
-        const int4 grp = p.groups[e];
+        const int4 gt = p.gtiles[e / per_tile];
+        const int g0 = (e % per_tile) * grows;
+        if (g0 >= gt.z) continue;                              // uniform over the workgroup
+        const int count = min(grows, gt.z - g0);
         int rows[GROUP_ROWS];
 #pragma unroll
-        for (int j = 0; j < GROUP_ROWS; ++j) rows[j] = p.shorts[grp.y + min(j, grp.z - 1)].y;
-        group_apply<E, DIREFT>(p, grp.x, rows, grp.z, z);
+        for (int j = 0; j < GROUP_ROWS; ++j) rows[j] = p.shorts[gt.y + g0 + min(j, count - 1)].y;
+        group_apply<E, DIREFT>(p, gt.x, rows, count, z);
     }
 }
 

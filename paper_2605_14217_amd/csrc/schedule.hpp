@@ -57,7 +57,8 @@ __device__ __forceinline__ int32_t block_exclusive_scan(int32_t v, int32_t *lds 
 // One workgroup.  Thread i owns the contiguous slice of segments [i*per, (i+1)*per), so the
 // chunk list keeps segment order (consecutive chunks of one segment share an adapter, which
 // the tile kernels exploit for cache locality).  Short rows are counting-sorted by adapter
-// (LDS histogram) and cut into groups of at most GROUP_ROWS rows of one adapter.
+// (LDS histogram) and cut into gathered tiles of at most GTILE_ROWS rows of one adapter; a
+// pool too large for the histogram gets one gathered tile per short segment instead.
 __global__ __launch_bounds__(SCHED_THREADS) void schedule_kernel(
     const int32_t *__restrict__ seg_start, const int32_t *__restrict__ seg_adapter,
     const int32_t *__restrict__ seg_prefill_len, int32_t S, int32_t T, int32_t N, int all_tokens,
@@ -97,32 +98,31 @@ __global__ __launch_bounds__(SCHED_THREADS) void schedule_kernel(
     int32_t seg_off   = block_exclusive_scan(my_short_segs, lds, &tot_short_segs);
     (void)block_exclusive_scan(my_act, lds, &tot_act);
 
-    // ---- sorted case: histogram -> first entry per adapter, group counts -> first group per adapter
+    // ---- sorted case: histogram -> first entry per adapter, tile counts -> first tile per adapter
     const int32_t bins_per = (N + SCHED_THREADS) / SCHED_THREADS;      // covers bins 0..N-1
     const int32_t b0 = min(tid * bins_per, N), b1 = min(b0 + bins_per, N);
-    int32_t tot_groups = tot_short_segs;
-    int32_t my_group_off = 0;
+    int32_t tot_gtiles = tot_short_segs;
+    int32_t my_gtile_off = 0;
     if (sorted) {
-        // few short rows: smaller groups, so that a decode-only step still fills the chip
-        const int32_t grows = max(1, min(GROUP_ROWS, tot_short / 512));
-        int32_t rows_here = 0, groups_here = 0;
+        constexpr int32_t grows = GTILE_ROWS;   // rows per gathered tile
+        int32_t rows_here = 0, gtiles_here = 0;
         for (int32_t a = b0; a < b1; ++a) {
             const int32_t c = bin_start[a];
             rows_here += c;
-            groups_here += (c + grows - 1) / grows;
+            gtiles_here += (c + grows - 1) / grows;
         }
         int32_t dummy;
         int32_t row_base = block_exclusive_scan(rows_here, lds, &dummy);
-        my_group_off = block_exclusive_scan(groups_here, lds, &tot_groups);
+        my_gtile_off = block_exclusive_scan(gtiles_here, lds, &tot_gtiles);
         // the scans end with a barrier-protected read of lds, the histogram is final here
-        int32_t grp = my_group_off;
+        int32_t grp = my_gtile_off;
         for (int32_t a = b0; a < b1; ++a) {
             const int32_t c = bin_start[a];
             bin_start[a] = row_base;
             bin_cursor[a] = row_base;
             for (int32_t i = 0; i * grows < c; ++i, ++grp)
                 if (grp < out.short_cap)
-                    out.groups[grp] = make_int4(a, row_base + i * grows, min(grows, c - i * grows), 0);
+                    out.gtiles[grp] = make_int4(a, row_base + i * grows, min(grows, c - i * grows), 0);
             row_base += c;
         }
         __syncthreads();
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(SCHED_THREADS) void schedule_kernel(
         out.header[1] = min(tot_short, out.short_cap);
         out.header[2] = tot_act;
         out.header[3] = all_tokens;
-        out.header[4] = min(tot_groups, out.short_cap);
+        out.header[4] = min(tot_gtiles, out.short_cap);
     }
 
     // ---- pass 2: emission.  All lanes of a wave run the same number of iterations; a segment
@@ -149,7 +149,7 @@ __global__ __launch_bounds__(SCHED_THREADS) void schedule_kernel(
                 pos = atomicAdd(&bin_cursor[g.adapter], g.n_act);
             } else {
                 pos = short_off;
-                if (seg_off < out.short_cap) out.groups[seg_off] = make_int4(g.adapter, pos, g.n_act, 0);
+                if (seg_off < out.short_cap) out.gtiles[seg_off] = make_int4(g.adapter, pos, g.n_act, 0);
                 short_off += g.n_act;
                 seg_off += 1;
             }

@@ -32,16 +32,15 @@ template <int RANK, int RB, int WAVES, bool DIREFT>
 __global__ __launch_bounds__(WAVES * 64) void valu_tile_kernel(ApplyArgs p)
 {
     constexpr int R = RB * WAVES;
-    constexpr int TPC = CHUNK_ROWS / R;
     static_assert(CHUNK_ROWS % R == 0, "tile height must divide the chunk height");
 
-    const int unit = xcd_unit(p.header[0] * TPC);
+    int n_chunk_units;
+    const int unit = xcd_unit(tile_units<R>(p, &n_chunk_units));
     if (unit < 0) return;
-    const int4 ch = p.chunks[unit / TPC];
-    const int tile_row0 = (unit % TPC) * R;
-    if (tile_row0 >= ch.z) return;
-    const int adapter = ch.x;
-    const int n_rows = min(R, ch.z - tile_row0);
+    TileRows tile;
+    if (!tile_rows<R>(p, unit, n_chunk_units, tile)) return;
+    const int adapter = tile.adapter;
+    const int n_rows = tile.n_rows;
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int wave_row0 = wave * RB;
@@ -58,7 +57,7 @@ __global__ __launch_bounds__(WAVES * 64) void valu_tile_kernel(ApplyArgs p)
     gptr_t yp[RB];
 #pragma unroll
     for (int i = 0; i < RB; ++i) {
-        const int64_t row = (int64_t)ch.y + tile_row0 + min(wave_row0 + i, n_rows - 1);
+        const int64_t row = tile.row(wave_row0 + i);
         xp[i] = as_global(p.x) + row * ldx_b;
         yp[i] = as_global(p.y) + row * ldy_b;
     }

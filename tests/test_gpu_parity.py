@@ -215,15 +215,23 @@ def test_schedule_counts_match_the_tables():
             short_cap = min(4 * tab.S, tab.T) + 1
             g0 = 64 + 16 * chunk_cap
             s0 = g0 + 16 * short_cap
-            groups = ws[g0:g0 + 16 * hdr[4]].view(torch.int32).view(-1, 4).cpu().numpy()
+            gtiles = ws[g0:g0 + 16 * hdr[4]].view(torch.int32).view(-1, 4).cpu().numpy()
             shorts = ws[s0:s0 + 8 * hdr[1]].view(torch.int32).view(-1, 2).cpu().numpy()
-            # groups partition the short-row list; a group's rows share its adapter
+            # gathered tiles partition the short-row list; a tile's rows share its adapter
             seen = np.zeros(len(shorts), dtype=np.int32)
-            for a, first, cnt, _ in groups:
-                assert 1 <= cnt <= 4
+            for a, first, cnt, _ in gtiles:
+                assert 1 <= cnt <= 16
                 assert np.all(shorts[first:first + cnt, 0] == a)
                 seen[first:first + cnt] += 1
             assert np.all(seen == 1)
+            # the launch grids are sized from these bounds
+            if N <= 4096:
+                assert np.all(np.diff(shorts[:, 0]) >= 0)                 # sorted by adapter
+                partial = gtiles[gtiles[:, 2] < 16, 0]
+                assert len(np.unique(partial)) == len(partial)            # one partial tile per adapter
+                assert len(gtiles) <= min(short_cap, N + short_cap // 16 + 1)
+            else:
+                assert len(gtiles) <= min(short_cap, tab.S)
             covered = np.zeros(tab.T, dtype=np.int32)
             owner = np.full(tab.T, -1, dtype=np.int32)
             for a, row0, nrows, seg in chunks:
