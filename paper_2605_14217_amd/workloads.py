@@ -173,6 +173,78 @@ def random_segments(rng: np.random.Generator, S: int, N: int, max_len: int,
 
 
 # ----------------------------------------------------------------------------------------
+# request stream and first-come-first-served engine steps (paper App. E.1 and E.3)
+# ----------------------------------------------------------------------------------------
+@dataclasses.dataclass
+class RequestStream:
+    prompt_len: np.ndarray   # int64 [R]
+    output_len: np.ndarray   # int64 [R], >= 2
+    adapter: np.ndarray      # int32 [R]
+
+
+def request_stream(n_requests: int, n_adapters: int, mix: str = "uniform", l_max: int = 2048,
+                   seed: int = 0, zipf_alpha: float = 1.0) -> RequestStream:
+    """Requests of the paper's serving microbenchmark (App. E.1).
+
+    Prompt length: lognormal with shape 0.8, shift -1 and scale 18 (i.e. -1 + 18 exp(0.8 Z)),
+    rounded to an integer (the paper does not say how it is made integral) and clipped to
+    [1, l_max - 2]; prompt + output drawn uniformly from [prompt + 2, l_max].  Adapter per
+    request from one of the four mixes: identical, uniform, skewed (Zipf), distinct.
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    p = -1.0 + 18.0 * np.exp(0.8 * rng.standard_normal(n_requests))
+    p = np.clip(np.rint(p), 1, l_max - 2).astype(np.int64)
+    total = rng.integers(p + 2, l_max + 1)               # inclusive upper end
+    if mix == "identical":
+        ids = np.zeros(n_requests, dtype=np.int32)
+    elif mix == "uniform":
+        ids = rng.integers(0, n_adapters, size=n_requests).astype(np.int32)
+    elif mix == "skewed":
+        ids = _zipf_ids(rng, n_requests, n_adapters, zipf_alpha)
+    elif mix == "distinct":
+        ids = (np.arange(n_requests) % n_adapters).astype(np.int32)
+        rng.shuffle(ids)
+    else:
+        raise ValueError(f"unknown adapter mix {mix!r}")
+    return RequestStream(p, total - p, ids)
+
+
+def fcfs_steps(req: RequestStream, batch: int):
+    """Engine steps of a first-come-first-served continuous-batching loop (App. E.3).
+
+    At most ``batch`` requests are in flight; a freed slot is refilled from the stream in
+    arrival order.  A request's first step holds its whole prompt as one segment (all rows are
+    prompt positions) and yields its first output token; each later step holds one decode
+    row for it, until ``output_len`` tokens exist.  Yields ``(table, repeat)``: ``repeat``
+    consecutive steps share the table (a run of decode-only steps between two departures).
+    """
+    R = len(req.prompt_len)
+    slots: List[Optional[list]] = [None] * batch      # [request, tokens produced]
+    nxt = 0
+    while True:
+        for i in range(batch):                        # admission, in arrival order
+            if slots[i] is None and nxt < R:
+                slots[i] = [nxt, 0]
+                nxt += 1
+        live = [s for s in slots if s is not None]
+        if not live:
+            return
+        lens = [int(req.prompt_len[r]) if done == 0 else 1 for r, done in live]
+        pre = [int(req.prompt_len[r]) if done == 0 else 0 for r, done in live]
+        ids = [int(req.adapter[r]) for r, _ in live]
+        repeat = 1
+        if all(done > 0 for _, done in live):         # decode-only: identical until someone leaves
+            repeat = min(int(req.output_len[r]) - done for r, done in live)
+        yield from_lengths(lens, ids, pre), repeat
+        for i in range(batch):
+            if slots[i] is None:
+                continue
+            slots[i][1] += repeat
+            if slots[i][1] >= int(req.output_len[slots[i][0]]):
+                slots[i] = None
+
+
+# ----------------------------------------------------------------------------------------
 # tensors
 # ----------------------------------------------------------------------------------------
 _TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16, "f64": torch.float64}

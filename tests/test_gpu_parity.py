@@ -379,3 +379,26 @@ def test_calls_are_graph_capturable_and_read_their_tables_on_the_device():
         torch.cuda.synchronize()
         assert torch.equal(bits(got), bits(y)), f"graph replay differs from the eager run (table {k})"
         assert not torch.equal(bits(got), bits(y0))
+
+
+def test_fcfs_trace_steps_match_the_oracle():
+    """Every engine step of a small first-come-first-served serving trace (App. E.1, E.3), in both
+    modes: prompt steps mix whole prompts with decode rows, decode-only steps hold one row per
+    request in flight."""
+    from parity_util import run_direft_case, run_lora_case
+    N, d, r = 3, 256, 8
+    req = wl.request_stream(14, N, "uniform", l_max=40, seed=4)
+    pool = wl.lora_pool(N, r, d, d, "bf16", device="cuda", seed=41)
+    dpool = wl.direft_pool(N, r, d, "bf16", device="cuda", seed=42)
+    x_all = wl.activations(4 * 40, d, "bf16", device="cuda", seed=43)
+    y_all = wl.activations(4 * 40, d, "bf16", device="cuda", seed=44)
+    steps = prompts = 0
+    for tab, repeat in wl.fcfs_steps(req, 4):
+        steps += repeat
+        prompts += int((tab.seg_prefill_len > 0).sum())
+        x, y0 = x_all[:tab.T].contiguous(), y_all[:tab.T].contiguous()
+        for all_tokens in (False, True):
+            _, counts = run_lora_case(tab, pool, x, y0, "bf16", 2.0, all_tokens)
+            assert counts[2] == (tab.T if all_tokens else int(tab.seg_prefill_len.sum()))
+            run_direft_case(tab, dpool, y0, "bf16", 1.0, all_tokens)
+    assert prompts == 14 and steps > 14
