@@ -13,6 +13,9 @@
  *   - Eq. 3  DiReFT:  Phi(h) = h + B^T (A h + b),        A, B in R^{r x d}, b in R^r,
  *            with the scalar prefactor s_r of App. C.2 (s_r = 1 gives Eq. 3 itself);
  *            the prefactor multiplies the whole B^T(Ah + b) term, bias included.
+ *   - App. C.2 LoReFT: Phi(h) = h + s_r R^T (W h + b - R h),  W, R in R^{r x d}, b in R^r
+ *            (R is the materialised rotation, rows orthonormal in the method; the
+ *            arithmetic below does not assume it).
  *   - Eq. 4  P^PreFT = {1..p}: the first p rows of a sequence (its prompt positions);
  *            the all-position set P^A of Sec. 3.2 is every row of the sequence.
  *
@@ -120,6 +123,26 @@ void ora_direft_row(double *out, const void *h,
     free(a);
 }
 
+/* App. C.2, LoReFT on one position: out = h + s * R^T (W h + b - R h).  W, R are [r,d]. */
+void ora_loreft_row(double *out, const void *h,
+                    const void *W, const void *R, const void *b,
+                    int64_t d, int32_t r, double s, int dt_act, int dt_w)
+{
+    double *a = (double *)malloc(sizeof(double) * (size_t)(r > 0 ? r : 1));
+    for (int32_t k = 0; k < r; ++k) {                        /* a = W h + b - R h      */
+        double wh = 0.0, rh = 0.0;
+        for (int64_t j = 0; j < d; ++j) wh += ld(W, (int64_t)k * d + j, dt_w) * ld(h, j, dt_act);
+        for (int64_t j = 0; j < d; ++j) rh += ld(R, (int64_t)k * d + j, dt_w) * ld(h, j, dt_act);
+        a[k] = wh + (b ? ld(b, k, dt_w) : 0.0) - rh;
+    }
+    for (int64_t j = 0; j < d; ++j) {                        /* out = h + s R^T a      */
+        double acc = 0.0;
+        for (int32_t k = 0; k < r; ++k) acc += ld(R, (int64_t)k * d + j, dt_w) * a[k];
+        out[j] = ld(h, j, dt_act) + s * acc;
+    }
+    free(a);
+}
+
 /*
  * LoRA over a batch.  If rows == NULL every row t in [0,T) is produced into out[t];
  * otherwise out[q] holds row rows[q], q < n_rows.  Rows outside the position set are
@@ -186,6 +209,38 @@ int ora_direft_batch(double *out, const int64_t *rows, int64_t n_rows,
             for (int64_t j = 0; j < d; ++j) o[j] = ld(h_t, j, dt_act);
         } else {
             ora_direft_row(o, h_t, A_pool[a], B_pool[a], b_pool ? b_pool[a] : NULL,
+                           d, r, s, dt_act, dt_w);
+        }
+    }
+    free(row_adapter);
+    return 0;
+}
+
+/* LoReFT over a batch; same conventions as ora_direft_batch. */
+int ora_loreft_batch(double *out, const int64_t *rows, int64_t n_rows,
+                     const void *h, int64_t ldh, int64_t T, int64_t d,
+                     const int32_t *seg_start, const int32_t *seg_adapter,
+                     const int32_t *seg_prompt_len, int32_t S,
+                     const void *const *W_pool, const void *const *R_pool,
+                     const void *const *b_pool, int32_t N,
+                     int32_t r, double s, int position_set, int dt_act, int dt_w, int gathered)
+{
+    int32_t *row_adapter = (int32_t *)malloc(sizeof(int32_t) * (size_t)(T > 0 ? T : 1));
+    if (ora_positions(row_adapter, T, seg_start, seg_adapter, seg_prompt_len, S, N, position_set)) {
+        free(row_adapter);
+        return -1;
+    }
+    int64_t count = rows ? n_rows : T;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t q = 0; q < count; ++q) {
+        int64_t t = rows ? rows[q] : q;
+        double *o = out + q * d;
+        int32_t a = row_adapter[t];
+        const void *h_t = row_ptr(h, (rows && gathered) ? q : t, ldh, dt_act);
+        if (a < 0) {
+            for (int64_t j = 0; j < d; ++j) o[j] = ld(h_t, j, dt_act);
+        } else {
+            ora_loreft_row(o, h_t, W_pool[a], R_pool[a], b_pool ? b_pool[a] : NULL,
                            d, r, s, dt_act, dt_w);
         }
     }

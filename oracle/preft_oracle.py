@@ -65,6 +65,8 @@ def _load():
                                          vpp, vpp, vpp, ctypes.c_int32,
                                          ctypes.c_int32, ctypes.c_double, ctypes.c_int,
                                          ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        lib.ora_loreft_batch.restype = ctypes.c_int
+        lib.ora_loreft_batch.argtypes = lib.ora_direft_batch.argtypes
         lib.ora_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -198,7 +200,20 @@ def direft(h, seg_start, seg_adapter, seg_prompt_len, A_pool, B_pool, b_pool, r,
     """Eq. 1/3/4 (with the prefactor s of App. C.2) over a batch: fp64 [T,d] or [len(rows),d].
 
     gathered=True (needs rows): h holds only the selected rows, in the order of `rows`."""
-    lib = _load()
+    return _reft(_load().ora_direft_batch, h, seg_start, seg_adapter, seg_prompt_len, A_pool, B_pool, b_pool,
+                 r, s, position_set, rows, gathered)
+
+
+def loreft(h, seg_start, seg_adapter, seg_prompt_len, W_pool, R_pool, b_pool, r, s,
+           position_set, rows=None, gathered=False):
+    """LoReFT of App. C.2, h + s R^T (W h + b - R h), on the rows of Eq. 1/4; W, R are [r,d] each.
+    Same conventions as `direft`."""
+    return _reft(_load().ora_loreft_batch, h, seg_start, seg_adapter, seg_prompt_len, W_pool, R_pool, b_pool,
+                 r, s, position_set, rows, gathered)
+
+
+def _reft(entry, h, seg_start, seg_adapter, seg_prompt_len, A_pool, B_pool, b_pool, r, s,
+          position_set, rows, gathered):
     ha, dt_h = _as_typed(h)
     d = ha.shape[1]
     ss, sa, sp = _i32(seg_start), _i32(seg_adapter), _i32(seg_prompt_len)
@@ -229,7 +244,7 @@ def direft(h, seg_start, seg_adapter, seg_prompt_len, A_pool, B_pool, b_pool, r,
         assert rows_arr.size == 0 or (rows_arr.min() >= 0 and rows_arr.max() < T)
         rows_p, count = _ptr(rows_arr, ctypes.c_int64), len(rows_arr)
     out = np.empty((count, d), dtype=np.float64)
-    rc = lib.ora_direft_batch(_ptr(out, ctypes.c_double), rows_p, count,
+    rc = entry(_ptr(out, ctypes.c_double), rows_p, count,
                               ha.ctypes.data, d, T, d,
                               _ptr(ss, ctypes.c_int32), _ptr(sa, ctypes.c_int32),
                               _ptr(sp, ctypes.c_int32), S,

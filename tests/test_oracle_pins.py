@@ -3,7 +3,8 @@
 Each test checks ``oracle/preft_oracle.c`` against what the paper and the mathematics fix:
 a hand-worked example (tests/golden/hand_example.txt), the merged dense operator computed
 by a library matmul, a brute-force block operator built in pure Python, the identity and
-position-set invariants of Eq. 1/4, and algebraic properties of Eq. 2/3.  The last test
+position-set invariants of Eq. 1/4, algebraic properties of Eq. 2/3, and for LoReFT (App. C.2)
+a hand example, its zero-delta initialisation, its reduction to DiReFT and its subspace property.  The last test
 shows that plausible mistakes (dropped prefactor, transposed operand, unscaled or missing
 bias, off-by-one position set) would fail these pins.
 """
@@ -356,6 +357,86 @@ def test_row_selection_matches_full_run():
     got = ora.direft(h[torch.from_numpy(rows)], tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, list(dp.A),
                      list(dp.B), list(dp.b), dp.r, 1.0, ora.PROMPT_ONLY, rows=rows, gathered=True)
     assert np.array_equal(got, full[rows])
+
+
+# ---------------------------------------------------------------------------------------
+# 7b. LoReFT (App. C.2): hand example, zero-delta initialisation, reduction to DiReFT, and the
+#     subspace property that defines it when R has orthonormal rows
+# ---------------------------------------------------------------------------------------
+def _loreft(tab, W, R, b, h, s=1.0, mode=ora.PROMPT_ONLY, rows=None):
+    return ora.loreft(h, tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, list(W), list(R),
+                      None if b is None else list(b), W[0].shape[0], s, mode, rows=rows)
+
+
+def test_loreft_hand_worked_example():
+    g = _read_gold()
+    tab = _one_seg(1)
+    out = _loreft(tab, [g["loreft_W"].reshape(2, 3)], [g["loreft_R"].reshape(2, 3)], [g["loreft_b"]],
+                  g["loreft_h"][None], float(g["loreft_s"][0]))
+    assert np.array_equal(out[0], g["loreft_out"])
+
+
+def test_loreft_identity_at_its_initialisation_and_on_rows_outside_the_set():
+    tab, pool, h = _rand_direft_case(21)
+    R = [m.numpy() for m in pool.B]
+    # W = R, b = 0 (the zero-delta initialisation of App. C.1): exact identity
+    out = _loreft(tab, R, R, [np.zeros(pool.r)] * pool.N, h, s=0.7, mode=ora.ALL_POSITIONS)
+    assert np.array_equal(out, h.numpy())
+    # rows outside the position set keep their value whatever the weights
+    W = [m.numpy() for m in pool.A]
+    out = _loreft(tab, W, R, list(pool.b), h, s=0.7)
+    owner = ora.positions(tab.T, tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, pool.N, ora.PROMPT_ONLY)
+    assert np.array_equal(out[owner < 0], h.numpy()[owner < 0])
+    assert not np.array_equal(out[owner >= 0], h.numpy()[owner >= 0])
+
+
+def test_loreft_is_direft_with_the_difference_factor():
+    # integer-valued factors: W - R is exact, so the two oracles must agree to rounding order
+    rng = RNG(22)
+    tab = wl.random_segments(rng, 10, 3, 7)
+    d, r, N = 12, 3, 3
+    W = [rng.integers(-4, 5, size=(r, d)).astype(np.float64) for _ in range(N)]
+    R = [rng.integers(-4, 5, size=(r, d)).astype(np.float64) for _ in range(N)]
+    b = [rng.integers(-4, 5, size=r).astype(np.float64) for _ in range(N)]
+    h = rng.integers(-4, 5, size=(tab.T, d)).astype(np.float64)
+    got = _loreft(tab, W, R, b, h, s=0.5, mode=ora.ALL_POSITIONS)
+    want = ora.direft(h, tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, [w - q for w, q in zip(W, R)], R, b,
+                      r, 0.5, ora.ALL_POSITIONS)
+    assert np.array_equal(got, want)             # small integers: every sum is exact in fp64
+
+
+@pytest.mark.parametrize("s", [1.0, 0.25])
+def test_loreft_subspace_property_with_orthonormal_rows(s):
+    # R R^T = I: the component of h in the row space of R becomes (1-s) R h + s (W h + b) and the
+    # orthogonal complement is untouched; for s = 1 the projection is replaced by W h + b outright
+    rng = RNG(23)
+    d, r, T = 40, 5, 9
+    R = np.linalg.qr(rng.standard_normal((d, r)))[0].T
+    W = rng.standard_normal((r, d))
+    b = rng.standard_normal(r)
+    h = rng.standard_normal((T, d))
+    out = _loreft(_one_seg(T), [W], [R], [b], h, s=s)
+    np.testing.assert_allclose(out @ R.T, (1 - s) * (h @ R.T) + s * (h @ W.T + b), rtol=1e-12, atol=1e-12)
+    P = np.eye(d) - R.T @ R
+    np.testing.assert_allclose(out @ P, h @ P, rtol=1e-12, atol=1e-12)
+
+
+def test_loreft_plausible_mistakes_would_fail_the_pins():
+    g = _read_gold()
+    W, R = g["loreft_W"].reshape(2, 3), g["loreft_R"].reshape(2, 3)
+    b, h, s = g["loreft_b"], g["loreft_h"], float(g["loreft_s"][0])
+    want = g["loreft_out"]
+    assert np.array_equal(h + s * (R.T @ (W @ h + b - R @ h)), want)
+    wrong = {
+        "rotation term added": h + s * (R.T @ (W @ h + b + R @ h)),
+        "rotation term missing": h + s * (R.T @ (W @ h + b)),
+        "W in the write-back": h + s * (W.T @ (W @ h + b - R @ h)),
+        "bias outside the prefactor": h + s * (R.T @ (W @ h - R @ h)) + R.T @ b,
+        "dropped prefactor": h + R.T @ (W @ h + b - R @ h),
+        "W and R swapped": h + s * (W.T @ (R @ h + b - W @ h)),
+    }
+    for name, w in wrong.items():
+        assert not np.allclose(w, want), name
 
 
 # ---------------------------------------------------------------------------------------
