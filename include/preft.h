@@ -149,6 +149,39 @@ int preft_direft_apply(void *h, int64_t ldh, int32_t T, int32_t d,
                        void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * LoReFT (paper App. C.2): h[t, :] += scale * R_i^T (W_i h[t, :] + b_i - R_i h[t, :]), with
+ * W_i, R_i in R^{rank x d} (R_i the materialised rotation) and b_i in R^rank.
+ *
+ * The rotation enters twice, once per layout the kernels stream (rank-major for the
+ * projection, column-major for the write-back), and the projection needs only W_i - R_i.  Like
+ * the derived tensors the paper caches outside its compiled region (App. D.3), these are
+ * computed once per weight update, not per call:
+ *
+ * preft_loreft_prepare writes, for one adapter,
+ *   D  [rank, d]  = W - R, rounded once (to nearest even) to the storage type,
+ *   Rt [d, rank]  = R transposed,
+ * from W, R [rank, d] (all device pointers, 16-byte aligned, contiguous; D and Rt are
+ * caller-owned and must not overlap W or R).  In bf16 the rounding of W - R is exact whenever
+ * W and R are within a factor two of each other elementwise (always at the zero-delta
+ * initialisation W = R and close to it); in general it perturbs each element of D by at most
+ * 2^-9 relative.
+ *
+ * preft_loreft_apply then computes h[t, :] += scale * Rt_i (D_i h[t, :] + b_i) on the active
+ * rows; its arguments, layouts and rules are those of preft_direft_apply with W1_pool = D_pool
+ * and W2t_pool = Rt_pool.
+ */
+int preft_loreft_prepare(void *D, void *Rt, const void *W, const void *R,
+                         int32_t d, int32_t rank, int dtype, void *stream);
+
+int preft_loreft_apply(void *h, int64_t ldh, int32_t T, int32_t d,
+                       const int32_t *seg_start, const int32_t *seg_adapter,
+                       const int32_t *seg_prefill_len, int32_t S,
+                       const void *const *D_pool, const void *const *Rt_pool,
+                       const void *const *b_pool, int32_t N,
+                       int32_t rank, float scale, int dtype, int mode,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Copies the schedule counters of a workspace to the host: counts[0] = multi-row work
  * units, counts[1] = single rows handled by the per-row path, counts[2] = active rows.
  * `counts` is a host pointer to 3 int32.  This call synchronises `stream`; it is meant

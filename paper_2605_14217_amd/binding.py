@@ -25,7 +25,7 @@ PREFT_KNOB_ROWBLOCKS = 2
 
 # every symbol include/preft.h declares
 ABI_SYMBOLS = ("preft_workspace_bytes", "preft_schedule", "preft_lora_apply", "preft_direft_apply",
-               "preft_schedule_counts", "preft_set_knob", "preft_strerror", "preft_version")
+               "preft_loreft_prepare", "preft_loreft_apply", "preft_schedule_counts", "preft_set_knob", "preft_strerror", "preft_version")
 
 _lib = None
 
@@ -59,6 +59,10 @@ def load_library(path: Optional[str] = None):
     lib.preft_direft_apply.restype = c.c_int
     lib.preft_direft_apply.argtypes = [vp, i64, i32, i32, vp, vp, vp, i32, vp, vp, vp, i32, i32,
                                        c.c_float, c.c_int, c.c_int, vp, sz, vp]
+    lib.preft_loreft_prepare.restype = c.c_int
+    lib.preft_loreft_prepare.argtypes = [vp, vp, vp, vp, i32, i32, c.c_int, vp]
+    lib.preft_loreft_apply.restype = c.c_int
+    lib.preft_loreft_apply.argtypes = lib.preft_direft_apply.argtypes
     lib.preft_schedule_counts.restype = c.c_int
     lib.preft_schedule_counts.argtypes = [vp, c.POINTER(i32), vp]
     lib.preft_set_knob.restype = c.c_int
@@ -175,21 +179,48 @@ def preft_lora_apply(y: torch.Tensor, x: torch.Tensor, seg_start, seg_adapter, s
     _check(rc, "preft_lora_apply")
 
 
+def preft_loreft_prepare(D: torch.Tensor, Rt: torch.Tensor, W: torch.Tensor, R: torch.Tensor, stream=None) -> None:
+    """Derived LoReFT factors of one adapter: D = W - R ([rank, d]) and Rt = R^T ([d, rank]),
+    written into the caller's contiguous device tensors."""
+    rank, d = int(W.shape[0]), int(W.shape[1])
+    for t, shape, name in ((D, (rank, d), "D"), (Rt, (d, rank), "Rt"), (W, (rank, d), "W"), (R, (rank, d), "R")):
+        if tuple(t.shape) != shape or not t.is_contiguous() or not t.is_cuda or t.dtype != W.dtype:
+            raise ValueError(f"{name}: need a contiguous device tensor of shape {shape} and the dtype of W")
+    rc = load_library().preft_loreft_prepare(D.data_ptr(), Rt.data_ptr(), W.data_ptr(), R.data_ptr(), d, rank,
+                                             _dtype_code(W), _stream(stream))
+    _check(rc, "preft_loreft_prepare")
+
+
+def preft_loreft_apply(h: torch.Tensor, seg_start, seg_adapter, seg_prefill_len,
+                       D_pool: torch.Tensor, Rt_pool: torch.Tensor, b_pool: Optional[torch.Tensor],
+                       rank: int, scale: float, mode: int, workspace: torch.Tensor, stream=None) -> None:
+    """h[t] += scale * R_i^T (W_i h[t] + b_i - R_i h[t]) on active rows, in place, from the derived
+    factors of preft_loreft_prepare (pointer tables of D = W - R and of R^T)."""
+    _reft_apply("preft_loreft_apply", h, seg_start, seg_adapter, seg_prefill_len, D_pool, Rt_pool, b_pool, rank,
+                scale, mode, workspace, stream)
+
+
 def preft_direft_apply(h: torch.Tensor, seg_start, seg_adapter, seg_prefill_len,
                        W1_pool: torch.Tensor, W2t_pool: torch.Tensor, b_pool: Optional[torch.Tensor],
                        rank: int, scale: float, mode: int, workspace: torch.Tensor, stream=None) -> None:
     """h[t] += scale * W2_i^T (W1_i h[t] + b_i) on active rows, in place.  W1_pool: [rank, d]
     matrices; W2t_pool: [d, rank] matrices (W2 transposed); b_pool: [rank] vectors or None."""
+    _reft_apply("preft_direft_apply", h, seg_start, seg_adapter, seg_prefill_len, W1_pool, W2t_pool, b_pool, rank,
+                scale, mode, workspace, stream)
+
+
+def _reft_apply(entry: str, h, seg_start, seg_adapter, seg_prefill_len, W1_pool, W2t_pool, b_pool, rank, scale,
+                mode, workspace, stream) -> None:
     hp, ldh, T, d = _matrix(h, "h")
     S = int(seg_adapter.numel())
     N = int(W1_pool.numel())
     if W2t_pool.numel() != N or (b_pool is not None and b_pool.numel() != N):
         raise ValueError("pools must be pointer tables of equal length")
-    rc = load_library().preft_direft_apply(
+    rc = getattr(load_library(), entry)(
         hp, ldh, T, d,
         _table(seg_start, "seg_start", S + 1), _table(seg_adapter, "seg_adapter", S),
         _table(seg_prefill_len, "seg_prefill_len", S), S,
         W1_pool.data_ptr(), W2t_pool.data_ptr(), None if b_pool is None else b_pool.data_ptr(), N,
         int(rank), float(scale), _dtype_code(h), int(mode),
         workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream))
-    _check(rc, "preft_direft_apply")
+    _check(rc, entry)

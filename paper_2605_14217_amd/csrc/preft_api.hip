@@ -262,6 +262,20 @@ int launch_apply(const ApplyArgs &a, int64_t S, int dtype, hipStream_t stream)
     return check_launch();
 }
 
+// LoReFT derived factors of one adapter (App. C.2): D = W - R in the storage type, Rt = R^T.
+template <typename E>
+__global__ __launch_bounds__(256) void loreft_prepare_kernel(void *D, void *Rt, const void *W, const void *R,
+                                                             int32_t d, int32_t rank)
+{
+    const int64_t n = (int64_t)d * rank;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t k = i / d, j = i - k * d;
+        const float w = Elem<E>::load1(as_global(W), i), q = Elem<E>::load1(as_global(R), i);
+        Elem<E>::store1(as_global(D), i, w - q);
+        Elem<E>::store1(as_global(Rt), j * rank + k, q);
+    }
+}
+
 int check_matrix(const void *p, int64_t ld, int32_t width, int dtype)
 {
     const int per16 = dtype == PREFT_BF16 ? 8 : 4;
@@ -320,6 +334,42 @@ int preft_lora_apply(void *y, int64_t ldy, const void *x, int64_t ldx, int32_t T
     a.A_pool = A_pool; a.Bt_pool = B_pool; a.bias_pool = nullptr; a.N = N; a.rank = rank; a.scale = scale;
     a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.gtiles = v.gtiles; a.gathered_only = 0;
     return launch_apply<false>(a, S, dtype, st);
+}
+
+int preft_loreft_prepare(void *D, void *Rt, const void *W, const void *R, int32_t d, int32_t rank, int dtype,
+                         void *stream)
+{
+    if (dtype != PREFT_F32 && dtype != PREFT_BF16) return PREFT_EINVAL;
+    if (!D || !Rt || !W || !R || d <= 0) return PREFT_EINVAL;
+    if (rank < 1 || rank > PREFT_MAX_RANK) return PREFT_EUNSUPPORTED;
+    if (!aligned16(D) || !aligned16(Rt) || !aligned16(W) || !aligned16(R)) return PREFT_EALIGN;
+    {   // outputs must not overlap the inputs or each other
+        const size_t bytes = (size_t)d * rank * (dtype == PREFT_BF16 ? 2 : 4);
+        const char *p[4] = {reinterpret_cast<const char *>(D), reinterpret_cast<const char *>(Rt),
+                            reinterpret_cast<const char *>(W), reinterpret_cast<const char *>(R)};
+        for (int a = 0; a < 2; ++a)
+            for (int b = a + 1; b < 4; ++b)
+                if (p[a] < p[b] + bytes && p[b] < p[a] + bytes) return PREFT_EINVAL;
+    }
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const int64_t n = (int64_t)d * rank;
+    const unsigned grid = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+    if (dtype == PREFT_BF16)
+        hipLaunchKernelGGL((loreft_prepare_kernel<bf16_tag>), dim3(grid), dim3(256), 0, st, D, Rt, W, R, d, rank);
+    else
+        hipLaunchKernelGGL((loreft_prepare_kernel<float>), dim3(grid), dim3(256), 0, st, D, Rt, W, R, d, rank);
+    return check_launch();
+}
+
+int preft_loreft_apply(void *h, int64_t ldh, int32_t T, int32_t d, const int32_t *seg_start,
+                       const int32_t *seg_adapter, const int32_t *seg_prefill_len, int32_t S,
+                       const void *const *D_pool, const void *const *Rt_pool, const void *const *b_pool,
+                       int32_t N, int32_t rank, float scale, int dtype, int mode, void *workspace, size_t bytes,
+                       void *stream)
+{
+    // h += s R^T (W h + b - R h) = s Rt (D h + b): the in-place kernels with the derived factors
+    return preft_direft_apply(h, ldh, T, d, seg_start, seg_adapter, seg_prefill_len, S, D_pool, Rt_pool, b_pool, N,
+                              rank, scale, dtype, mode, workspace, bytes, stream);
 }
 
 int preft_direft_apply(void *h, int64_t ldh, int32_t T, int32_t d, const int32_t *seg_start,

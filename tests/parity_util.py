@@ -171,3 +171,31 @@ def run_direft_case(tab: wl.SegmentTable, pool: wl.DireftPool, h0: torch.Tensor,
     worst = compare(h, h0, want, row_adapter, dtype, rows=rows)
     assert counts[2] == int((row_adapter >= 0).sum())
     return worst, counts
+
+
+def run_loreft_case(tab: wl.SegmentTable, W, R, b, h0: torch.Tensor, dtype: str, scale: float, all_tokens: bool,
+                    pad_cols=0):
+    """W, R: lists of [r,d] device tensors, b: list of [r] or None.  Derived factors come from
+    preft_loreft_prepare; the oracle sees W, R and b themselves."""
+    N, r, d = len(W), int(W[0].shape[0]), int(W[0].shape[1])
+    T = tab.T
+    mode = preft.PREFT_ALL_TOKENS if all_tokens else preft.PREFT_PREFILL_ONLY
+    ss, sa, sp = dev_tables(tab)
+    D = [torch.full_like(W[i], float("nan")) for i in range(N)]
+    Rt = [torch.full((d, r), float("nan"), dtype=W[i].dtype, device=W[i].device) for i in range(N)]
+    for i in range(N):
+        preft.preft_loreft_prepare(D[i], Rt[i], W[i], R[i])
+    hbuf, h = padded(h0, pad_cols, 7.0)
+    ws = preft.new_workspace(T, tab.S)
+    preft.preft_loreft_apply(h, ss, sa, sp, preft.pointer_table(D), preft.pointer_table(Rt),
+                             None if b is None else preft.pointer_table(b), r, scale, mode, ws)
+    torch.cuda.synchronize()
+    for i in range(N):         # the derived factors themselves: one rounding of the exact difference, exact transpose
+        assert torch.equal(bits(D[i]), bits((W[i].double() - R[i].double()).to(W[i].dtype)))
+        assert torch.equal(bits(Rt[i]), bits(R[i].t().contiguous()))
+    check_guards(hbuf, T, d, 7.0)
+    pos = ora.ALL_POSITIONS if all_tokens else ora.PROMPT_ONLY
+    row_adapter = ora.positions(T, tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, N, pos)
+    want = ora.loreft(h0.cpu(), tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, [w.cpu() for w in W],
+                      [q.cpu() for q in R], None if b is None else [v.cpu() for v in b], r, scale, pos)
+    return compare(h, h0, want, row_adapter, dtype)

@@ -402,3 +402,72 @@ def test_fcfs_trace_steps_match_the_oracle():
             assert counts[2] == (tab.T if all_tokens else int(tab.seg_prefill_len.sum()))
             run_direft_case(tab, dpool, y0, "bf16", 1.0, all_tokens)
     assert prompts == 14 and steps > 14
+
+
+# ---------------------------------------------------------------------------------------
+# LoReFT (App. C.2) through its derived factors
+# ---------------------------------------------------------------------------------------
+def _loreft_weights(N, r, d, dtype, seed, spread):
+    """R with orthonormal rows (before rounding to the storage type); W = R + spread * noise."""
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    td = wl.torch_dtype(dtype)
+    W, R, b = [], [], []
+    for _ in range(N):
+        q = torch.linalg.qr(torch.randn(d, r, generator=g, device="cuda", dtype=torch.float32))[0].t().contiguous()
+        noise = torch.randn(r, d, generator=g, device="cuda", dtype=torch.float32) / d ** 0.5
+        R.append(q.to(td))
+        W.append((q + spread * noise).to(td))
+        b.append(torch.randn(r, generator=g, device="cuda", dtype=torch.float32).to(td))
+    return W, R, b
+
+
+@pytest.mark.parametrize("dtype,r,d,spread", [("bf16", 4, 512, 1.0), ("bf16", 16, 1000, 1.0), ("bf16", 8, 4096, 0.05),
+                                              ("bf16", 3, 264, 1.0), ("f32", 4, 512, 1.0), ("bf16", 64, 1024, 1.0)])
+def test_loreft_matches_the_oracle(dtype, r, d, spread):
+    from parity_util import run_loreft_case
+    N = 5
+    rng = np.random.Generator(np.random.PCG64(90 + r))
+    tab = wl.random_segments(rng, 40, N + 1, 70)
+    W, R, b = _loreft_weights(N, r, d, dtype, seed=91, spread=spread)
+    h0 = wl.activations(tab.T, d, dtype, device="cuda", seed=92)
+    for all_tokens in (False, True):
+        worst = run_loreft_case(tab, W, R, b, h0, dtype, 1.0 / r ** 0.5, all_tokens, pad_cols=8)
+        print(f"  loreft {dtype} r={r} d={d} all_tokens={all_tokens} worst {worst:.2e}")
+
+
+def test_loreft_is_the_identity_at_its_initialisation():
+    """W = R, b = 0 (zero-delta initialisation, App. C.1): the derived difference factor is exactly
+    zero and every row keeps its bits."""
+    from parity_util import bits, dev_tables
+    N, r, d = 3, 8, 1024
+    W, R, _ = _loreft_weights(N, r, d, "bf16", seed=93, spread=0.0)
+    rng = np.random.Generator(np.random.PCG64(94))
+    tab = wl.random_segments(rng, 20, N, 50)
+    h0 = wl.activations(tab.T, d, "bf16", device="cuda", seed=95)
+    h = h0.clone()
+    D = [torch.empty_like(w) for w in W]
+    Rt = [torch.empty((d, r), dtype=w.dtype, device="cuda") for w in W]
+    for i in range(N):
+        preft.preft_loreft_prepare(D[i], Rt[i], W[i], R[i])
+    ss, sa, sp = dev_tables(tab)
+    ws = preft.new_workspace(tab.T, tab.S)
+    zero_b = [torch.zeros(r, dtype=torch.bfloat16, device="cuda") for _ in range(N)]
+    preft.preft_loreft_apply(h, ss, sa, sp, preft.pointer_table(D), preft.pointer_table(Rt),
+                             preft.pointer_table(zero_b), r, 0.7, preft.PREFT_ALL_TOKENS, ws)
+    torch.cuda.synchronize()
+    assert all(int(torch.count_nonzero(m)) == 0 for m in D)
+    assert torch.equal(bits(h), bits(h0))
+
+
+def test_loreft_prepare_rejects_bad_arguments():
+    lib = preft.load_library()
+    W = torch.zeros(4, 64, dtype=torch.bfloat16, device="cuda")
+    R, D, Rt = torch.zeros_like(W), torch.zeros_like(W), torch.zeros(64, 4, dtype=torch.bfloat16, device="cuda")
+    call = lambda D_, Rt_, W_, R_, d, r, dt: lib.preft_loreft_prepare(D_, Rt_, W_, R_, d, r, dt, None)
+    assert call(D.data_ptr(), Rt.data_ptr(), W.data_ptr(), R.data_ptr(), 64, 4, preft.PREFT_BF16) == 0
+    assert call(None, Rt.data_ptr(), W.data_ptr(), R.data_ptr(), 64, 4, preft.PREFT_BF16) == -1
+    assert call(D.data_ptr(), Rt.data_ptr(), W.data_ptr(), R.data_ptr(), 64, 4, 7) == -1
+    assert call(D.data_ptr(), Rt.data_ptr(), W.data_ptr(), R.data_ptr(), 64, 129, preft.PREFT_BF16) == -2
+    assert call(D.data_ptr() + 2, Rt.data_ptr(), W.data_ptr(), R.data_ptr(), 64, 4, preft.PREFT_BF16) == -3
+    assert call(W.data_ptr(), Rt.data_ptr(), W.data_ptr(), R.data_ptr(), 64, 4, preft.PREFT_BF16) == -1   # D aliases W
+    torch.cuda.synchronize()
