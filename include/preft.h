@@ -38,8 +38,9 @@
  * in place between calls.  Only the slots named by active segments are dereferenced.
  *
  * Ownership / execution: every pointer is caller-owned device memory unless marked
- * "host".  The library allocates nothing and keeps no state between calls (apart from the
- * benchmarking knobs of preft_set_knob).  Calls only
+ * "host".  The schedule and apply calls allocate nothing and keep no state between calls
+ * (apart from the benchmarking knobs of preft_set_knob); only the optional slot manager at the
+ * end of this header owns memory.  Calls only
  * enqueue work on `stream` (a hipStream_t passed as void*, NULL = the default stream) and
  * return; they never synchronise.  All launch shapes depend on host-visible sizes only,
  * so a call may be captured into a HIP graph.
@@ -78,7 +79,8 @@ enum {
     PREFT_EALIGN       = -3,   /* base pointer or row stride not 16-byte aligned, or a   */
                                /* width that is not a multiple of 16 bytes               */
     PREFT_EWORKSPACE   = -4,   /* workspace missing, misaligned or too small             */
-    PREFT_EHIP         = -5    /* the HIP runtime refused a launch                       */
+    PREFT_EHIP         = -5,   /* the HIP runtime refused a launch, copy or allocation   */
+    PREFT_ECAPACITY    = -6    /* slot manager: more distinct adapters than slots        */
 };
 
 #define PREFT_MAX_RANK 128
@@ -180,6 +182,51 @@ int preft_loreft_apply(void *h, int64_t ldh, int32_t T, int32_t d,
                        const void *const *b_pool, int32_t N,
                        int32_t rank, float scale, int dtype, int mode,
                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Adapter slot manager (paper Sec. 4, paged setting: 512 adapters of which 32 are on the GPU;
+ * App. E.2: the active set in GPU memory, the catalogue in host memory; App. D.4: weights at
+ * stable addresses are refreshed in place so the next launch or graph replay sees them).
+ *
+ * A manager owns: a pinned host store with one record per adapter (n_parts matrices of
+ * part_bytes[p] bytes each, e.g. {A, B} for LoRA or {W1, W2t, b} for DiReFT), a device slab
+ * of n_slots records at addresses that never change, and per part a device table of n_slots
+ * pointers (preft_slots_pool) to pass as A_pool / B_pool / ... with N = n_slots.  The apply
+ * calls then take SLOT ids in seg_adapter: before a batch, preft_slots_acquire maps the
+ * batch's adapter ids to slot ids, bringing missing adapters in (least recently used slot
+ * first, never a slot the same call names) with asynchronous host-to-device copies on
+ * `stream`.  Work that uses the slots must run on the same stream, or be ordered after it
+ * by the caller.  These calls are host-side bookkeeping and copies: no kernel.
+ *
+ * preft_slots_create    allocates the three areas (the only allocating call of the library;
+ *                       n_slots is clamped to n_adapters).  n_parts == 0 makes a manager
+ *                       without memory that only does the residency bookkeeping.
+ * preft_slots_store     copies part `part` of adapter `adapter` from host memory `src`
+ *                       (part_bytes[part] bytes) into the store; if the adapter is resident
+ *                       its slot is refreshed in place on `stream` (the call first waits
+ *                       for `stream`, so a pending copy never reads a half-written record).
+ * preft_slots_acquire   adapter_ids[n] (host) -> slot_ids[n] (host); ids outside
+ *                       [0, n_adapters) map to -1 ("no adapter").  PREFT_ECAPACITY if the call
+ *                       names more distinct adapters than there are slots (the manager stays
+ *                       consistent; slot_ids past the failing entry are -1).
+ * preft_slots_pool      device array of n_slots device pointers for part `part`, or NULL.
+ * preft_slots_resident  slot of an adapter, or -1.
+ * preft_slots_stats     stats[5] (host) = {hits, misses, evictions, bytes copied, n_slots};
+ *                       a hit or miss is counted once per distinct adapter and acquire call.
+ * preft_slots_destroy   frees everything; the caller makes sure no work still uses the slots.
+ * Not thread-safe: one thread drives a manager.
+ */
+typedef struct preft_slots preft_slots_t;
+
+int preft_slots_create(preft_slots_t **out, int32_t n_adapters, int32_t n_slots, int32_t n_parts,
+                       const size_t *part_bytes);
+int preft_slots_destroy(preft_slots_t *m);
+int preft_slots_store(preft_slots_t *m, int32_t adapter, int32_t part, const void *src, void *stream);
+int preft_slots_acquire(preft_slots_t *m, const int32_t *adapter_ids, int32_t n, int32_t *slot_ids,
+                        void *stream);
+const void *const *preft_slots_pool(preft_slots_t *m, int32_t part);
+int32_t preft_slots_resident(const preft_slots_t *m, int32_t adapter);
+int preft_slots_stats(const preft_slots_t *m, int64_t *stats);
 
 /*
  * Copies the schedule counters of a workspace to the host: counts[0] = multi-row work

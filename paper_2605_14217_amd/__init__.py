@@ -11,5 +11,6 @@ from .binding import (  # noqa: F401
     PreftError, load_library, pointer_table, preft_direft_apply, preft_lora_apply, preft_loreft_apply,
     preft_loreft_prepare, preft_schedule,
     preft_schedule_counts, preft_set_knob, preft_strerror, preft_version, preft_workspace_bytes,
-    new_workspace,
+    new_workspace, preft_slots_create, preft_slots_destroy, preft_slots_store, preft_slots_acquire,
+    preft_slots_pool, preft_slots_resident, preft_slots_stats, PREFT_ECAPACITY,
 )

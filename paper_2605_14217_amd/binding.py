@@ -19,13 +19,16 @@ PREFT_ALL_TOKENS = 1
 PREFT_SCHEDULE_READY = 0x100
 PREFT_F32 = 0
 PREFT_BF16 = 1
+PREFT_ECAPACITY = -6
 PREFT_KNOB_VARIANT = 0
 PREFT_KNOB_WAVES = 1
 PREFT_KNOB_ROWBLOCKS = 2
 
 # every symbol include/preft.h declares
 ABI_SYMBOLS = ("preft_workspace_bytes", "preft_schedule", "preft_lora_apply", "preft_direft_apply",
-               "preft_loreft_prepare", "preft_loreft_apply", "preft_schedule_counts", "preft_set_knob", "preft_strerror", "preft_version")
+               "preft_loreft_prepare", "preft_loreft_apply", "preft_slots_create", "preft_slots_destroy",
+               "preft_slots_store", "preft_slots_acquire", "preft_slots_pool", "preft_slots_resident",
+               "preft_slots_stats", "preft_schedule_counts", "preft_set_knob", "preft_strerror", "preft_version")
 
 _lib = None
 
@@ -63,6 +66,20 @@ def load_library(path: Optional[str] = None):
     lib.preft_loreft_prepare.argtypes = [vp, vp, vp, vp, i32, i32, c.c_int, vp]
     lib.preft_loreft_apply.restype = c.c_int
     lib.preft_loreft_apply.argtypes = lib.preft_direft_apply.argtypes
+    lib.preft_slots_create.restype = c.c_int
+    lib.preft_slots_create.argtypes = [c.POINTER(vp), i32, i32, i32, c.POINTER(sz)]
+    lib.preft_slots_destroy.restype = c.c_int
+    lib.preft_slots_destroy.argtypes = [vp]
+    lib.preft_slots_store.restype = c.c_int
+    lib.preft_slots_store.argtypes = [vp, i32, i32, vp, vp]
+    lib.preft_slots_acquire.restype = c.c_int
+    lib.preft_slots_acquire.argtypes = [vp, c.POINTER(i32), i32, c.POINTER(i32), vp]
+    lib.preft_slots_pool.restype = vp
+    lib.preft_slots_pool.argtypes = [vp, i32]
+    lib.preft_slots_resident.restype = i32
+    lib.preft_slots_resident.argtypes = [vp, i32]
+    lib.preft_slots_stats.restype = c.c_int
+    lib.preft_slots_stats.argtypes = [vp, c.POINTER(i64)]
     lib.preft_schedule_counts.restype = c.c_int
     lib.preft_schedule_counts.argtypes = [vp, c.POINTER(i32), vp]
     lib.preft_set_knob.restype = c.c_int
@@ -114,6 +131,21 @@ def pointer_table(mats: Sequence[torch.Tensor]) -> torch.Tensor:
         if not m.is_cuda or not m.is_contiguous():
             raise ValueError("pool slots must be contiguous device tensors")
     return torch.tensor([m.data_ptr() for m in mats], dtype=torch.int64, device=dev)
+
+
+class PoolRef:
+    """A pointer table that lives in library-owned device memory (the slot manager's): quacks like
+    the int64 tensor of pointer_table as far as the apply calls need."""
+    dtype = torch.int64
+
+    def __init__(self, address: int, n: int):
+        self._address, self._n = int(address), int(n)
+
+    def data_ptr(self) -> int:
+        return self._address
+
+    def numel(self) -> int:
+        return self._n
 
 
 def preft_version() -> int:
@@ -224,3 +256,58 @@ def _reft_apply(entry: str, h, seg_start, seg_adapter, seg_prefill_len, W1_pool,
         int(rank), float(scale), _dtype_code(h), int(mode),
         workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, entry)
+
+
+# ----------------------------------------------------------------------------------------
+# adapter slot manager (argument marshalling only; the handle is the library's opaque pointer)
+# ----------------------------------------------------------------------------------------
+def preft_slots_create(n_adapters: int, n_slots: int, part_bytes) -> int:
+    """Returns the manager handle.  part_bytes: bytes of each matrix of one adapter ([] = bookkeeping only)."""
+    handle = ctypes.c_void_p()
+    arr = (ctypes.c_size_t * max(len(part_bytes), 1))(*[int(b) for b in part_bytes])
+    _check(load_library().preft_slots_create(ctypes.byref(handle), int(n_adapters), int(n_slots), len(part_bytes), arr),
+           "preft_slots_create")
+    return handle.value
+
+
+def preft_slots_destroy(handle: int) -> None:
+    _check(load_library().preft_slots_destroy(handle), "preft_slots_destroy")
+
+
+def preft_slots_store(handle: int, adapter: int, part: int, src: torch.Tensor, stream=None) -> None:
+    """src: contiguous CPU tensor holding the matrix."""
+    if src.is_cuda or not src.is_contiguous():
+        raise ValueError("src: need a contiguous CPU tensor")
+    _check(load_library().preft_slots_store(handle, int(adapter), int(part), src.data_ptr(),
+                                            _stream(stream) if torch.cuda.is_available() else None),
+           "preft_slots_store")
+
+
+def preft_slots_acquire(handle: int, adapter_ids, stream=None):
+    """adapter_ids: sequence of ints -> list of slot ids (-1 = no adapter)."""
+    n = len(adapter_ids)
+    ids = (ctypes.c_int32 * max(n, 1))(*[int(a) for a in adapter_ids])
+    out = (ctypes.c_int32 * max(n, 1))()
+    _check(load_library().preft_slots_acquire(handle, ids, n, out,
+                                              _stream(stream) if torch.cuda.is_available() else None),
+           "preft_slots_acquire")
+    return [int(out[i]) for i in range(n)]
+
+
+def preft_slots_pool(handle: int, part: int) -> PoolRef:
+    """Pointer table of part `part` (n_slots entries), usable as a pool argument of the apply calls."""
+    address = load_library().preft_slots_pool(handle, int(part))
+    if not address:
+        raise PreftError(-1, "preft_slots_pool")
+    return PoolRef(address, preft_slots_stats(handle)["n_slots"])
+
+
+def preft_slots_resident(handle: int, adapter: int) -> int:
+    return int(load_library().preft_slots_resident(handle, int(adapter)))
+
+
+def preft_slots_stats(handle: int) -> dict:
+    out = (ctypes.c_int64 * 5)()
+    _check(load_library().preft_slots_stats(handle, out), "preft_slots_stats")
+    return dict(hits=int(out[0]), misses=int(out[1]), evictions=int(out[2]), bytes_copied=int(out[3]),
+                n_slots=int(out[4]))

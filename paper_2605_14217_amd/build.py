@@ -17,7 +17,7 @@ HIPCC_FLAGS = [
 
 
 def sources():
-    return [os.path.join(CSRC, "preft_api.hip")]
+    return [os.path.join(CSRC, "preft_api.hip"), os.path.join(CSRC, "slots.hip")]
 
 
 def build_library(verbose: bool = False) -> str:

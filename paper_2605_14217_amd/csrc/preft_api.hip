@@ -429,7 +429,8 @@ const char *preft_strerror(int code)
     case PREFT_EUNSUPPORTED: return "unsupported rank (must be 1..128)";
     case PREFT_EALIGN:       return "pointer, width or row stride not a multiple of 16 bytes";
     case PREFT_EWORKSPACE:   return "workspace missing, misaligned or smaller than preft_workspace_bytes(T, S)";
-    case PREFT_EHIP:         return "HIP runtime error at launch";
+    case PREFT_EHIP:         return "HIP runtime error (launch, copy or allocation)";
+    case PREFT_ECAPACITY:    return "more distinct adapters in one batch than the slot manager has slots";
     default:                 return "unknown preft error code";
     }
 }

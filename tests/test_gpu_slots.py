@@ -1,0 +1,113 @@
+"""Adapter slot manager on the GPU: a catalogue larger than the resident set, served batch by batch
+through stable device slots, must give what the oracle gives with every adapter at hand."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_14217_amd as preft
+from oracle import preft_oracle as ora
+from paper_2605_14217_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def _bytes(t):
+    return t.numel() * t.element_size()
+
+
+def test_paged_lora_matches_the_oracle_and_refreshes_in_place():
+    from parity_util import bits, compare, dev_tables
+    N, M, r, d_in, d_out = 12, 4, 16, 512, 384
+    pool = wl.lora_pool(N, r, d_in, d_out, "bf16", device="cpu", seed=51)
+    A = [pool.A[i].contiguous() for i in range(N)]
+    B = [pool.B[i].contiguous() for i in range(N)]
+    h = preft.preft_slots_create(N, M, [_bytes(A[0]), _bytes(B[0])])
+    try:
+        for i in range(N):
+            preft.preft_slots_store(h, i, 0, A[i])
+            preft.preft_slots_store(h, i, 1, B[i])
+        Ap, Bp = preft.preft_slots_pool(h, 0), preft.preft_slots_pool(h, 1)
+        assert Ap.numel() == M
+        rng = np.random.Generator(np.random.PCG64(52))
+        copied = 0
+        for step in range(12):
+            if step == 6:            # weight update of an adapter (resident or not): next batch must see it
+                first = int([a for a in ids if a >= 0][0])
+                for i in (first, (first + 5) % N):
+                    A[i] = (A[i].float() * -0.5).to(torch.bfloat16).contiguous()
+                    preft.preft_slots_store(h, i, 0, A[i])
+            lens = rng.integers(1, 90, size=6)
+            ids = rng.choice(N, size=M, replace=False)[rng.integers(0, M, size=6)]       # <= M distinct
+            ids[rng.integers(0, 6)] = -1
+            pre = np.where(rng.random(6) < 0.6, lens, 0)
+            tab = wl.from_lengths(lens, ids, pre)
+            slots = preft.preft_slots_acquire(h, ids.tolist())
+            assert all((s == -1) == (a == -1) for s, a in zip(slots, ids))
+            slot_tab = wl.from_lengths(lens, slots, pre)
+            x = wl.activations(tab.T, d_in, "bf16", device="cuda", seed=500 + step)
+            y0 = wl.activations(tab.T, d_out, "bf16", device="cuda", seed=600 + step)
+            y = y0.clone()
+            ss, sa, sp = dev_tables(slot_tab)
+            ws = preft.new_workspace(tab.T, tab.S)
+            for mode, pos in ((preft.PREFT_PREFILL_ONLY, ora.PROMPT_ONLY), (preft.PREFT_ALL_TOKENS, ora.ALL_POSITIONS)):
+                y.copy_(y0)
+                preft.preft_lora_apply(y, x, ss, sa, sp, Ap, Bp, r, 2.0, mode, ws)
+                torch.cuda.synchronize()
+                want = ora.lora(y0.cpu(), x.cpu(), tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, A, B, r, 2.0, pos)
+                owner = ora.positions(tab.T, tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, N, pos)
+                compare(y, y0, want, owner, "bf16")
+            st = preft.preft_slots_stats(h)
+            assert st["bytes_copied"] >= copied
+            copied = st["bytes_copied"]
+        st = preft.preft_slots_stats(h)
+        assert st["misses"] > M and st["evictions"] > 0 and st["hits"] > 0
+    finally:
+        torch.cuda.synchronize()
+        preft.preft_slots_destroy(h)
+
+
+def test_graph_replay_sees_refreshed_weights():
+    """Weights live at stable addresses (App. D.4): a captured apply call picks up a refresh."""
+    from parity_util import bits, dev_tables
+    N, M, r, d = 3, 2, 8, 256
+    dp = wl.direft_pool(N, r, d, "bf16", device="cpu", seed=53)
+    parts = lambda i: (dp.A[i].contiguous(), dp.B[i].t().contiguous(), dp.b[i].contiguous())
+    h = preft.preft_slots_create(N, M, [_bytes(t) for t in parts(0)])
+    try:
+        for i in range(N):
+            for p, t in enumerate(parts(i)):
+                preft.preft_slots_store(h, i, p, t)
+        pools = [preft.preft_slots_pool(h, p) for p in range(3)]
+        tab = wl.from_lengths([40, 1, 7], [1, 1, 2], [40, 0, 7])
+        slots = preft.preft_slots_acquire(h, tab.seg_adapter.tolist())
+        ss, sa, sp = dev_tables(wl.from_lengths([40, 1, 7], slots, [40, 0, 7]))
+        ws = preft.new_workspace(tab.T, tab.S)
+        h0 = wl.activations(tab.T, d, "bf16", device="cuda", seed=54)
+        hh = h0.clone()
+
+        def body():
+            hh.copy_(h0)
+            preft.preft_direft_apply(hh, ss, sa, sp, pools[0], pools[1], pools[2], r, 1.0, preft.PREFT_PREFILL_ONLY, ws)
+
+        body()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            body()
+        g.replay()
+        torch.cuda.synchronize()
+        first = hh.clone()
+        new_b = (dp.b[1].float() + 3.0).to(torch.bfloat16).contiguous()
+        preft.preft_slots_store(h, 1, 2, new_b)                  # resident: refreshed in its slot
+        g.replay()
+        torch.cuda.synchronize()
+        assert not torch.equal(bits(first), bits(hh))
+        want = ora.direft(h0.cpu(), tab.seg_start, tab.seg_adapter, tab.seg_prefill_len,
+                          [dp.A[i] for i in range(N)], [dp.B[i] for i in range(N)],
+                          [dp.b[0], new_b, dp.b[2]], r, 1.0, ora.PROMPT_ONLY)
+        from parity_util import compare
+        owner = ora.positions(tab.T, tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, N, ora.PROMPT_ONLY)
+        compare(hh, h0, want, owner, "bf16")
+    finally:
+        torch.cuda.synchronize()
+        preft.preft_slots_destroy(h)
