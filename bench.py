@@ -32,12 +32,6 @@ if ROOT not in sys.path:
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E, published
 
 
-def lora_bytes(T_act, d_in, d_out, r, n_adapters, e=2):
-    """Algorithmic bytes of one LoRA apply: x once in, y once in and once out, each distinct
-    active adapter's two factors once."""
-    return e * T_act * (d_in + 2 * d_out) + e * r * (d_in + d_out) * n_adapters
-
-
 def direft_bytes(T_act, d, r, n_adapters, e=2):
     """Algorithmic bytes of one DiReFT apply: h once in, once out; factors and bias once."""
     return e * T_act * 2 * d + e * (2 * r * d + r) * n_adapters
@@ -58,6 +52,8 @@ def main():
     ap.add_argument("--rowblocks", type=int, default=0)
     ap.add_argument("--ldpad", type=int, default=0, help="experiment: extra elements of row stride on every buffer")
     ap.add_argument("--only", default="", help="experiment: comma-separated subset of projections")
+    ap.add_argument("--no-packed", action="store_true",
+                    help="one launch per projection instead of packed q,k,v and gate,up launches")
     ap.add_argument("--no-trace", action="store_true", help="skip the serving-trace replay leg")
     ap.add_argument("--trace-requests", type=int, default=1000)
     ap.add_argument("--trace-batch", type=int, default=32)
@@ -123,21 +119,41 @@ def main():
     h = act(T, d_res, args.seed + 300)
     direft_scale = 1.0
 
-    def step(mode, tables=(ss, sa, sp), T_=T, events=None):
+    # launches of a step: projections that read the same x (q,k,v; gate,up) go out as one packed call
+    packs = {"q": "qkv", "k": "qkv", "v": "qkv", "gate": "gate_up", "up": "gate_up"}
+    groups = []
+    for p in projs:
+        key = None if args.no_packed else packs.get(p["name"])
+        if key is not None and groups and groups[-1]["key"] == key and groups[-1]["members"][0]["d_in"] == p["d_in"]:
+            groups[-1]["members"].append(p)
+        else:
+            groups.append(dict(key=key, members=[p]))
+    for g_ in groups:
+        g_["name"] = "+".join(m["name"] for m in g_["members"])
+
+    singles = [dict(key=None, members=[p], name=p["name"]) for p in projs]
+
+    def step(mode, tables=(ss, sa, sp), T_=T, events=None, groups=groups):
         s0, s1, s2 = tables
         preft.preft_schedule(ws, s0, s1, s2, T_, N, mode)
         ready = mode | preft.PREFT_SCHEDULE_READY
-        for i, p in enumerate(projs):
+        for i, g_ in enumerate(groups):
+            m = g_["members"]
             if events is not None:
                 events[i][0].record()
-            preft.preft_lora_apply(p["y"][:T_], p["x"][:T_], s0, s1, s2, p["Ap"], p["Bp"], r, scale, ready, ws)
+            if len(m) == 1:
+                preft.preft_lora_apply(m[0]["y"][:T_], m[0]["x"][:T_], s0, s1, s2, m[0]["Ap"], m[0]["Bp"], r, scale,
+                                       ready, ws)
+            else:
+                preft.preft_lora_apply_packed([q["y"][:T_] for q in m], m[0]["x"][:T_], s0, s1, s2,
+                                              [q["Ap"] for q in m], [q["Bp"] for q in m], r, scale, ready, ws)
             if events is not None:
                 events[i][1].record()
         if events is not None:
-            events[len(projs)][0].record()
+            events[len(groups)][0].record()
         preft.preft_direft_apply(h[:T_], s0, s1, s2, W1p, W2tp, bp, r, direft_scale, ready, ws)
         if events is not None:
-            events[len(projs)][1].record()
+            events[len(groups)][1].record()
 
     def timed(fn, iters, warm):
         for _ in range(warm):
@@ -152,7 +168,7 @@ def main():
     # ---- timed region: K prefill-only steps ------------------------------------------------
     K, W = args.steps, args.warmup
     ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-           for _ in range(len(projs) + 1)] for _ in range(K)]
+           for _ in range(len(groups) + 1)] for _ in range(K)]
     for _ in range(W):
         step(preft.PREFT_PREFILL_ONLY)
     torch.cuda.synchronize()
@@ -167,10 +183,13 @@ def main():
     mean_ms = per_launch_ms.mean(axis=0)
     breakdown = {}
     lora_b, lora_t = 0.0, 0.0
-    for i, p in enumerate(projs):
-        b = lora_bytes(T_act, p["d_in"], p["d_out"], r, n_ad)
-        breakdown[p["name"]] = dict(us=round(mean_ms[i] * 1e3, 2), GBps=round(b / mean_ms[i] / 1e6, 1),
-                                    frac=round(b / mean_ms[i] / 1e6 / PEAK_HBM_GBPS, 4))
+    for i, g_ in enumerate(groups):
+        m = g_["members"]
+        # x once per launch, every output read and written once, every distinct adapter's factors once
+        b = 2 * T_act * (m[0]["d_in"] + 2 * sum(q["d_out"] for q in m)) \
+            + 2 * r * n_ad * sum(q["d_in"] + q["d_out"] for q in m)
+        breakdown[g_["name"]] = dict(us=round(mean_ms[i] * 1e3, 2), GBps=round(b / mean_ms[i] / 1e6, 1),
+                                     frac=round(b / mean_ms[i] / 1e6 / PEAK_HBM_GBPS, 4))
         lora_b += b
         lora_t += mean_ms[i]
     db = direft_bytes(T_act, d_res, r, n_ad)
@@ -178,11 +197,11 @@ def main():
                                frac=round(db / mean_ms[-1] / 1e6 / PEAK_HBM_GBPS, 4))
     if projs:
         achieved = lora_b / lora_t / 1e6                                                 # GB/s
-        roofline = dict(bound="hbm", kernel=f"lora tile kernel ({len(projs)} launches per step: "
-                                            + ",".join(p["name"] for p in projs) + ")",
+        roofline = dict(bound="hbm", kernel=f"lora tile kernel ({len(groups)} launches per step: "
+                                            + ",".join(g_["name"] for g_ in groups) + ")",
                         achieved=round(achieved, 1), peak=PEAK_HBM_GBPS, unit="GB/s",
                         frac=round(achieved / PEAK_HBM_GBPS, 4), traffic=None,
-                        bytes_per_launch=int(lora_b / len(projs)), us_per_launch=round(lora_t / len(projs) * 1e3, 2))
+                        bytes_per_launch=int(lora_b / len(groups)), us_per_launch=round(lora_t / len(groups) * 1e3, 2))
     else:
         achieved = db / mean_ms[-1] / 1e6
         roofline = dict(bound="hbm", kernel="direft tile kernel (1 launch per step)",
@@ -193,7 +212,7 @@ def main():
     # HBM traffic of the dominant kernel comes from two rocprofv3 --pmc runs of this same command;
     # their summary is committed under profiles/ and quoted here when the configuration matches.
     if projs and args.config == "llama8b_lora" and r == 16 and not (args.variant or args.waves or args.rowblocks
-                                                                     or args.ldpad or args.only):
+                                                                     or args.ldpad or args.only or args.no_packed):
         try:
             with open(os.path.join(ROOT, "profiles", "lora_tile_kernel_llama8b_rank16_hbm_traffic.txt")) as f:
                 for line in f:
@@ -209,7 +228,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": f"{args.config}: one decoder layer's adapter work = scheduler + {len(projs)} LoRA projections "
-                               f"({','.join(p['name'] for p in projs)}) + DiReFT d={d_res}, rank {r}, prefill-only",
+                               f"({','.join(p['name'] for p in projs)}; launches: {','.join(g_['name'] for g_ in groups)}) "
+                               f"+ DiReFT d={d_res}, rank {r}, prefill-only",
                    "T": T, "S": S, "active_rows": T_act, "decode_rows": int(T - T_act), "adapters": N,
                    "distinct_active_adapters": n_ad, "rank": r, "seed": args.seed,
                    "schedule": {"chunks": counts[0], "short_rows": counts[1]}},
@@ -242,6 +262,10 @@ def main():
         ms_dec_all = timed(g_all.replay, 50, 5)
         ms_dec_pre = timed(g_pre.replay, 50, 5)
         out["all_token"] = {"ms_per_step": round(ms_all, 4), "speedup_prefill_only": round(ms_all / ms_per_step, 4)}
+        if len(groups) != len(singles):
+            ms_single = timed(lambda: step(preft.PREFT_PREFILL_ONLY, groups=singles), max(5, K // 4), 3)
+            out["one_launch_per_projection"] = {"ms_per_step": round(ms_single, 4),
+                                                "speedup_packed": round(ms_single / ms_per_step, 4)}
         out["decode_only_step"] = {"rows": dec.T, "all_token_ms": round(ms_dec_all, 4),
                                    "prefill_only_ms": round(ms_dec_pre, 4),
                                    "speedup_prefill_only": round(ms_dec_all / ms_dec_pre, 2)}

@@ -84,6 +84,7 @@ enum {
 };
 
 #define PREFT_MAX_RANK 128
+#define PREFT_MAX_PACKED 3      /* projections one packed call may fuse */
 
 /*
  * Bytes of device workspace that hold the schedule of a batch of T rows in S segments.
@@ -130,6 +131,27 @@ int preft_lora_apply(void *y, int64_t ldy, const void *x, int64_t ldx,
                      const void *const *A_pool, const void *const *B_pool, int32_t N,
                      int32_t rank, float scale, int dtype, int mode,
                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Packed projections: n_proj (1..PREFT_MAX_PACKED) LoRA applications that read the SAME x --
+ * the q, k and v projections of an attention block, the gate and up projections of an MLP
+ * (the paper's LoRA targets, App. A.1) -- as one call:
+ *   y_p[t, :] += scale * B_{p,i} (A_{p,i} x[t, :])      p = 0 .. n_proj-1, active rows t.
+ * Each projection has its own output y[p] ([T, d_out[p]], row stride ldy[p]) and its own pools
+ * A_pools[p] / B_pools[p] (device pointer tables as in preft_lora_apply); y, ldy, d_out, A_pools
+ * and B_pools are HOST arrays of n_proj entries.  The outputs may be separate buffers or
+ * disjoint column ranges of one buffer (a fused qkv or gate-up output: same row stride, every
+ * range inside one row); any other overlap, and any overlap with x, is PREFT_EINVAL.
+ * The result is that of n_proj preft_lora_apply calls.  For bf16 and rank 4, 8, 12 or 16 they run as
+ * one launch that reads x once; otherwise the call issues one launch per projection.
+ */
+int preft_lora_apply_packed(int32_t n_proj, void *const *y, const int64_t *ldy, const int32_t *d_out,
+                            const void *x, int64_t ldx, int32_t T, int32_t d_in,
+                            const int32_t *seg_start, const int32_t *seg_adapter,
+                            const int32_t *seg_prefill_len, int32_t S,
+                            const void *const *const *A_pools, const void *const *const *B_pools,
+                            int32_t N, int32_t rank, float scale, int dtype, int mode,
+                            void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Segmented multi-adapter DiReFT (paper Eq. 3 with the prefactor of App. C.2, under the

@@ -25,7 +25,8 @@ PREFT_KNOB_WAVES = 1
 PREFT_KNOB_ROWBLOCKS = 2
 
 # every symbol include/preft.h declares
-ABI_SYMBOLS = ("preft_workspace_bytes", "preft_schedule", "preft_lora_apply", "preft_direft_apply",
+ABI_SYMBOLS = ("preft_workspace_bytes", "preft_schedule", "preft_lora_apply", "preft_lora_apply_packed",
+               "preft_direft_apply",
                "preft_loreft_prepare", "preft_loreft_apply", "preft_slots_create", "preft_slots_destroy",
                "preft_slots_store", "preft_slots_acquire", "preft_slots_pool", "preft_slots_resident",
                "preft_slots_stats", "preft_schedule_counts", "preft_set_knob", "preft_strerror", "preft_version")
@@ -59,6 +60,10 @@ def load_library(path: Optional[str] = None):
     lib.preft_lora_apply.restype = c.c_int
     lib.preft_lora_apply.argtypes = [vp, i64, vp, i64, i32, i32, i32, vp, vp, vp, i32, vp, vp, i32, i32,
                                      c.c_float, c.c_int, c.c_int, vp, sz, vp]
+    lib.preft_lora_apply_packed.restype = c.c_int
+    lib.preft_lora_apply_packed.argtypes = [i32, c.POINTER(vp), c.POINTER(i64), c.POINTER(i32), vp, i64, i32, i32,
+                                            vp, vp, vp, i32, c.POINTER(vp), c.POINTER(vp), i32, i32,
+                                            c.c_float, c.c_int, c.c_int, vp, sz, vp]
     lib.preft_direft_apply.restype = c.c_int
     lib.preft_direft_apply.argtypes = [vp, i64, i32, i32, vp, vp, vp, i32, vp, vp, vp, i32, i32,
                                        c.c_float, c.c_int, c.c_int, vp, sz, vp]
@@ -209,6 +214,34 @@ def preft_lora_apply(y: torch.Tensor, x: torch.Tensor, seg_start, seg_adapter, s
         A_pool.data_ptr(), B_pool.data_ptr(), N, int(rank), float(scale), _dtype_code(y), int(mode),
         workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, "preft_lora_apply")
+
+
+def preft_lora_apply_packed(ys: Sequence[torch.Tensor], x: torch.Tensor, seg_start, seg_adapter, seg_prefill_len,
+                            A_pools: Sequence, B_pools: Sequence, rank: int, scale: float, mode: int,
+                            workspace: torch.Tensor, stream=None) -> None:
+    """ys[p][t] += scale * B_{p,i} (A_{p,i} x[t]) for every projection p of the same x (q,k,v or
+    gate,up); ys may be separate tensors or column slices of one tensor."""
+    n = len(ys)
+    if len(A_pools) != n or len(B_pools) != n:
+        raise ValueError("one A pool and one B pool per output")
+    xp, ldx, T, d_in = _matrix(x, "x")
+    yp, ldy, d_out = (ctypes.c_void_p * n)(), (ctypes.c_int64 * n)(), (ctypes.c_int32 * n)()
+    Ap, Bp = (ctypes.c_void_p * n)(), (ctypes.c_void_p * n)()
+    N = int(A_pools[0].numel())
+    for i, y in enumerate(ys):
+        yp[i], ldy[i], T2, d_out[i] = _matrix(y, f"ys[{i}]")
+        if T2 != T or y.dtype != x.dtype:
+            raise ValueError("x and every y must agree in rows and dtype")
+        if A_pools[i].numel() != N or B_pools[i].numel() != N or A_pools[i].dtype != torch.int64:
+            raise ValueError("pools must be int64 pointer tables of equal length")
+        Ap[i], Bp[i] = A_pools[i].data_ptr(), B_pools[i].data_ptr()
+    S = int(seg_adapter.numel())
+    rc = load_library().preft_lora_apply_packed(
+        n, yp, ldy, d_out, xp, ldx, T, d_in,
+        _table(seg_start, "seg_start", S + 1), _table(seg_adapter, "seg_adapter", S),
+        _table(seg_prefill_len, "seg_prefill_len", S), S, Ap, Bp, N, int(rank), float(scale), _dtype_code(x),
+        int(mode), workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc, "preft_lora_apply_packed")
 
 
 def preft_loreft_prepare(D: torch.Tensor, Rt: torch.Tensor, W: torch.Tensor, R: torch.Tensor, stream=None) -> None:

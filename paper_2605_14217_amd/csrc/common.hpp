@@ -170,7 +170,22 @@ struct ApplyArgs {
     const int2         *shorts;
     const int4         *gtiles;
     int32_t             gathered_only;   // tile kernels: skip the chunks (another launch covers them)
+    // packed projections (LoRA only): further outputs computed from the same x, each with its
+    // own factors; slice 0 is (y, ldy, d_out, A_pool, Bt_pool) above
+    struct Slice {
+        void               *y;
+        int64_t             ldy;
+        int32_t             d_out;
+        const void *const  *A_pool;
+        const void *const  *Bt_pool;
+    } more[2];
 };
+
+template <int SL> __device__ __forceinline__ void *slice_y(const ApplyArgs &p) { if constexpr (SL == 0) return p.y; else return p.more[SL - 1].y; }
+template <int SL> __device__ __forceinline__ int64_t slice_ldy(const ApplyArgs &p) { if constexpr (SL == 0) return p.ldy; else return p.more[SL - 1].ldy; }
+template <int SL> __device__ __forceinline__ int32_t slice_d_out(const ApplyArgs &p) { if constexpr (SL == 0) return p.d_out; else return p.more[SL - 1].d_out; }
+template <int SL> __device__ __forceinline__ const void *const *slice_A(const ApplyArgs &p) { if constexpr (SL == 0) return p.A_pool; else return p.more[SL - 1].A_pool; }
+template <int SL> __device__ __forceinline__ const void *const *slice_Bt(const ApplyArgs &p) { if constexpr (SL == 0) return p.Bt_pool; else return p.more[SL - 1].Bt_pool; }
 
 // The tile a workgroup of a tile kernel of height R works on: rows of one adapter, either
 // consecutive (a tile of a chunk) or listed one by one (a gathered tile).

@@ -41,6 +41,8 @@
 #pragma once
 #include "common.hpp"
 
+#include <type_traits>
+
 namespace preft {
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(u32x4_t v) { return __builtin_bit_cast(bf16x8_t, v); }
@@ -67,18 +69,24 @@ constexpr int mfma_min_waves(int NB, int MB, int WAVES, int HUNITS)
     return (HUNITS > 0 && WAVES == 8 && NB * MB == 1 && HUNITS <= 4) ? 4 : 1;
 }
 
-template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT>
+// SLICES > 1 (LoRA only): packed projections.  The outputs y_0 .. y_{SLICES-1} are all computed
+// from the same x (q, k, v of an attention block; gate and up of an MLP), each with its own
+// factors of NB rank blocks: one shrink sweep over x feeds SLICES * NB accumulator blocks, then
+// one expand sweep per output.  x is read once instead of SLICES times.
+template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT, int SLICES = 1>
 __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) void mfma_tile_kernel(ApplyArgs p)
 {
     constexpr int R = 16 * MB;
-    constexpr int TPC = CHUNK_ROWS / R;
-    constexpr bool PREFETCH_A = (NB * MB <= 2);               // register budget
+    constexpr int NBT = NB * SLICES;                          // rank blocks of the shrink sweep
+    constexpr bool PREFETCH_A = (NBT * MB <= 3);              // register budget
+    static_assert(SLICES == 1 || (!DIREFT && HUNITS == 0), "packed projections are a LoRA feature");
     static_assert(CHUNK_ROWS % R == 0, "tile height must divide the chunk height");
     static_assert(HUNITS == 0 || DIREFT, "only the in-place variant keeps its tile in registers");
     static_assert(WAVES >= 4, "the tail steps are dealt one per wavefront");
 
-    __shared__ float red[WAVES * NB * MB * 4 * 64];           // cross-wavefront reduction of z
-    __shared__ u32x4_t turn[WAVES][MB * 16 * MFMA_TRS];       // wavefront-private turn buffers
+    __shared__ float red[WAVES * NBT * MB * 4 * 64];          // cross-wavefront reduction of z
+    __shared__ u32x4_t turn[WAVES][MB * 16 * MFMA_TRS];       // wavefront-private turn buffers: activations
+    __shared__ u32x4_t turn_a[WAVES][16 * MFMA_TRS];          // ... and one rank block of the factor
 
     int n_chunk_units;
     const int unit = xcd_unit(tile_units<R>(p, &n_chunk_units));
@@ -94,10 +102,9 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
     const int ld_row = lane >> 2, ld_chunk = lane & 3;        // step load order: row, 16-byte chunk
 
     const int r = p.rank;
-    const int64_t ldx_b = p.ldx * 2, ldy_b = p.ldy * 2;
-    gcptr_t A  = as_global(p.A_pool[adapter]);
-    gcptr_t Bt = as_global(p.Bt_pool[adapter]);
+    const int64_t ldx_b = p.ldx * 2;
     u32x4_t *tr = turn[wave];
+    u32x4_t *tra = turn_a[wave];
 
     // ---- lane permutations for single 32-column steps (factors, tails) ----------------
     const int gather_addr  = (4 * (lane & 15) + (lane >> 4)) << 2;    // MFMA lane <- step-load lane
@@ -118,26 +125,33 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
     // ---- row pointers.  Row slots past the end of the tile alias its last row: they load the
     // same bytes, compute the same values and store the same bits, so no access below depends
     // on the row.
-    gcptr_t xu[MB][4];            // unit order: instruction i covers rows 4i .. 4i+3
-    gptr_t yu[MB][4];
-    gcptr_t xs[MB];               // step order
-    gptr_t ys[MB];
+    int64_t row_u[MB][4], row_s[MB];   // unit order: instruction i covers rows 4i .. 4i+3; step order
+    gcptr_t xu[MB][4];
+    gcptr_t xs[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int64_t row = tile.row(mb * 16 + 4 * i + q);
-            xu[mb][i] = as_global(p.x) + row * ldx_b + c16 * 16;
-            yu[mb][i] = as_global(p.y) + row * ldy_b + c16 * 16;
+            row_u[mb][i] = tile.row(mb * 16 + 4 * i + q);
+            xu[mb][i] = as_global(p.x) + row_u[mb][i] * ldx_b + c16 * 16;
         }
-        const int64_t row = tile.row(mb * 16 + ld_row);
-        xs[mb] = as_global(p.x) + row * ldx_b + ld_chunk * 16;
-        ys[mb] = as_global(p.y) + row * ldy_b + ld_chunk * 16;
+        row_s[mb] = tile.row(mb * 16 + ld_row);
+        xs[mb] = as_global(p.x) + row_s[mb] * ldx_b + ld_chunk * 16;
     }
-    // factor pointers, step order (ranks past r alias rank r-1; their z entries are zeroed below)
-    gcptr_t ap[NB];
+    // factor pointers (ranks past r alias rank r-1; their z entries are zeroed below): a uniform
+    // base per rank block's slice plus per-lane byte offsets, in unit order (instruction i covers
+    // ranks 4i .. 4i+3 of a block, 256 bytes each) and in step order (the tails)
+    gcptr_t abase[SLICES];
+    abase[0] = as_global(slice_A<0>(p)[adapter]);
+    if constexpr (SLICES > 1) abase[1] = as_global(slice_A<1>(p)[adapter]);
+    if constexpr (SLICES > 2) abase[2] = as_global(slice_A<2>(p)[adapter]);
+    int32_t aoff_u[NB][4], aoff_s[NB];
 #pragma unroll
-    for (int b = 0; b < NB; ++b) ap[b] = A + ((int64_t)min(16 * b + ld_row, r - 1) * p.d_in + ld_chunk * 8) * 2;
+    for (int b = 0; b < NB; ++b) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) aoff_u[b][i] = (min(16 * b + 4 * i + q, r - 1) * p.d_in + c16 * 8) * 2;
+        aoff_s[b] = (min(16 * b + ld_row, r - 1) * p.d_in + ld_chunk * 8) * 2;
+    }
 
     // one unit (16 MB rows x 128 columns) from load order to MFMA order, through LDS
     auto unit_to_mfma = [&](const u32x4_t (&raw)[MB][4], u32x4_t (&op)[MB][4]) {
@@ -152,9 +166,9 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
     };
 
     // ---------------------------------------------------------------- shrink
-    f32x4_t acc[NB][MB];
+    f32x4_t acc[NBT][MB];
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+    for (int b = 0; b < NBT; ++b)
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) acc[b][mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
@@ -173,26 +187,30 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
 #pragma unroll
             for (int i = 0; i < 4; ++i) raw[mb][i] = ld16(xu[mb][i] + off);
     };
-    auto load_a_unit = [&](u32x4_t (&araw)[4][NB], int u) {
+    auto load_a_unit = [&](u32x4_t (&araw)[NBT][4], int u) {
         const int64_t off = (int64_t)(wave + u * WAVES) * 256;
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+        for (int b = 0; b < NBT; ++b)
 #pragma unroll
-            for (int b = 0; b < NB; ++b) araw[s][b] = ld16(ap[b] + off + s * 64);
+            for (int i = 0; i < 4; ++i) araw[b][i] = ld16(abase[b / NB] + off + aoff_u[b % NB][i]);
     };
-    auto mfma_unit = [&](const u32x4_t (&op)[MB][4], const u32x4_t (&araw)[4][NB]) {
+    // a rank block of the factor is turned into MFMA order like the activations: lane (rank rl, g)
+    // then holds columns 8g .. 8g+7 of step s
+    auto mfma_unit = [&](const u32x4_t (&op)[MB][4], const u32x4_t (&araw)[NBT][4]) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+        for (int b = 0; b < NBT; ++b) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                const u32x4_t t = araw[s][b];
-                const bf16x8_t ao = step_to_mfma(t);
+            for (int i = 0; i < 4; ++i) tra[(4 * i + q) * MFMA_TRS + c16] = araw[b][i];
+            u32x4_t aop[4];
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    const u32x4_t xo = op[mb][s];
-                    acc[b][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ao, as_bf16x8(xo), acc[b][mb], 0, 0, 0);
-                }
-            }
+            for (int s = 0; s < 4; ++s) aop[s] = tra[rl * MFMA_TRS + 4 * s + g];
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+                    acc[b][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(aop[s]), as_bf16x8(op[mb][s]),
+                                                                         acc[b][mb], 0, 0, 0);
+        }
     };
 
     if constexpr (HUNITS > 0) {
@@ -204,19 +222,19 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
 #pragma unroll
         for (int u = 0; u < HUNITS; ++u)
             if (u < my_ku) {
-                u32x4_t araw[4][NB];
+                u32x4_t araw[NBT][4];
                 load_a_unit(araw, u);
                 unit_to_mfma(raw[u], hreg[u]);
                 mfma_unit(hreg[u], araw);
             }
     } else {
         if (my_ku > 0) {
-            u32x4_t x0[MB][4], x1[MB][4], a0[4][NB], a1[4][NB], op[MB][4];
-            auto stage_load = [&](u32x4_t (&xr)[MB][4], u32x4_t (&ar)[4][NB], int u) {
+            u32x4_t x0[MB][4], x1[MB][4], a0[NBT][4], a1[NBT][4], op[MB][4];
+            auto stage_load = [&](u32x4_t (&xr)[MB][4], u32x4_t (&ar)[NBT][4], int u) {
                 load_x_unit(xr, u);
                 if constexpr (PREFETCH_A) load_a_unit(ar, u);
             };
-            auto stage_compute = [&](const u32x4_t (&xr)[MB][4], u32x4_t (&ar)[4][NB], int u) {
+            auto stage_compute = [&](const u32x4_t (&xr)[MB][4], u32x4_t (&ar)[NBT][4], int u) {
                 if constexpr (!PREFETCH_A) load_a_unit(ar, u);
                 unit_to_mfma(xr, op);
                 mfma_unit(op, ar);
@@ -249,8 +267,8 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) htail[mb] = as_u32x4(step_to_mfma(col_ok ? ld16(xs[mb] + off) : zero));
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const bf16x8_t av = step_to_mfma(col_ok ? ld16(ap[b] + off) : zero);
+        for (int b = 0; b < NBT; ++b) {
+            const bf16x8_t av = step_to_mfma(col_ok ? ld16(abase[b / NB] + off + aoff_s[b % NB]) : zero);
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
                 acc[b][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(htail[mb]), acc[b][mb], 0, 0, 0);
@@ -259,9 +277,9 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
 
     // ---------------------------------------------------------------- reduce over wavefronts
     {
-        constexpr int PER = NB * MB * 4;
+        constexpr int PER = NBT * MB * 4;
 #pragma unroll
-        for (int b = 0; b < NB; ++b)
+        for (int b = 0; b < NBT; ++b)
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -269,7 +287,7 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
                     red[(wave * PER + (b * MB + mb) * 4 + v) * 64 + lane] = acc[b][mb][v];
         __syncthreads();          // also: every read of the tile precedes every write (in-place use)
 #pragma unroll
-        for (int b = 0; b < NB; ++b)
+        for (int b = 0; b < NBT; ++b)
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -284,10 +302,10 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
     // ---------------------------------------------------------------- z -> expand operand
     // lane (row rl, g) holds z[row][16b + 4g + v]; add the bias, apply the prefactor, zero the
     // padding ranks, and split into bf16 head + bf16 remainder.
-    bf16x8_t zop[NB][MB];
+    bf16x8_t zop[NBT][MB];
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        const int rank0 = 16 * b + 4 * g;
+    for (int b = 0; b < NBT; ++b) {
+        const int rank0 = 16 * (b % NB) + 4 * g;              // rank within the block's own slice
         const bool rank_ok = rank0 < r;                       // r % 4 == 0: all four or none
         float bias[4] = {0.f, 0.f, 0.f, 0.f};
         if (DIREFT && p.bias_pool && rank_ok) {
@@ -314,7 +332,20 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
         }
     }
 
-    // ---------------------------------------------------------------- expand
+    // ---------------------------------------------------------------- expand (once per output)
+    auto expand_slice = [&](auto sl_tag) {
+    constexpr int SL = decltype(sl_tag)::value;
+    gcptr_t Bt = as_global(slice_Bt<SL>(p)[adapter]);
+    const int d_out = slice_d_out<SL>(p);
+    const int64_t ldy_b = slice_ldy<SL>(p) * 2;
+    gptr_t yu[MB][4];             // unit order
+    gptr_t ys[MB];                // step order
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) yu[mb][i] = as_global(slice_y<SL>(p)) + row_u[mb][i] * ldy_b + c16 * 16;
+        ys[mb] = as_global(slice_y<SL>(p)) + row_s[mb] * ldy_b + ld_chunk * 16;
+    }
     // Weight pointer of MFMA e, rank block b: column 8(rl/4) + 4e + rl%4 of the current
     // 32-column step, ranks 16b + 4g .. +3 (padding ranks alias rank 0; their z is zero).
     gcptr_t bp[2][NB];
@@ -338,7 +369,7 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
             for (int b = 0; b < NB; ++b) {
                 const u32x2_t w = wv[e][b];
                 const bf16x8_t wop = as_bf16x8(u32x4_t{w[0], w[1], w[0], w[1]});
-                d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wop, zop[b][mb], d, 0, 0, 0);
+                d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wop, zop[SL * NB + b][mb], d, 0, 0, 0);
             }
             const uint32_t y01 = yv[2 * e], y23 = yv[2 * e + 1];
             out[4 * e + 0] = bf16_lo(y01) + d[0];
@@ -380,9 +411,9 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
             for (int i = 0; i < 4; ++i) st16(yu[mb][i] + off, tr[(mb * 16 + 4 * i + q) * MFMA_TRS + c16]);
     };
 
-    const int c_units = p.d_out >> 7;
+    const int c_units = d_out >> 7;
     const int my_cu = c_units > wave ? (c_units - wave + WAVES - 1) / WAVES : 0;
-    const int c_steps = (p.d_out + 31) >> 5;
+    const int c_steps = (d_out + 31) >> 5;
     const int c_tail_step = c_units * 4 + wave;
 
     if constexpr (HUNITS > 0) {
@@ -428,7 +459,7 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
     // tail step of this wavefront (DiReFT: it still holds those activations in htail)
     if (c_tail_step < c_steps) {
         const int c0 = c_tail_step * 32;
-        const bool col_ok = (c0 + ld_chunk * 8) < p.d_out;              // step-load lane order
+        const bool col_ok = (c0 + ld_chunk * 8) < d_out;              // step-load lane order
         const int64_t off = (int64_t)c_tail_step * 64;
         u32x2_t wv[2][NB];
 #pragma unroll
@@ -436,7 +467,7 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
             // this lane's weight column may lie past d_out: alias the last column (its
             // products land in outputs that are not stored)
             const int col = c0 + 8 * (rl >> 2) + 4 * e + (rl & 3);
-            const int64_t back = col < p.d_out ? 0 : (int64_t)(col - (p.d_out - 1)) * r * 2;
+            const int64_t back = col < d_out ? 0 : (int64_t)(col - (d_out - 1)) * r * 2;
 #pragma unroll
             for (int b = 0; b < NB; ++b) wv[e][b] = ld8(bp[e][b] + c_tail_step * w_step - back);
         }
@@ -453,6 +484,10 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
             if (col_ok) st16(ys[mb] + off, o);
         }
     }
+    };
+    expand_slice(std::integral_constant<int, 0>{});
+    if constexpr (SLICES > 1) expand_slice(std::integral_constant<int, 1>{});
+    if constexpr (SLICES > 2) expand_slice(std::integral_constant<int, 2>{});
 }
 
 }  // namespace preft

@@ -177,6 +177,21 @@ void launch_mfma_nb(const ApplyArgs &a, int64_t S, hipStream_t stream)
     launch_mfma_stream<NB, DIREFT>(a, S, mb, waves, stream);
 }
 
+// packed projections (LoRA, rank <= 16): one shrink sweep over x, one expand sweep per output
+template <int SLICES>
+void launch_mfma_packed(const ApplyArgs &a, int64_t S, hipStream_t stream)
+{
+    // three outputs: 4 wavefronts per tile leave room for two workgroups per compute unit (measured
+    // better on small and large batches); two outputs: as for a single projection
+    const int waves = g_waves ? (g_waves == 8 ? 8 : 4) : ((SLICES == 2 && a.T <= 65536) ? 8 : 4);
+    if (waves == 8)
+        hipLaunchKernelGGL((mfma_tile_kernel<1, 1, 8, 0, false, SLICES>), dim3(tile_grid(a, S, 16)), dim3(512), 0,
+                           stream, a);
+    else
+        hipLaunchKernelGGL((mfma_tile_kernel<1, 1, 4, 0, false, SLICES>), dim3(tile_grid(a, S, 16)), dim3(256), 0,
+                           stream, a);
+}
+
 template <bool DIREFT>
 void launch_mfma_rank(const ApplyArgs &a, int64_t S, hipStream_t stream)
 {
@@ -334,6 +349,70 @@ int preft_lora_apply(void *y, int64_t ldy, const void *x, int64_t ldx, int32_t T
     a.A_pool = A_pool; a.Bt_pool = B_pool; a.bias_pool = nullptr; a.N = N; a.rank = rank; a.scale = scale;
     a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.gtiles = v.gtiles; a.gathered_only = 0;
     return launch_apply<false>(a, S, dtype, st);
+}
+
+int preft_lora_apply_packed(int32_t n_proj, void *const *y, const int64_t *ldy, const int32_t *d_out, const void *x,
+                            int64_t ldx, int32_t T, int32_t d_in, const int32_t *seg_start,
+                            const int32_t *seg_adapter, const int32_t *seg_prefill_len, int32_t S,
+                            const void *const *const *A_pools, const void *const *const *B_pools, int32_t N,
+                            int32_t rank, float scale, int dtype, int mode, void *workspace, size_t bytes,
+                            void *stream)
+{
+    if (n_proj < 1 || n_proj > PREFT_MAX_PACKED || !y || !ldy || !d_out || !A_pools || !B_pools) return PREFT_EINVAL;
+    if (dtype != PREFT_F32 && dtype != PREFT_BF16) return PREFT_EINVAL;
+    int rc = check_tables(workspace, bytes, seg_start, seg_adapter, seg_prefill_len, S, T, N, mode);
+    if (rc != PREFT_OK) return rc;
+    if (rank < 1 || rank > PREFT_MAX_RANK) return PREFT_EUNSUPPORTED;
+    if (T == 0 || S == 0) return PREFT_OK;
+    if ((rc = check_matrix(x, ldx, d_in, dtype)) != PREFT_OK) return rc;
+    const size_t es = dtype == PREFT_BF16 ? 2 : 4;
+    const char *x0 = reinterpret_cast<const char *>(x), *x1 = x0 + ((size_t)(T - 1) * ldx + d_in) * es;
+    for (int32_t i = 0; i < n_proj; ++i) {
+        if ((rc = check_matrix(y[i], ldy[i], d_out[i], dtype)) != PREFT_OK) return rc;
+        if (!A_pools[i] || !B_pools[i]) return PREFT_EINVAL;
+        const char *y0 = reinterpret_cast<const char *>(y[i]), *y1 = y0 + ((size_t)(T - 1) * ldy[i] + d_out[i]) * es;
+        if (y0 < x1 && x0 < y1) return PREFT_EINVAL;                       // x and y must not overlap
+        // outputs must not share an element: disjoint buffers, or disjoint column ranges of one
+        // buffer (same row stride, both inside one row pitch); anything else that overlaps is refused
+        for (int32_t j = 0; j < i; ++j) {
+            const char *z0 = reinterpret_cast<const char *>(y[j]);
+            const char *z1 = z0 + ((size_t)(T - 1) * ldy[j] + d_out[j]) * es;
+            if (!(y0 < z1 && z0 < y1)) continue;
+            if (ldy[i] != ldy[j]) return PREFT_EINVAL;
+            const bool i_low = y0 < z0;
+            const size_t w_lo = (size_t)(i_low ? d_out[i] : d_out[j]) * es, w_hi = (size_t)(i_low ? d_out[j] : d_out[i]) * es;
+            const size_t delta = (size_t)(i_low ? z0 - y0 : y0 - z0), pitch = (size_t)ldy[i] * es;
+            if (delta < w_lo || delta + w_hi > pitch) return PREFT_EINVAL;
+        }
+    }
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (!(mode & PREFT_SCHEDULE_READY)) {
+        rc = launch_schedule(workspace, seg_start, seg_adapter, seg_prefill_len, S, T, N, mode, st);
+        if (rc != PREFT_OK) return rc;
+    }
+    const int ready = mode | PREFT_SCHEDULE_READY;
+    const bool fused = n_proj > 1 && dtype == PREFT_BF16 && rank <= 16 && (rank % 4) == 0 &&
+                       (g_variant == 0 || g_variant == 3);
+    if (!fused) {                                  // same result, one launch per projection
+        for (int32_t i = 0; i < n_proj; ++i) {
+            rc = preft_lora_apply(y[i], ldy[i], x, ldx, T, d_in, d_out[i], seg_start, seg_adapter, seg_prefill_len, S,
+                                  A_pools[i], B_pools[i], N, rank, scale, dtype, ready, workspace, bytes, stream);
+            if (rc != PREFT_OK) return rc;
+        }
+        return PREFT_OK;
+    }
+    ScheduleView v = view_of(workspace, T, S);
+    ApplyArgs a;
+    a.y = y[0]; a.x = x; a.ldy = ldy[0]; a.ldx = ldx; a.T = T; a.d_in = d_in; a.d_out = d_out[0];
+    a.A_pool = A_pools[0]; a.Bt_pool = B_pools[0]; a.bias_pool = nullptr; a.N = N; a.rank = rank; a.scale = scale;
+    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.gtiles = v.gtiles; a.gathered_only = 0;
+    for (int32_t i = 1; i < n_proj; ++i) {
+        a.more[i - 1].y = y[i]; a.more[i - 1].ldy = ldy[i]; a.more[i - 1].d_out = d_out[i];
+        a.more[i - 1].A_pool = A_pools[i]; a.more[i - 1].Bt_pool = B_pools[i];
+    }
+    if (n_proj == 2) launch_mfma_packed<2>(a, S, st);
+    else             launch_mfma_packed<3>(a, S, st);
+    return check_launch();
 }
 
 int preft_loreft_prepare(void *D, void *Rt, const void *W, const void *R, int32_t d, int32_t rank, int dtype,

@@ -471,3 +471,91 @@ def test_loreft_prepare_rejects_bad_arguments():
     assert call(D.data_ptr() + 2, Rt.data_ptr(), W.data_ptr(), R.data_ptr(), 64, 4, preft.PREFT_BF16) == -3
     assert call(W.data_ptr(), Rt.data_ptr(), W.data_ptr(), R.data_ptr(), 64, 4, preft.PREFT_BF16) == -1   # D aliases W
     torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------------------------------
+# packed projections: several LoRA outputs from one x
+# ---------------------------------------------------------------------------------------
+def _packed_case(dtype, r, d_in, d_outs, fused_buffer, seed, all_tokens, S=30, max_len=150):
+    from oracle import preft_oracle as ora
+    from parity_util import bits, compare, dev_tables, lora_pools_to_device
+    N = 5
+    rng = np.random.Generator(np.random.PCG64(seed))
+    tab = wl.random_segments(rng, S, N + 1, max_len)
+    T = tab.T
+    x = wl.activations(T, d_in, dtype, device="cuda", seed=seed + 1)
+    pools = [wl.lora_pool(N, r, d_in, n, dtype, device="cuda", seed=seed + 10 + i) for i, n in enumerate(d_outs)]
+    if fused_buffer:            # one [T, sum d_out (+ padding)] buffer, outputs are column ranges of it
+        width = sum(d_outs) + 8
+        buf0 = wl.activations(T, width, dtype, device="cuda", seed=seed + 2)
+        buf = buf0.clone()
+        offs = np.concatenate([[0], np.cumsum(d_outs)])
+        ys = [buf[:, offs[i]:offs[i + 1]] for i in range(len(d_outs))]
+        y0s = [buf0[:, offs[i]:offs[i + 1]] for i in range(len(d_outs))]
+    else:
+        y0s = [wl.activations(T, n, dtype, device="cuda", seed=seed + 20 + i) for i, n in enumerate(d_outs)]
+        ys = [y.clone() for y in y0s]
+    tables = [lora_pools_to_device(pl) for pl in pools]
+    ss, sa, sp = dev_tables(tab)
+    ws = preft.new_workspace(T, tab.S)
+    mode = preft.PREFT_ALL_TOKENS if all_tokens else preft.PREFT_PREFILL_ONLY
+    preft.preft_lora_apply_packed(ys, x, ss, sa, sp, [t[0] for t in tables], [t[1] for t in tables], r, 2.0, mode, ws)
+    torch.cuda.synchronize()
+    pos = ora.ALL_POSITIONS if all_tokens else ora.PROMPT_ONLY
+    owner = ora.positions(T, tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, N, pos)
+    worst = 0.0
+    for i, pl in enumerate(pools):
+        want = ora.lora(y0s[i].contiguous().cpu(), x.cpu(), tab.seg_start, tab.seg_adapter, tab.seg_prefill_len,
+                        [a.cpu() for a in pl.A], [b.cpu() for b in pl.B], r, 2.0, pos)
+        worst = max(worst, compare(ys[i], y0s[i], want, owner, dtype))
+    if fused_buffer:            # the padding columns of the fused buffer are not touched
+        assert torch.equal(bits(buf[:, sum(d_outs):].contiguous()), bits(buf0[:, sum(d_outs):].contiguous()))
+    assert torch.equal(bits(x), bits(wl.activations(T, d_in, dtype, device="cuda", seed=seed + 1)))
+    return worst
+
+
+@pytest.mark.parametrize("dtype,r,d_in,d_outs,fused_buffer", [
+    ("bf16", 16, 512, (512, 128, 128), True),        # q, k, v into one fused output
+    ("bf16", 16, 512, (1408, 1408), True),           # gate, up
+    ("bf16", 8, 1000, (264, 520), False),            # widths with 32- and 8-column tails, separate buffers
+    ("bf16", 4, 256, (256, 256, 256), False),
+    ("bf16", 16, 4096, (4096, 1024, 1024), True),    # Llama-3.1-8B q, k, v
+    ("bf16", 32, 512, (512, 128), True),             # rank above the fused path: one launch per projection
+    ("bf16", 3, 512, (512, 128, 128), False),        # odd rank: vector-ALU kernels, one launch each
+    ("f32", 4, 256, (256, 64), True),
+    ("bf16", 16, 512, (384,), False),                # a single projection is an ordinary apply
+])
+def test_packed_projections_match_the_oracle(dtype, r, d_in, d_outs, fused_buffer):
+    for all_tokens in (False, True):
+        worst = _packed_case(dtype, r, d_in, list(d_outs), fused_buffer, 300 + r, all_tokens)
+        print(f"  packed {dtype} r={r} {d_in}->{d_outs} fused_buffer={fused_buffer} all_tokens={all_tokens} worst {worst:.2e}")
+
+
+def test_packed_projections_reject_overlapping_outputs():
+    from parity_util import dev_tables, lora_pools_to_device
+    N, r, d = 3, 16, 256
+    tab = wl.from_lengths([20, 1], [0, 1], [20, 0])
+    x = wl.activations(tab.T, d, "bf16", device="cuda", seed=1)
+    buf = wl.activations(tab.T, 3 * d, "bf16", device="cuda", seed=2)
+    before = buf.clone()
+    pool = wl.lora_pool(N, r, d, d, "bf16", device="cuda", seed=3)
+    Ap, Bp, keep = lora_pools_to_device(pool)
+    ss, sa, sp = dev_tables(tab)
+    ws = preft.new_workspace(tab.T, tab.S)
+    def call(ys, xin=x):
+        preft.preft_lora_apply_packed(ys, xin, ss, sa, sp, [Ap] * len(ys), [Bp] * len(ys), r, 1.0,
+                                      preft.PREFT_PREFILL_ONLY, ws)
+    for ys in ([buf[:, :d], buf[:, :d]],                       # the same range twice
+               [buf[:, :d], buf[:, d // 2:d // 2 + d]],        # ranges that share columns
+               [buf[:, :d], buf[1:, d:2 * d][:tab.T - 1]]):    # rows/dtype mismatch is caught by the binding
+        with pytest.raises((preft.PreftError, ValueError)):
+            call(ys)
+    with pytest.raises(preft.PreftError):                      # x inside the output buffer
+        call([buf[:, :d], buf[:, d:2 * d]], xin=buf[:, 2 * d:])
+    with pytest.raises(preft.PreftError):                      # four projections
+        call([buf[:, :64], buf[:, 64:128], buf[:, 128:192], buf[:, 192:256]])
+    torch.cuda.synchronize()
+    assert torch.equal(buf, before)
+    call([buf[:, :d], buf[:, d:2 * d], buf[:, 2 * d:]])        # three disjoint ranges of one buffer: fine
+    torch.cuda.synchronize()
+    assert not torch.equal(buf, before)
