@@ -120,10 +120,13 @@ def main():
     direft_scale = 1.0
 
     # launches of a step: projections that read the same x (q,k,v; gate,up) go out as one packed call
+    # (the library fuses such a call into one launch for rank 4, 8, 12, 16; other ranks stay one
+    # call and one launch per projection, accounted per projection)
     packs = {"q": "qkv", "k": "qkv", "v": "qkv", "gate": "gate_up", "up": "gate_up"}
+    packed = not args.no_packed and r % 4 == 0 and r <= 16
     groups = []
     for p in projs:
-        key = None if args.no_packed else packs.get(p["name"])
+        key = packs.get(p["name"]) if packed else None
         if key is not None and groups and groups[-1]["key"] == key and groups[-1]["members"][0]["d_in"] == p["d_in"]:
             groups[-1]["members"].append(p)
         else:
@@ -212,7 +215,7 @@ def main():
     # HBM traffic of the dominant kernel comes from two rocprofv3 --pmc runs of this same command;
     # their summary is committed under profiles/ and quoted here when the configuration matches.
     if projs and args.config == "llama8b_lora" and r == 16 and not (args.variant or args.waves or args.rowblocks
-                                                                     or args.ldpad or args.only or args.no_packed):
+                                                                     or args.ldpad or args.only or not packed):
         try:
             with open(os.path.join(ROOT, "profiles", "lora_tile_kernel_llama8b_rank16_hbm_traffic.txt")) as f:
                 for line in f:

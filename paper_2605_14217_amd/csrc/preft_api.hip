@@ -111,12 +111,14 @@ void launch_mfma_stream(const ApplyArgs &a, int64_t S, int mb, int waves, hipStr
     launch_mfma<NB, 1, 4, 0, DIREFT>(a, S, stream);
 }
 
-// DiReFT with the tile held in registers between the sweeps: 8 wavefronts, HUNITS units of 128
-// columns each (register budget: 16 VGPRs per unit)
+// DiReFT with the tile held in registers between the sweeps (rank <= 16): 8 wavefronts, HUNITS
+// units of 128 columns each (register budget: 16 VGPRs per unit).  From rank 32 up the factor
+// sweeps of a 16-row tile outweigh its activations and the register file has no room left to
+// run them ahead, so those ranks take 32-row tiles (rank 32) or the row-split kernel (rank >= 64).
 template <int NB>
 bool launch_mfma_resident(const ApplyArgs &a, int64_t S, hipStream_t stream)
 {
-    if constexpr (NB > 4) {
+    if constexpr (NB > 1) {
         return false;
     } else {
         const int units = ((a.d_in >> 7) + 7) / 8;        // whole units per wavefront
@@ -124,11 +126,9 @@ bool launch_mfma_resident(const ApplyArgs &a, int64_t S, hipStream_t stream)
             launch_mfma<NB, 1, 8, 4, true>(a, S, stream);
             return true;
         }
-        if constexpr (NB <= 2) {
-            if (units <= 8) {
-                launch_mfma<NB, 1, 8, 8, true>(a, S, stream);
-                return true;
-            }
+        if (units <= 8) {
+            launch_mfma<NB, 1, 8, 8, true>(a, S, stream);
+            return true;
         }
         return false;
     }
@@ -159,19 +159,31 @@ void launch_mfma_nb(const ApplyArgs &a, int64_t S, hipStream_t stream)
 {
     // rank >= 32: the factors outweigh a 16-row tile's activations, so more rows share them:
     // the row-split kernel with 8 wavefronts x 16 rows (a whole 128-row chunk per workgroup)
-    int mb = g_rowblocks ? g_rowblocks : 1;
-    // rank <= 16 (column-split kernel): 8 wavefronts per 16-row tile on small batches, where a
-    // shorter workgroup lifetime shortens the kernel's tail; 4 on large ones
-    int waves = g_waves ? (g_waves == 8 ? 8 : 4) : ((NB >= 2 || a.T <= 65536) ? 8 : 4);
+    const int wide_mb = g_rowblocks ? g_rowblocks : 1;
+    const int wide_waves = g_waves ? (g_waves == 8 ? 8 : 4) : ((NB >= 2 || a.T <= 65536) ? 8 : 4);
+    // column-split kernel.  rank <= 16: 8 wavefronts per 16-row tile on small batches, where a
+    // shorter workgroup lifetime shortens the kernel's tail, 4 on large ones; rank 32 (widths the
+    // row-split kernel does not take): 32-row tiles of 4 wavefronts
+    const int mb = g_rowblocks ? g_rowblocks : (NB == 2 ? 2 : 1);
+    const int waves = g_waves ? (g_waves == 8 ? 8 : 4) : (NB == 2 ? 4 : wide_waves);
     if constexpr (DIREFT) {
         if (g_waves == 0 && g_variant != 4 && launch_mfma_resident<NB>(a, S, stream)) return;
+        // rank 32: 32-row tiles of the column-split kernel (half the factor traffic per row of a
+        // 16-row tile, and the tile's second read mostly still finds it in the memory-side cache)
+        // measured ahead of the resident and row-split shapes at d = 4096 and d = 8192
+        if constexpr (NB == 2) {
+            if (g_waves == 0 && g_variant == 0 && g_rowblocks == 0) {
+                launch_mfma<2, 2, 4, 0, true>(a, S, stream);
+                return;
+            }
+        }
     }
-    if (g_variant != 3 && launch_mfma_wide<NB, DIREFT>(a, S, mb, waves, stream)) {
+    if (g_variant != 3 && launch_mfma_wide<NB, DIREFT>(a, S, wide_mb, wide_waves, stream)) {
         // the row-split kernel shares one adapter's factors among the 128 rows of a chunk;
         // gathered tiles (16 rows of an adapter) go to the column-split kernel
         ApplyArgs g = a;
         g.gathered_only = 1;
-        launch_mfma_stream<NB, DIREFT>(g, S, 1, NB >= 8 ? 4 : 8, stream);
+        launch_mfma_stream<NB, DIREFT>(g, S, 1, NB >= 2 ? 4 : 8, stream);
         return;
     }
     launch_mfma_stream<NB, DIREFT>(a, S, mb, waves, stream);
