@@ -120,10 +120,10 @@ def main():
     direft_scale = 1.0
 
     # launches of a step: projections that read the same x (q,k,v; gate,up) go out as one packed call
-    # (the library fuses such a call into one launch for rank 4, 8, 12, 16; other ranks stay one
+    # (the library fuses such a call into one launch for rank 1-4, 8, 12, 16; other ranks stay one
     # call and one launch per projection, accounted per projection)
     packs = {"q": "qkv", "k": "qkv", "v": "qkv", "gate": "gate_up", "up": "gate_up"}
-    packed = not args.no_packed and r % 4 == 0 and r <= 16
+    packed = not args.no_packed and (r <= 3 or (r % 4 == 0 and r <= 16))
     groups = []
     for p in projs:
         key = packs.get(p["name"]) if packed else None

@@ -230,6 +230,18 @@ void launch_valu(const ApplyArgs &a, int64_t S, hipStream_t stream)
                            dim3(64), 0, stream, a);
 }
 
+// packed projections at ranks 1..3 (vector-ALU kernel)
+template <int SLICES>
+void launch_valu_packed(const ApplyArgs &a, int64_t S, hipStream_t stream)
+{
+    constexpr int RB = 4;
+    switch (a.rank) {
+    case 1:  hipLaunchKernelGGL((valu_tile_kernel<1, RB, 4, false, SLICES>), dim3(tile_grid(a, S, RB * 4)), dim3(256), 0, stream, a); break;
+    case 2:  hipLaunchKernelGGL((valu_tile_kernel<2, RB, 4, false, SLICES>), dim3(tile_grid(a, S, RB * 4)), dim3(256), 0, stream, a); break;
+    default: hipLaunchKernelGGL((valu_tile_kernel<3, RB, 4, false, SLICES>), dim3(tile_grid(a, S, RB * 4)), dim3(256), 0, stream, a); break;
+    }
+}
+
 template <bool DIREFT>
 void launch_valu_rank(const ApplyArgs &a, int64_t S, hipStream_t stream)
 {
@@ -403,8 +415,11 @@ int preft_lora_apply_packed(int32_t n_proj, void *const *y, const int64_t *ldy, 
         if (rc != PREFT_OK) return rc;
     }
     const int ready = mode | PREFT_SCHEDULE_READY;
-    const bool fused = n_proj > 1 && dtype == PREFT_BF16 && rank <= 16 && (rank % 4) == 0 &&
-                       (g_variant == 0 || g_variant == 3);
+    const bool fused_mfma = n_proj > 1 && dtype == PREFT_BF16 && rank <= 16 && (rank % 4) == 0 &&
+                            (g_variant == 0 || g_variant == 3);
+    const bool fused_valu = n_proj > 1 && dtype == PREFT_BF16 && rank <= 3 && (g_variant == 0 || g_variant == 2) &&
+                            (g_waves == 0 || g_waves == 4);
+    const bool fused = fused_mfma || fused_valu;
     if (!fused) {                                  // same result, one launch per projection
         for (int32_t i = 0; i < n_proj; ++i) {
             rc = preft_lora_apply(y[i], ldy[i], x, ldx, T, d_in, d_out[i], seg_start, seg_adapter, seg_prefill_len, S,
@@ -422,8 +437,13 @@ int preft_lora_apply_packed(int32_t n_proj, void *const *y, const int64_t *ldy, 
         a.more[i - 1].y = y[i]; a.more[i - 1].ldy = ldy[i]; a.more[i - 1].d_out = d_out[i];
         a.more[i - 1].A_pool = A_pools[i]; a.more[i - 1].Bt_pool = B_pools[i];
     }
-    if (n_proj == 2) launch_mfma_packed<2>(a, S, st);
-    else             launch_mfma_packed<3>(a, S, st);
+    if (fused_mfma) {
+        if (n_proj == 2) launch_mfma_packed<2>(a, S, st);
+        else             launch_mfma_packed<3>(a, S, st);
+    } else {
+        if (n_proj == 2) launch_valu_packed<2>(a, S, st);
+        else             launch_valu_packed<3>(a, S, st);
+    }
     return check_launch();
 }
 

@@ -14,6 +14,9 @@
 //
 // A workgroup of WAVES wavefronts owns a tile of RB * WAVES consecutive rows of a chunk;
 // wavefronts never exchange data.
+//
+// SLICES > 1 (LoRA only): packed projections, as in mfma_tile_kernel: the outputs share x, so
+// one shrink sweep feeds SLICES * RANK partial sums per row and one expand sweep per output follows.
 #pragma once
 #include "common.hpp"
 #include "mfma_kernel.hpp"   // xcd_unit
@@ -28,10 +31,12 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc)
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), acc, false);
 }
 
-template <int RANK, int RB, int WAVES, bool DIREFT>
+template <int RANK, int RB, int WAVES, bool DIREFT, int SLICES = 1>
 __global__ __launch_bounds__(WAVES * 64) void valu_tile_kernel(ApplyArgs p)
 {
     constexpr int R = RB * WAVES;
+    constexpr int RT = RANK * SLICES;                         // partial sums per row in the shrink sweep
+    static_assert(SLICES == 1 || !DIREFT, "packed projections are a LoRA feature");
     static_assert(CHUNK_ROWS % R == 0, "tile height must divide the chunk height");
 
     int n_chunk_units;
@@ -46,33 +51,34 @@ __global__ __launch_bounds__(WAVES * 64) void valu_tile_kernel(ApplyArgs p)
     const int wave_row0 = wave * RB;
     if (wave_row0 >= n_rows) return;
 
-    gcptr_t A  = as_global(p.A_pool[adapter]);
-    gcptr_t Bt = as_global(p.Bt_pool[adapter]);
-    const int64_t ldx_b = p.ldx * 2, ldy_b = p.ldy * 2;
+    gcptr_t A[SLICES];
+    A[0] = as_global(slice_A<0>(p)[adapter]);
+    if constexpr (SLICES > 1) A[1] = as_global(slice_A<1>(p)[adapter]);
+    if constexpr (SLICES > 2) A[2] = as_global(slice_A<2>(p)[adapter]);
+    const int64_t ldx_b = p.ldx * 2;
 
     // Row slots past the end of the tile alias its last row (which this wavefront owns): they
     // load the same bytes, compute the same values and store the same bits, so no access in
     // the sweeps below is conditional.
     gcptr_t xp[RB];
-    gptr_t yp[RB];
+    int64_t rows[RB];
 #pragma unroll
     for (int i = 0; i < RB; ++i) {
-        const int64_t row = tile.row(wave_row0 + i);
-        xp[i] = as_global(p.x) + row * ldx_b;
-        yp[i] = as_global(p.y) + row * ldy_b;
+        rows[i] = tile.row(wave_row0 + i);
+        xp[i] = as_global(p.x) + rows[i] * ldx_b;
     }
 
     // ---------------------------------------------------------------- shrink
-    float z[RB][RANK];
+    float z[RB][RT];
 #pragma unroll
     for (int i = 0; i < RB; ++i)
 #pragma unroll
-        for (int k = 0; k < RANK; ++k) z[i][k] = 0.f;
+        for (int k = 0; k < RT; ++k) z[i][k] = 0.f;
 
     const int nvec_in = p.d_in >> 3;                          // 16-byte vectors per row
-    auto shrink_step = [&](const u32x4_t (&xv)[RB], const u32x4_t (&av)[RANK]) {
+    auto shrink_step = [&](const u32x4_t (&xv)[RB], const u32x4_t (&av)[RT]) {
 #pragma unroll
-        for (int k = 0; k < RANK; ++k)
+        for (int k = 0; k < RT; ++k)
 #pragma unroll
             for (int i = 0; i < RB; ++i)
 #pragma unroll
@@ -81,68 +87,79 @@ __global__ __launch_bounds__(WAVES * 64) void valu_tile_kernel(ApplyArgs p)
     };
     int c = lane;
     for (; c + 64 < nvec_in; c += 128) {                      // two sweeps in flight
-        u32x4_t xv0[RB], xv1[RB], av0[RANK], av1[RANK];
+        u32x4_t xv0[RB], xv1[RB], av0[RT], av1[RT];
 #pragma unroll
         for (int i = 0; i < RB; ++i) {
             xv0[i] = ld16(xp[i] + (int64_t)c * 16);
             xv1[i] = ld16(xp[i] + (int64_t)(c + 64) * 16);
         }
 #pragma unroll
-        for (int k = 0; k < RANK; ++k) {
-            av0[k] = ld16(A + ((int64_t)k * p.d_in + (int64_t)c * 8) * 2);
-            av1[k] = ld16(A + ((int64_t)k * p.d_in + (int64_t)(c + 64) * 8) * 2);
+        for (int k = 0; k < RT; ++k) {
+            av0[k] = ld16(A[k / RANK] + ((int64_t)(k % RANK) * p.d_in + (int64_t)c * 8) * 2);
+            av1[k] = ld16(A[k / RANK] + ((int64_t)(k % RANK) * p.d_in + (int64_t)(c + 64) * 8) * 2);
         }
         shrink_step(xv0, av0);
         shrink_step(xv1, av1);
     }
     for (; c < nvec_in; c += 64) {
-        u32x4_t xv[RB], av[RANK];
+        u32x4_t xv[RB], av[RT];
 #pragma unroll
         for (int i = 0; i < RB; ++i) xv[i] = ld16(xp[i] + (int64_t)c * 16);
 #pragma unroll
-        for (int k = 0; k < RANK; ++k) av[k] = ld16(A + ((int64_t)k * p.d_in + (int64_t)c * 8) * 2);
+        for (int k = 0; k < RT; ++k) av[k] = ld16(A[k / RANK] + ((int64_t)(k % RANK) * p.d_in + (int64_t)c * 8) * 2);
         shrink_step(xv, av);
     }
 #pragma unroll
-    for (int k = 0; k < RANK; ++k) {
+    for (int k = 0; k < RT; ++k) {
         float bias = 0.f;
         if (DIREFT && p.bias_pool) bias = Elem<bf16_tag>::load1(as_global(p.bias_pool[adapter]), k);
 #pragma unroll
         for (int i = 0; i < RB; ++i) z[i][k] = (wave_sum(z[i][k]) + bias) * p.scale;
     }
 
-    // ---------------------------------------------------------------- expand
-    const int nvec_out = p.d_out >> 3;
-    for (int c = lane; c < nvec_out; c += 64) {
-        // 8 columns x RANK factors, contiguous: RANK 16-byte vectors
-        float w[8 * RANK];
-        gcptr_t wp = Bt + (int64_t)c * 8 * RANK * 2;
+    // ---------------------------------------------------------------- expand (once per output)
+    auto expand_slice = [&](auto sl_tag) {
+        constexpr int SL = decltype(sl_tag)::value;
+        gcptr_t Bt = as_global(slice_Bt<SL>(p)[adapter]);
+        const int64_t ldy_b = slice_ldy<SL>(p) * 2;
+        gptr_t yp[RB];
 #pragma unroll
-        for (int j = 0; j < RANK; ++j) {
-            const u32x4_t raw = ld16(wp + j * 16);
+        for (int i = 0; i < RB; ++i) yp[i] = as_global(slice_y<SL>(p)) + rows[i] * ldy_b;
+        const int nvec_out = slice_d_out<SL>(p) >> 3;
+        for (int c = lane; c < nvec_out; c += 64) {
+            // 8 columns x RANK factors, contiguous: RANK 16-byte vectors
+            float w[8 * RANK];
+            gcptr_t wp = Bt + (int64_t)c * 8 * RANK * 2;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                w[j * 8 + 2 * q] = bf16_lo(raw[q]);
-                w[j * 8 + 2 * q + 1] = bf16_hi(raw[q]);
+            for (int j = 0; j < RANK; ++j) {
+                const u32x4_t raw = ld16(wp + j * 16);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    w[j * 8 + 2 * q] = bf16_lo(raw[q]);
+                    w[j * 8 + 2 * q + 1] = bf16_hi(raw[q]);
+                }
+            }
+            u32x4_t yv[RB];
+#pragma unroll
+            for (int i = 0; i < RB; ++i) yv[i] = ld16(yp[i] + (int64_t)c * 16);
+#pragma unroll
+            for (int i = 0; i < RB; ++i) {
+                float out[8];
+                Elem<bf16_tag>::unpack(yv[i], out);
+#pragma unroll
+                for (int col = 0; col < 8; ++col) {
+                    float d = 0.f;
+#pragma unroll
+                    for (int k = 0; k < RANK; ++k) d = fmaf(w[col * RANK + k], z[i][SL * RANK + k], d);
+                    out[col] += d;
+                }
+                st16(yp[i] + (int64_t)c * 16, Elem<bf16_tag>::pack(out));
             }
         }
-        u32x4_t yv[RB];
-#pragma unroll
-        for (int i = 0; i < RB; ++i) yv[i] = ld16(yp[i] + (int64_t)c * 16);
-#pragma unroll
-        for (int i = 0; i < RB; ++i) {
-            float out[8];
-            Elem<bf16_tag>::unpack(yv[i], out);
-#pragma unroll
-            for (int col = 0; col < 8; ++col) {
-                float d = 0.f;
-#pragma unroll
-                for (int k = 0; k < RANK; ++k) d = fmaf(w[col * RANK + k], z[i][k], d);
-                out[col] += d;
-            }
-            st16(yp[i] + (int64_t)c * 16, Elem<bf16_tag>::pack(out));
-        }
-    }
+    };
+    expand_slice(std::integral_constant<int, 0>{});
+    if constexpr (SLICES > 1) expand_slice(std::integral_constant<int, 1>{});
+    if constexpr (SLICES > 2) expand_slice(std::integral_constant<int, 2>{});
 }
 
 }  // namespace preft

@@ -521,7 +521,10 @@ def _packed_case(dtype, r, d_in, d_outs, fused_buffer, seed, all_tokens, S=30, m
     ("bf16", 4, 256, (256, 256, 256), False),
     ("bf16", 16, 4096, (4096, 1024, 1024), True),    # Llama-3.1-8B q, k, v
     ("bf16", 32, 512, (512, 128), True),             # rank above the fused path: one launch per projection
-    ("bf16", 3, 512, (512, 128, 128), False),        # odd rank: vector-ALU kernels, one launch each
+    ("bf16", 3, 512, (512, 128, 128), False),        # ranks 1..3: fused by the vector-ALU kernel
+    ("bf16", 1, 4096, (4096, 1024, 1024), True),
+    ("bf16", 2, 520, (1408, 264), False),
+    ("bf16", 5, 512, (512, 128), True),              # a rank neither kernel fuses: one launch each
     ("f32", 4, 256, (256, 64), True),
     ("bf16", 16, 512, (384,), False),                # a single projection is an ordinary apply
 ])
