@@ -252,7 +252,8 @@ int preft_slots_stats(const preft_slots_t *m, int64_t *stats);
 
 /*
  * Copies the schedule counters of a workspace to the host: counts[0] = multi-row work
- * units, counts[1] = single rows handled by the per-row path, counts[2] = active rows.
+ * units (chunks of up to 128 rows of one segment), counts[1] = rows of short segments (at most
+ * 4 active rows, e.g. decode tokens), which run as gathered tiles, counts[2] = active rows.
  * `counts` is a host pointer to 3 int32.  This call synchronises `stream`; it is meant
  * for tests, statistics and debugging, never for the serving loop.
  */

@@ -1,13 +1,12 @@
 // Per-row ("batched gather matrix-vector") kernel: one workgroup applies one adapter to a group
 // of at most GROUP_ROWS rows that share it.
 //
-// This is the path of the conventional all-position baseline for decode tokens -- every row
-// gathers its own adapter's factors, which is the memory-bound cost the paper's Sec. 3.2
-// attributes to per-request adapters at decode time -- and of any segment with at most
-// SHORT_ROWS active rows.  The scheduler sorts such rows by adapter, so an adapter's factors
-// are streamed once per group of rows rather than once per row.  The same code is the generic
-// fallback for element types and ranks the tile kernels do not cover (fp32; bf16 ranks that
-// are neither <= 8 nor multiples of 4), where a chunk is cut into groups of consecutive rows.
+// This is the generic fallback for element types and ranks the tile kernels do not cover (fp32;
+// bf16 ranks that are neither <= 8 nor multiples of 4): a chunk is cut into groups of consecutive
+// rows, and the short rows (decode tokens of the all-position baseline, segments with at most
+// SHORT_ROWS active rows), which the scheduler has sorted by adapter and cut into gathered tiles,
+// into groups of rows of one adapter -- an adapter's factors are streamed once per group rather
+// than once per row, the per-request gather cost the paper's Sec. 3.2 attributes to decode time.
 //
 //   shrink  (Eq. 2: A x;  Eq. 3: A h + b):  wavefront w owns ranks w, w+4, ... (two at a time);
 //           its 64 lanes sweep the rows with 16-byte loads, every factor vector is used for all
