@@ -65,3 +65,47 @@ def test_fullsize_direft(config, rank, all_tokens):
     rows = wl.sample_rows(tab, 2, max_rows=1200)
     worst, counts = run_direft_case(tab, pool, h, dtype, 1.0 / np.sqrt(rank), all_tokens, rows=rows)
     print(f"  T={tab.T} S={tab.S} rows checked={len(rows)} worst {worst:.2e} counts {counts}")
+
+
+PACKED = [("llama8b_lora", ("q", "k", "v"), 16, False), ("llama8b_lora", ("gate", "up"), 16, False),
+          ("llama8b_lora", ("q", "k", "v"), 1, True), ("llama70b_lora", ("q", "k", "v"), 16, True),
+          ("llama70b_lora", ("gate", "up"), 1, False)]
+
+
+@pytest.mark.parametrize("config,projs,rank,all_tokens", PACKED,
+                         ids=[f"{c}-{'+'.join(p)}-r{r}-{'all' if a else 'prefill'}" for c, p, r, a in PACKED])
+def test_fullsize_packed_lora(config, projs, rank, all_tokens):
+    """The packed launches of the benchmark step (q+k+v, gate+up), at full size, on sampled rows."""
+    from oracle import preft_oracle as ora
+    from parity_util import compare, dev_tables, lora_pools_to_device
+    cfg = wl.CONFIGS[config]
+    N = cfg["N"]
+    shapes = [cfg["lora_shapes"][p] for p in projs]
+    d_in = shapes[0][0]
+    assert all(s[0] == d_in for s in shapes)
+    tab = wl.make_segments(config, seed=0)
+    x = wl.activations(tab.T, d_in, "bf16", device="cuda", seed=71)
+    pools = [wl.lora_pool(N, rank, d_in, n, "bf16", device="cuda", seed=72 + i) for i, (_, n) in enumerate(shapes)]
+    y0s = [wl.activations(tab.T, n, "bf16", device="cuda", seed=80 + i) for i, (_, n) in enumerate(shapes)]
+    ys = [y.clone() for y in y0s]
+    tables = [lora_pools_to_device(pl) for pl in pools]
+    ss, sa, sp = dev_tables(tab)
+    ws = preft.new_workspace(tab.T, tab.S)
+    mode = preft.PREFT_ALL_TOKENS if all_tokens else preft.PREFT_PREFILL_ONLY
+    preft.preft_lora_apply_packed(ys, x, ss, sa, sp, [t[0] for t in tables], [t[1] for t in tables], rank,
+                                  cfg["lora_scale"], mode, ws)
+    torch.cuda.synchronize()
+    rows = wl.sample_rows(tab, 2, max_rows=1200)
+    idx = torch.from_numpy(np.asarray(rows)).to("cuda")
+    pos = ora.ALL_POSITIONS if all_tokens else ora.PROMPT_ONLY
+    owner = ora.positions(tab.T, tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, N, pos)
+    needed = set(np.unique(owner[rows][owner[rows] >= 0]).tolist())
+    x_rows = x[idx].cpu()
+    worst = 0.0
+    for i, pl in enumerate(pools):
+        A = [pl.A[j].cpu() if j in needed else None for j in range(N)]
+        B = [pl.B[j].cpu() if j in needed else None for j in range(N)]
+        want = ora.lora(y0s[i][idx].cpu(), x_rows, tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, A, B, rank,
+                        cfg["lora_scale"], pos, rows=rows, gathered=True)
+        worst = max(worst, compare(ys[i], y0s[i], want, owner, "bf16", rows=rows))
+    print(f"  T={tab.T} S={tab.S} rows checked={len(rows)} outputs={len(projs)} worst {worst:.2e}")
