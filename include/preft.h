@@ -103,7 +103,8 @@ size_t preft_workspace_bytes(int32_t T, int32_t S);
  * The schedule depends on (tables, S, T, N, position set) only -- not on dtype, rank or
  * widths -- so one schedule serves every projection and layer of an engine step: pass the
  * same workspace with mode | PREFT_SCHEDULE_READY to the apply calls that follow on the
- * same stream.
+ * same stream, with the same T, S, N and position set (the launch sizes of an apply call are
+ * bounds computed from T, S and N; with other values part of the batch would be skipped).
  *
  * mode: PREFT_PREFILL_ONLY or PREFT_ALL_TOKENS.
  */
