@@ -59,6 +59,9 @@ def main():
     ap.add_argument("--trace-batch", type=int, default=32)
     ap.add_argument("--trace-adapters", type=int, default=32)
     ap.add_argument("--trace-mix", default="uniform", choices=["identical", "uniform", "skewed", "distinct"])
+    ap.add_argument("--trace-slots", type=int, default=0,
+                    help="serve the trace through the adapter slot manager with this many device slots "
+                         "(0: every adapter resident); --trace-adapters may then exceed the configuration's pool")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -136,25 +139,28 @@ def main():
 
     singles = [dict(key=None, members=[p], name=p["name"]) for p in projs]
 
-    def step(mode, tables=(ss, sa, sp), T_=T, events=None, groups=groups):
+    def step(mode, tables=(ss, sa, sp), T_=T, events=None, groups=groups, pools=None):
+        # pools: {projection: (A table, B table), "direft": (W1, W2t, b tables), "N": slots} from a slot manager
         s0, s1, s2 = tables
-        preft.preft_schedule(ws, s0, s1, s2, T_, N, mode)
+        preft.preft_schedule(ws, s0, s1, s2, T_, N if pools is None else pools["N"], mode)
         ready = mode | preft.PREFT_SCHEDULE_READY
         for i, g_ in enumerate(groups):
             m = g_["members"]
             if events is not None:
                 events[i][0].record()
+            Aps = [q["Ap"] if pools is None else pools[q["name"]][0] for q in m]
+            Bps = [q["Bp"] if pools is None else pools[q["name"]][1] for q in m]
             if len(m) == 1:
-                preft.preft_lora_apply(m[0]["y"][:T_], m[0]["x"][:T_], s0, s1, s2, m[0]["Ap"], m[0]["Bp"], r, scale,
-                                       ready, ws)
+                preft.preft_lora_apply(m[0]["y"][:T_], m[0]["x"][:T_], s0, s1, s2, Aps[0], Bps[0], r, scale, ready, ws)
             else:
-                preft.preft_lora_apply_packed([q["y"][:T_] for q in m], m[0]["x"][:T_], s0, s1, s2,
-                                              [q["Ap"] for q in m], [q["Bp"] for q in m], r, scale, ready, ws)
+                preft.preft_lora_apply_packed([q["y"][:T_] for q in m], m[0]["x"][:T_], s0, s1, s2, Aps, Bps, r, scale,
+                                              ready, ws)
             if events is not None:
                 events[i][1].record()
         if events is not None:
             events[len(groups)][0].record()
-        preft.preft_direft_apply(h[:T_], s0, s1, s2, W1p, W2tp, bp, r, direft_scale, ready, ws)
+        d1, d2, d3 = (W1p, W2tp, bp) if pools is None else pools["direft"]
+        preft.preft_direft_apply(h[:T_], s0, s1, s2, d1, d2, d3, r, direft_scale, ready, ws)
         if events is not None:
             events[len(groups)][1].record()
 
@@ -279,16 +285,39 @@ def main():
     # prompt are launched eagerly.  Only the adapter kernels run: the ratio says how the adapter
     # cost splits over a serving run, it is not an end-to-end throughput ratio.
     if not args.no_trace and not args.no_extras:
-        req = wl.request_stream(args.trace_requests, min(args.trace_adapters, N), args.trace_mix, l_max=2048,
-                                seed=args.seed)
+        paged = args.trace_slots > 0
+        n_trace_adapters = args.trace_adapters if paged else min(args.trace_adapters, N)
+        req = wl.request_stream(args.trace_requests, n_trace_adapters, args.trace_mix, l_max=2048, seed=args.seed)
         epochs = list(wl.fcfs_steps(req, args.trace_batch))
         Bmax = args.trace_batch
+        mgr, trace_pools = None, None
+        if paged:
+            # the paper's paged setting (Sec. 4; App. E.2): the catalogue in pinned host memory, at most
+            # --trace-slots adapters in device slots; a step first makes its adapters resident.  One
+            # random matrix per part serves every adapter: only the traffic matters here.
+            shapes = []
+            for p_ in projs:
+                shapes += [(r, p_["d_in"]), (p_["d_out"], r)]
+            shapes += [(r, d_res), (d_res, r), (r,)]
+            host = [torch.randn(sh).to(torch.bfloat16).contiguous() for sh in shapes]
+            mgr = preft.preft_slots_create(n_trace_adapters, args.trace_slots, [t.numel() * 2 for t in host])
+            for a_ in range(n_trace_adapters):
+                for pi, t in enumerate(host):
+                    preft.preft_slots_store(mgr, a_, pi, t)
+            trace_pools = {p_["name"]: (preft.preft_slots_pool(mgr, 2 * i), preft.preft_slots_pool(mgr, 2 * i + 1))
+                           for i, p_ in enumerate(projs)}
+            nb = 2 * len(projs)
+            trace_pools["direft"] = tuple(preft.preft_slots_pool(mgr, nb + j) for j in range(3))
+            trace_pools["N"] = preft.preft_slots_stats(mgr)["n_slots"]
         st = [torch.zeros(Bmax + 1, dtype=torch.int32, device=dev), torch.zeros(Bmax, dtype=torch.int32, device=dev),
               torch.zeros(Bmax, dtype=torch.int32, device=dev)]
 
         def upload(t_):
+            ids = t_.seg_adapter
+            if paged:                  # adapter ids -> slot ids; missing adapters are copied in on this stream
+                ids = np.asarray(preft.preft_slots_acquire(mgr, ids.tolist()), dtype=np.int32)
             st[0][:t_.S + 1].copy_(torch.from_numpy(t_.seg_start.copy()))
-            st[1][:t_.S].copy_(torch.from_numpy(t_.seg_adapter.copy()))
+            st[1][:t_.S].copy_(torch.from_numpy(ids.copy()))
             st[2][:t_.S].copy_(torch.from_numpy(t_.seg_prefill_len.copy()))
             return (st[0][:t_.S + 1], st[1][:t_.S], st[2][:t_.S])
 
@@ -297,25 +326,24 @@ def main():
             for t_, repeat in epochs:
                 if t_.T > T:
                     raise RuntimeError("trace step larger than the benchmark buffers")
-                views = upload(t_)
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 decode_only = not bool(t_.seg_prefill_len.any())
+                if decode_only and t_.S not in graphs:
+                    views = upload(t_)
+                    step(mode, views, t_.T, pools=trace_pools)
+                    torch.cuda.synchronize()
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g):
+                        step(mode, views, t_.T, pools=trace_pools)
+                    graphs[t_.S] = g
+                e0.record()                      # the bracket holds the table upload and any adapter copies
+                views = upload(t_)
                 if decode_only:
-                    if t_.S not in graphs:
-                        step(mode, views, t_.T)
-                        torch.cuda.synchronize()
-                        g = torch.cuda.CUDAGraph()
-                        with torch.cuda.graph(g):
-                            step(mode, views, t_.T)
-                        graphs[t_.S] = g
-                    e0.record()
                     for _ in range(repeat):
                         graphs[t_.S].replay()
-                    e1.record()
                 else:
-                    e0.record()
-                    step(mode, views, t_.T)
-                    e1.record()
+                    step(mode, views, t_.T, pools=trace_pools)
+                e1.record()
                 pairs.append((decode_only, e0, e1))
             torch.cuda.synchronize()
             ms_dec = sum(a.elapsed_time(b) for d_, a, b in pairs if d_)
@@ -328,7 +356,7 @@ def main():
         n_dec_steps = sum(rep for t_, rep in epochs if not t_.seg_prefill_len.any())
         out["fcfs_trace"] = {
             "requests": len(req.prompt_len), "in_flight": Bmax, "mix": args.trace_mix,
-            "adapters": int(min(args.trace_adapters, N)), "l_max": 2048,
+            "adapters": int(n_trace_adapters), "l_max": 2048,
             "engine_steps": int(n_steps), "decode_only_steps": int(n_dec_steps),
             "prompt_rows": int(req.prompt_len.sum()), "decode_rows": int((req.output_len - 1).sum()),
             "prefill_only_ms": {"steps_with_prompts": round(pre_p, 2), "decode_only_steps": round(dec_p, 2)},
@@ -338,6 +366,13 @@ def main():
             "us_per_decode_only_step": {"all_token": round(dec_a / max(n_dec_steps, 1) * 1e3, 2),
                                         "prefill_only": round(dec_p / max(n_dec_steps, 1) * 1e3, 2)},
         }
+        if paged:
+            torch.cuda.synchronize()
+            stats = preft.preft_slots_stats(mgr)           # both replays together
+            out["fcfs_trace"]["slot_manager"] = {"device_slots": stats["n_slots"], "hits": stats["hits"],
+                                                 "misses": stats["misses"], "evictions": stats["evictions"],
+                                                 "MB_copied": round(stats["bytes_copied"] / 1e6, 1)}
+            preft.preft_slots_destroy(mgr)
 
     # ---- CPU oracle on a sample of the same batch ---------------------------------------------
     if not args.no_cpu_baseline:

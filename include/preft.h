@@ -85,6 +85,7 @@ enum {
 
 #define PREFT_MAX_RANK 128
 #define PREFT_MAX_PACKED 3      /* projections one packed call may fuse */
+#define PREFT_MAX_PARTS 32      /* matrices per adapter a slot manager may hold */
 
 /*
  * Bytes of device workspace that hold the schedule of a batch of T rows in S segments.
@@ -211,8 +212,8 @@ int preft_loreft_apply(void *h, int64_t ldh, int32_t T, int32_t d,
  * App. E.2: the active set in GPU memory, the catalogue in host memory; App. D.4: weights at
  * stable addresses are refreshed in place so the next launch or graph replay sees them).
  *
- * A manager owns: a pinned host store with one record per adapter (n_parts matrices of
- * part_bytes[p] bytes each, e.g. {A, B} for LoRA or {W1, W2t, b} for DiReFT), a device slab
+ * A manager owns: a pinned host store with one record per adapter (n_parts <= PREFT_MAX_PARTS
+ * matrices of part_bytes[p] bytes each, e.g. {A, B} for LoRA or {W1, W2t, b} for DiReFT), a device slab
  * of n_slots records at addresses that never change, and per part a device table of n_slots
  * pointers (preft_slots_pool) to pass as A_pool / B_pool / ... with N = n_slots.  The apply
  * calls then take SLOT ids in seg_adapter: before a batch, preft_slots_acquire maps the

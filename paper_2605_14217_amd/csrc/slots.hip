@@ -24,7 +24,7 @@ struct preft_slots {
     std::vector<int32_t> slot_of;                  // per adapter: slot or -1
     std::vector<int32_t> adapter_in;               // per slot: adapter or -1
     std::vector<int64_t> last_use;                 // per slot: tick of the last acquire that named it
-    std::vector<int64_t> stored;                   // per adapter: bit p set once part p was stored
+    std::vector<int64_t> stored;                   // per adapter: bit p set once part p was stored (PREFT_MAX_PARTS <= 64)
     int64_t tick = 0, hits = 0, misses = 0, evictions = 0, bytes_copied = 0;
 };
 
@@ -49,7 +49,7 @@ extern "C" {
 int preft_slots_create(preft_slots_t **out, int32_t n_adapters, int32_t n_slots, int32_t n_parts,
                        const size_t *part_bytes)
 {
-    if (!out || n_adapters < 1 || n_slots < 1 || n_parts < 0 || n_parts > 8 || (n_parts > 0 && !part_bytes))
+    if (!out || n_adapters < 1 || n_slots < 1 || n_parts < 0 || n_parts > PREFT_MAX_PARTS || (n_parts > 0 && !part_bytes))
         return PREFT_EINVAL;
     preft_slots *m = new (std::nothrow) preft_slots;
     if (!m) return PREFT_EINVAL;

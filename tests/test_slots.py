@@ -89,7 +89,7 @@ def test_bad_arguments():
     assert lib.preft_slots_create(ctypes.byref(handle), 0, 2, 0, None) == -1
     assert lib.preft_slots_create(ctypes.byref(handle), 4, 0, 0, None) == -1
     assert lib.preft_slots_create(ctypes.byref(handle), 4, 2, 2, None) == -1
-    assert lib.preft_slots_create(ctypes.byref(handle), 4, 2, 9, None) == -1
+    assert lib.preft_slots_create(ctypes.byref(handle), 4, 2, 33, None) == -1
     assert lib.preft_slots_acquire(None, None, 0, None, None) == -1
     assert lib.preft_slots_stats(None, None) == -1
     assert lib.preft_slots_resident(None, 0) == -1
