@@ -50,6 +50,7 @@ def main():
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--waves", type=int, default=0)
     ap.add_argument("--rowblocks", type=int, default=0)
+    ap.add_argument("--colsplit", type=int, default=0, help="workgroups per tile on small batches (0: automatic)")
     ap.add_argument("--ldpad", type=int, default=0, help="experiment: extra elements of row stride on every buffer")
     ap.add_argument("--only", default="", help="experiment: comma-separated subset of projections")
     ap.add_argument("--no-packed", action="store_true",
@@ -82,6 +83,7 @@ def main():
     preft.preft_set_knob(preft.PREFT_KNOB_VARIANT, args.variant)
     preft.preft_set_knob(preft.PREFT_KNOB_WAVES, args.waves)
     preft.preft_set_knob(preft.PREFT_KNOB_ROWBLOCKS, args.rowblocks)
+    preft.preft_set_knob(preft.PREFT_KNOB_COLSPLIT, args.colsplit)
     dev = "cuda:0"
     torch.cuda.set_device(0)
 

@@ -276,8 +276,11 @@ int preft_schedule_counts(const void *workspace, int32_t *counts, void *stream);
  *                        non-zero value also makes DiReFT stream its tile instead of
  *                        holding it in registers)
  *   PREFT_KNOB_ROWBLOCKS MFMA kernel: 16-row blocks per tile: 0 = automatic, 1 or 2
+ *   PREFT_KNOB_COLSPLIT  LoRA, MFMA column-split kernel: workgroups that share a tile, each
+ *                        writing its share of the output columns: 0 = automatic (4 for batches of
+ *                        up to 1024 rows, else 1), or 1..16
  */
-enum { PREFT_KNOB_VARIANT = 0, PREFT_KNOB_WAVES = 1, PREFT_KNOB_ROWBLOCKS = 2 };
+enum { PREFT_KNOB_VARIANT = 0, PREFT_KNOB_WAVES = 1, PREFT_KNOB_ROWBLOCKS = 2, PREFT_KNOB_COLSPLIT = 3 };
 int preft_set_knob(int knob, int value);
 
 /* Static, NUL-terminated description of a return code (host pointer, never freed). */

@@ -23,6 +23,7 @@ PREFT_ECAPACITY = -6
 PREFT_KNOB_VARIANT = 0
 PREFT_KNOB_WAVES = 1
 PREFT_KNOB_ROWBLOCKS = 2
+PREFT_KNOB_COLSPLIT = 3
 
 # every symbol include/preft.h declares
 ABI_SYMBOLS = ("preft_workspace_bytes", "preft_schedule", "preft_lora_apply", "preft_lora_apply_packed",

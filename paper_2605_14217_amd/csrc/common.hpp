@@ -170,6 +170,7 @@ struct ApplyArgs {
     const int2         *shorts;
     const int4         *gtiles;
     int32_t             gathered_only;   // tile kernels: skip the chunks (another launch covers them)
+    int32_t             col_split;       // >= 1: workgroups per tile, each expanding its share of the columns
     // packed projections (LoRA only): further outputs computed from the same x, each with its
     // own factors; slice 0 is (y, ldy, d_out, A_pool, Bt_pool) above
     struct Slice {

@@ -73,9 +73,12 @@ constexpr int mfma_min_waves(int NB, int MB, int WAVES, int HUNITS)
 // from the same x (q, k, v of an attention block; gate and up of an MLP), each with its own
 // factors of NB rank blocks: one shrink sweep over x feeds SLICES * NB accumulator blocks, then
 // one expand sweep per output.  x is read once instead of SLICES times.
-template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT, int SLICES = 1>
+//
+// COLSPLIT (LoRA only): the small-batch shape, see below.
+template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT, int SLICES = 1, bool COLSPLIT = false>
 __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) void mfma_tile_kernel(ApplyArgs p)
 {
+    static_assert(!COLSPLIT || !DIREFT, "a tile of an in-place call belongs to one workgroup");
     constexpr int R = 16 * MB;
     constexpr int NBT = NB * SLICES;                          // rank blocks of the shrink sweep
     constexpr bool PREFETCH_A = (NBT * MB <= 3);              // register budget
@@ -88,8 +91,22 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
     __shared__ u32x4_t turn[WAVES][MB * 16 * MFMA_TRS];       // wavefront-private turn buffers: activations
     __shared__ u32x4_t turn_a[WAVES][16 * MFMA_TRS];          // ... and one rank block of the factor
 
-    int n_chunk_units;
-    const int unit = xcd_unit(tile_units<R>(p, &n_chunk_units));
+    // Small batches (LoRA): col_split workgroups share a tile.  Each runs the whole shrink sweep
+    // (the tile's x and the factor come from L2 after the first) and expands its own share of
+    // the output columns, so that a step of a few dozen rows is spread over the chip instead
+    // of walking every column in one workgroup.  Never in place: another workgroup's writes
+    // must not meet this one's reads.
+    const int csplit = COLSPLIT ? p.col_split : 1;
+    int n_chunk_units, cslice = 0;
+    const int n_units = tile_units<R>(p, &n_chunk_units);
+    int unit;
+    if constexpr (COLSPLIT) {
+        unit = blockIdx.x / csplit;
+        cslice = blockIdx.x - unit * csplit;
+        if (unit >= n_units) unit = -1;
+    } else {
+        unit = xcd_unit(n_units);
+    }
     if (unit < 0) return;
     TileRows tile;
     if (!tile_rows<R>(p, unit, n_chunk_units, tile)) return;   // uniform over the workgroup
@@ -338,6 +355,11 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
     gcptr_t Bt = as_global(slice_Bt<SL>(p)[adapter]);
     const int d_out = slice_d_out<SL>(p);
     const int64_t ldy_b = slice_ldy<SL>(p) * 2;
+    // this workgroup's share of the output: whole units [ubase, ubase + n_cu), and the tail
+    // steps of an odd width if it has the last share
+    const int c_units = d_out >> 7;
+    const int ubase = c_units * cslice / csplit;
+    const int n_cu = c_units * (cslice + 1) / csplit - ubase;
     gptr_t yu[MB][4];             // unit order
     gptr_t ys[MB];                // step order
 #pragma unroll
@@ -380,7 +402,7 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
         return Elem<bf16_tag>::pack(out);
     };
     auto load_w_unit = [&](u32x2_t (&wv)[4][2][NB], int u) {
-        const int cs0 = (wave + u * WAVES) * 4;
+        const int cs0 = (ubase + wave + u * WAVES) * 4;
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
@@ -389,7 +411,7 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
                 for (int b = 0; b < NB; ++b) wv[s][e][b] = ld8(bp[e][b] + (cs0 + s) * w_step);
     };
     auto load_y_unit = [&](u32x4_t (&raw)[MB][4], int u) {
-        const int64_t off = (int64_t)(wave + u * WAVES) * 256;
+        const int64_t off = (int64_t)(ubase + wave + u * WAVES) * 256;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -404,16 +426,15 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
                 const u32x4_t yv = yop[mb][s];
                 tr[(mb * 16 + rl) * MFMA_TRS + 4 * s + g] = expand_step(yv, wv[s], mb);
             }
-        const int64_t off = (int64_t)(wave + u * WAVES) * 256;
+        const int64_t off = (int64_t)(ubase + wave + u * WAVES) * 256;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int i = 0; i < 4; ++i) st16(yu[mb][i] + off, tr[(mb * 16 + 4 * i + q) * MFMA_TRS + c16]);
     };
 
-    const int c_units = d_out >> 7;
-    const int my_cu = c_units > wave ? (c_units - wave + WAVES - 1) / WAVES : 0;
-    const int c_steps = (d_out + 31) >> 5;
+    const int my_cu = n_cu > wave ? (n_cu - wave + WAVES - 1) / WAVES : 0;
+    const int c_steps = cslice == csplit - 1 ? (d_out + 31) >> 5 : 0;
     const int c_tail_step = c_units * 4 + wave;
 
     if constexpr (HUNITS > 0) {

@@ -18,6 +18,7 @@ using namespace preft;
 int g_variant = 0;      // PREFT_KNOB_VARIANT
 int g_waves = 0;        // PREFT_KNOB_WAVES
 int g_rowblocks = 0;    // PREFT_KNOB_ROWBLOCKS
+int g_colsplit = 0;     // PREFT_KNOB_COLSPLIT
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -77,7 +78,23 @@ inline unsigned tile_grid(const ApplyArgs &a, int64_t S, int rows)
     const int64_t per_gtile = rows >= GTILE_ROWS ? 1 : GTILE_ROWS / rows;
     int64_t units = gtile_capacity(a.T, S, a.N) * per_gtile;
     if (!a.gathered_only) units += chunk_capacity(a.T, S) * (CHUNK_ROWS / rows);
-    return (unsigned)(((units + 7) / 8) * 8);
+    return (unsigned)(((units + 7) / 8) * 8 * (a.col_split > 1 ? a.col_split : 1));
+}
+// Workgroups per tile for the LoRA column-split kernel: a batch of a few hundred rows has too
+// few tiles to occupy the chip, and one workgroup per tile would walk every output column alone.
+inline int choose_col_split(int32_t T)
+{
+    if (g_colsplit) return g_colsplit;
+    return T <= 1024 ? 4 : 1;
+}
+
+// the small-batch shape of the column-split kernel (col_split > 1): one shape per rank class
+template <int NB, int SLICES>
+void launch_mfma_colsplit(const ApplyArgs &a, int64_t S, hipStream_t stream)
+{
+    constexpr int WAVES = NB >= 4 ? 4 : 8;                 // register budget
+    hipLaunchKernelGGL((mfma_tile_kernel<NB, 1, WAVES, 0, false, SLICES, true>), dim3(tile_grid(a, S, 16)),
+                       dim3(WAVES * 64), 0, stream, a);
 }
 // the row-split kernel takes whole chunks only
 inline unsigned chunk_grid(const ApplyArgs &a, int64_t S, int rows)
@@ -98,11 +115,13 @@ void launch_mfma(const ApplyArgs &a, int64_t S, hipStream_t stream)
 template <int NB, bool DIREFT>
 void launch_mfma_stream(const ApplyArgs &a, int64_t S, int mb, int waves, hipStream_t stream)
 {
-    if constexpr (NB < 8) {                                // LDS / register budget
+    if constexpr (NB < 2) {                                // register budget
         if (waves == 8) {
             launch_mfma<NB, 1, 8, 0, DIREFT>(a, S, stream);
             return;
         }
+    }
+    if constexpr (NB < 8) {
         if (mb == 2) {
             launch_mfma<NB, 2, 4, 0, DIREFT>(a, S, stream);
             return;
@@ -178,6 +197,12 @@ void launch_mfma_nb(const ApplyArgs &a, int64_t S, hipStream_t stream)
             }
         }
     }
+    if constexpr (!DIREFT) {
+        if (a.col_split > 1) {
+            launch_mfma_colsplit<NB, 1>(a, S, stream);
+            return;
+        }
+    }
     if (g_variant != 3 && launch_mfma_wide<NB, DIREFT>(a, S, wide_mb, wide_waves, stream)) {
         // the row-split kernel shares one adapter's factors among the 128 rows of a chunk;
         // gathered tiles (16 rows of an adapter) go to the column-split kernel
@@ -193,6 +218,10 @@ void launch_mfma_nb(const ApplyArgs &a, int64_t S, hipStream_t stream)
 template <int SLICES>
 void launch_mfma_packed(const ApplyArgs &a, int64_t S, hipStream_t stream)
 {
+    if (a.col_split > 1) {
+        launch_mfma_colsplit<1, SLICES>(a, S, stream);
+        return;
+    }
     // three outputs: 4 wavefronts per tile leave room for two workgroups per compute unit (measured
     // better on small and large batches); two outputs: as for a single projection
     const int waves = g_waves ? (g_waves == 8 ? 8 : 4) : ((SLICES == 2 && a.T <= 65536) ? 8 : 4);
@@ -287,9 +316,12 @@ template <bool DIREFT>
 int launch_apply(const ApplyArgs &a, int64_t S, int dtype, hipStream_t stream)
 {
     switch (choose_path(dtype, a.rank)) {
-    case Path::Mfma:                       // the tile kernels take chunks and gathered tiles alike
-        launch_mfma_rank<DIREFT>(a, S, stream);
+    case Path::Mfma: {                     // the tile kernels take chunks and gathered tiles alike
+        ApplyArgs b = a;
+        if (!DIREFT) b.col_split = choose_col_split(a.T);
+        launch_mfma_rank<DIREFT>(b, S, stream);
         break;
+    }
     case Path::Valu:
         launch_valu_rank<DIREFT>(a, S, stream);
         break;
@@ -371,7 +403,7 @@ int preft_lora_apply(void *y, int64_t ldy, const void *x, int64_t ldx, int32_t T
     ApplyArgs a;
     a.y = y; a.x = x; a.ldy = ldy; a.ldx = ldx; a.T = T; a.d_in = d_in; a.d_out = d_out;
     a.A_pool = A_pool; a.Bt_pool = B_pool; a.bias_pool = nullptr; a.N = N; a.rank = rank; a.scale = scale;
-    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.gtiles = v.gtiles; a.gathered_only = 0;
+    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.gtiles = v.gtiles; a.gathered_only = 0; a.col_split = 1;
     return launch_apply<false>(a, S, dtype, st);
 }
 
@@ -432,12 +464,13 @@ int preft_lora_apply_packed(int32_t n_proj, void *const *y, const int64_t *ldy, 
     ApplyArgs a;
     a.y = y[0]; a.x = x; a.ldy = ldy[0]; a.ldx = ldx; a.T = T; a.d_in = d_in; a.d_out = d_out[0];
     a.A_pool = A_pools[0]; a.Bt_pool = B_pools[0]; a.bias_pool = nullptr; a.N = N; a.rank = rank; a.scale = scale;
-    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.gtiles = v.gtiles; a.gathered_only = 0;
+    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.gtiles = v.gtiles; a.gathered_only = 0; a.col_split = 1;
     for (int32_t i = 1; i < n_proj; ++i) {
         a.more[i - 1].y = y[i]; a.more[i - 1].ldy = ldy[i]; a.more[i - 1].d_out = d_out[i];
         a.more[i - 1].A_pool = A_pools[i]; a.more[i - 1].Bt_pool = B_pools[i];
     }
     if (fused_mfma) {
+        a.col_split = choose_col_split(T);
         if (n_proj == 2) launch_mfma_packed<2>(a, S, st);
         else             launch_mfma_packed<3>(a, S, st);
     } else {
@@ -505,7 +538,7 @@ int preft_direft_apply(void *h, int64_t ldh, int32_t T, int32_t d, const int32_t
     ApplyArgs a;
     a.y = h; a.x = h; a.ldy = ldh; a.ldx = ldh; a.T = T; a.d_in = d; a.d_out = d;
     a.A_pool = W1_pool; a.Bt_pool = W2t_pool; a.bias_pool = b_pool; a.N = N; a.rank = rank; a.scale = scale;
-    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.gtiles = v.gtiles; a.gathered_only = 0;
+    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.gtiles = v.gtiles; a.gathered_only = 0; a.col_split = 1;
     return launch_apply<true>(a, S, dtype, st);
 }
 
@@ -525,6 +558,7 @@ int preft_set_knob(int knob, int value)
     case PREFT_KNOB_VARIANT:   if (value < 0 || value > 4) return PREFT_EINVAL; slot = &g_variant; break;
     case PREFT_KNOB_WAVES:     if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return PREFT_EINVAL; slot = &g_waves; break;
     case PREFT_KNOB_ROWBLOCKS: if (value < 0 || value > 2) return PREFT_EINVAL; slot = &g_rowblocks; break;
+    case PREFT_KNOB_COLSPLIT:  if (value < 0 || value > 16) return PREFT_EINVAL; slot = &g_colsplit; break;
     default: return PREFT_EINVAL;
     }
     const int prev = *slot;

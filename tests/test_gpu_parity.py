@@ -23,6 +23,7 @@ def _announce_and_reset(request):
     preft.preft_set_knob(preft.PREFT_KNOB_VARIANT, 0)
     preft.preft_set_knob(preft.PREFT_KNOB_WAVES, 0)
     preft.preft_set_knob(preft.PREFT_KNOB_ROWBLOCKS, 0)
+    preft.preft_set_knob(preft.PREFT_KNOB_COLSPLIT, 0)
 
 
 def _set(variant=0, waves=0, rowblocks=0):
@@ -562,3 +563,36 @@ def test_packed_projections_reject_overlapping_outputs():
     call([buf[:, :d], buf[:, d:2 * d], buf[:, 2 * d:]])        # three disjoint ranges of one buffer: fine
     torch.cuda.synchronize()
     assert not torch.equal(buf, before)
+
+
+# ---------------------------------------------------------------------------------------
+# small batches: several workgroups share a tile, each writes its share of the columns
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("colsplit", [1, 2, 3, 5, 8, 16])
+@pytest.mark.parametrize("r,d_in,d_out", [(16, 512, 1024), (8, 1000, 264), (64, 512, 520), (4, 256, 128)])
+def test_column_split_over_workgroups(colsplit, r, d_in, d_out):
+    from parity_util import run_lora_case
+    N = 5
+    preft.preft_set_knob(preft.PREFT_KNOB_COLSPLIT, colsplit)
+    tab = _mixed_table(700 + r, N, n_prompts=3, max_len=90, n_decode=12)
+    pool = wl.lora_pool(N, r, d_in, d_out, "bf16", device="cuda", seed=71)
+    x = wl.activations(tab.T, d_in, "bf16", device="cuda", seed=72)
+    y0 = wl.activations(tab.T, d_out, "bf16", device="cuda", seed=73)
+    for all_tokens in (False, True):
+        worst, _ = run_lora_case(tab, pool, x, y0, "bf16", 2.0, all_tokens, pad_cols=8)
+        print(f"  colsplit={colsplit} r={r} {d_in}->{d_out} all_tokens={all_tokens} worst {worst:.2e}")
+
+
+@pytest.mark.parametrize("colsplit", [1, 4, 7])
+def test_column_split_with_packed_projections_and_in_place_calls(colsplit):
+    """Packed outputs are split per output; DiReFT (in place) never splits a tile over workgroups."""
+    from parity_util import run_direft_case
+    preft.preft_set_knob(preft.PREFT_KNOB_COLSPLIT, colsplit)
+    for all_tokens in (False, True):
+        worst = _packed_case("bf16", 16, 512, [512, 128, 264], True, 800 + colsplit, all_tokens, S=12, max_len=60)
+        print(f"  colsplit={colsplit} packed all_tokens={all_tokens} worst {worst:.2e}")
+    N, r, d = 4, 16, 1000
+    tab = _mixed_table(810, N, n_prompts=3, max_len=90, n_decode=12)
+    pool = wl.direft_pool(N, r, d, "bf16", device="cuda", seed=81)
+    h = wl.activations(tab.T, d, "bf16", device="cuda", seed=82)
+    run_direft_case(tab, pool, h, "bf16", 0.25, True)
