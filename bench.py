@@ -56,6 +56,8 @@ def main():
     ap.add_argument("--no-packed", action="store_true",
                     help="one launch per projection instead of packed q,k,v and gate,up launches")
     ap.add_argument("--no-trace", action="store_true", help="skip the serving-trace replay leg")
+    ap.add_argument("--no-other-ranks", action="store_true",
+                    help="skip the short runs at the configuration's other ranks")
     ap.add_argument("--trace-requests", type=int, default=1000)
     ap.add_argument("--trace-batch", type=int, default=32)
     ap.add_argument("--trace-adapters", type=int, default=32)
@@ -280,6 +282,28 @@ def main():
         out["decode_only_step"] = {"rows": dec.T, "all_token_ms": round(ms_dec_all, 4),
                                    "prefill_only_ms": round(ms_dec_pre, 4),
                                    "speedup_prefill_only": round(ms_dec_all / ms_dec_pre, 2)}
+
+    # ---- the configuration's other ranks: the same measurement in a child process each ----------
+    if not (args.no_extras or args.no_other_ranks or args.variant or args.waves or args.rowblocks or args.colsplit
+            or args.ldpad or args.only or args.no_packed):
+        import subprocess
+        others = {}
+        for rk in cfg["ranks"]:
+            if rk == r:
+                continue
+            cmd = [sys.executable, os.path.abspath(__file__), "--config", args.config, "--rank", str(rk), "--seed",
+                   str(args.seed), "--steps", str(max(5, K // 4)), "--warmup", "3", "--no-extras", "--no-cpu-baseline"]
+            res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, text=True, timeout=600)
+            lines = [l for l in res.stdout.splitlines() if l.startswith("{")]
+            if res.returncode != 0 or not lines:
+                others[str(rk)] = {"error": f"child exited with {res.returncode}"}
+                continue
+            d_ = json.loads(lines[-1])
+            others[str(rk)] = {"value": d_["value"], "ms_per_step": d_["ms_per_step"],
+                               "roofline_frac": d_["roofline"]["frac"],
+                               "frac_per_launch": {k_: v_["frac"] for k_, v_ in d_["breakdown"].items()}}
+        if others:
+            out["other_ranks"] = others
 
     # ---- serving-weighted comparison: first-come-first-served trace of the paper's microbenchmark --
     # (App. E.1, E.3): every engine step's adapter work, in both modes.  Decode-only steps are
