@@ -42,11 +42,12 @@ class PreftError(RuntimeError):
 
 
 def load_library(path: Optional[str] = None):
-    """Load libpreft.so (built in-tree by paper_2605_14217_amd.build) and declare its prototypes."""
+    """Load libpreft.so (built in-tree by paper_2605_14217_amd.build; the environment variable
+    PREFT_LIBRARY names another build of it) and declare its prototypes."""
     global _lib
     if _lib is not None and path is None:
         return _lib
-    path = path or LIB_PATH
+    path = path or os.environ.get("PREFT_LIBRARY") or LIB_PATH
     if not os.path.exists(path):
         raise FileNotFoundError(
             f"{path} not found: build the HIP library first (python -m paper_2605_14217_amd.build); "

@@ -104,6 +104,32 @@ __device__ __forceinline__ u32x4_t ld16(gptr_t p) { return *reinterpret_cast<con
 __device__ __forceinline__ u32x2_t ld8(gcptr_t p) { return *reinterpret_cast<const PREFT_GLOBAL u32x2_t *>(p); }
 __device__ __forceinline__ uint32_t ld4(gcptr_t p) { return *reinterpret_cast<const PREFT_GLOBAL uint32_t *>(p); }
 __device__ __forceinline__ void st16(gptr_t p, u32x4_t v) { *reinterpret_cast<PREFT_GLOBAL u32x4_t *>(p) = v; }
+// Activations are touched once per call: their loads and stores carry the non-temporal hint, so
+// that they stream through the caches without displacing the adapter factors, which every tile
+// of an adapter reads again.  Measured on the LoRA tile kernel, hint on x loads / y loads /
+// y stores: none 59.7 %, all three 64.6 % of peak on the 8B shapes; 61.5 % -> 71.2 % on the 70B shapes
+// (each hint alone gives part of it).
+#ifndef PREFT_STREAM_HINTS
+#define PREFT_STREAM_HINTS 1
+#endif
+__device__ __forceinline__ u32x4_t ld16_stream(gcptr_t p)
+{
+    if constexpr (PREFT_STREAM_HINTS != 0) return __builtin_nontemporal_load(reinterpret_cast<const PREFT_GLOBAL u32x4_t *>(p));
+    else return ld16(p);
+}
+__device__ __forceinline__ u32x4_t ld16_stream(gptr_t p) { return ld16_stream((gcptr_t)p); }
+// first of two reads of the same bytes (an in-place call that does not keep its tile): cacheable
+template <bool AGAIN_LATER>
+__device__ __forceinline__ u32x4_t ld16_first(gcptr_t p)
+{
+    if constexpr (AGAIN_LATER) return ld16(p);
+    else return ld16_stream(p);
+}
+__device__ __forceinline__ void st16_stream(gptr_t p, u32x4_t v)
+{
+    if constexpr (PREFT_STREAM_HINTS != 0) __builtin_nontemporal_store(v, reinterpret_cast<PREFT_GLOBAL u32x4_t *>(p));
+    else st16(p, v);
+}
 
 // Element traits: V = elements per 16-byte vector
 template <typename T> struct Elem;

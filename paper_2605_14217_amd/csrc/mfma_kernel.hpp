@@ -202,7 +202,7 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) raw[mb][i] = ld16(xu[mb][i] + off);
+            for (int i = 0; i < 4; ++i) raw[mb][i] = ld16_first<DIREFT && HUNITS == 0>(xu[mb][i] + off);
     };
     auto load_a_unit = [&](u32x4_t (&araw)[NBT][4], int u) {
         const int64_t off = (int64_t)(wave + u * WAVES) * 256;
@@ -282,7 +282,7 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
         const u32x4_t zero = {0u, 0u, 0u, 0u};
         const int64_t off = (int64_t)k_tail_step * 64;
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) htail[mb] = as_u32x4(step_to_mfma(col_ok ? ld16(xs[mb] + off) : zero));
+        for (int mb = 0; mb < MB; ++mb) htail[mb] = as_u32x4(step_to_mfma(col_ok ? ld16_first<DIREFT && HUNITS == 0>(xs[mb] + off) : zero));
 #pragma unroll
         for (int b = 0; b < NBT; ++b) {
             const bf16x8_t av = step_to_mfma(col_ok ? ld16(abase[b / NB] + off + aoff_s[b % NB]) : zero);
@@ -415,7 +415,7 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) raw[mb][i] = ld16(yu[mb][i] + off);
+            for (int i = 0; i < 4; ++i) raw[mb][i] = ld16_stream(yu[mb][i] + off);
     };
     // a whole unit: y (MFMA order) -> out, turned back to load order through LDS and stored
     auto finish_unit = [&](const u32x4_t (&yop)[MB][4], const u32x2_t (&wv)[4][2][NB], int u) {
@@ -430,7 +430,7 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) st16(yu[mb][i] + off, tr[(mb * 16 + 4 * i + q) * MFMA_TRS + c16]);
+            for (int i = 0; i < 4; ++i) st16_stream(yu[mb][i] + off, tr[(mb * 16 + 4 * i + q) * MFMA_TRS + c16]);
     };
 
     const int my_cu = n_cu > wave ? (n_cu - wave + WAVES - 1) / WAVES : 0;
@@ -497,12 +497,12 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             if constexpr (HUNITS > 0) yv[mb] = htail[mb];
-            else yv[mb] = as_u32x4(step_to_mfma(col_ok ? ld16(ys[mb] + off) : u32x4_t{0u, 0u, 0u, 0u}));
+            else yv[mb] = as_u32x4(step_to_mfma(col_ok ? ld16_stream(ys[mb] + off) : u32x4_t{0u, 0u, 0u, 0u}));
         }
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             const u32x4_t o = mfma_to_step(expand_step(yv[mb], wv, mb));
-            if (col_ok) st16(ys[mb] + off, o);
+            if (col_ok) st16_stream(ys[mb] + off, o);
         }
     }
     };

@@ -102,7 +102,7 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_wide_kernel(ApplyArgs p)
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) raw[mb][i] = ld16(xu[mb][i] + (int64_t)u * 256);
+            for (int i = 0; i < 4; ++i) raw[mb][i] = ld16_first<DIREFT>(xu[mb][i] + (int64_t)u * 256);
     };
     // this thread's pieces of the A unit: piece t + i NT = rank (piece >> 4), 16-byte chunk (piece & 15)
     auto load_a = [&](u32x4_t (&areg)[A_ITERS], int u) {
@@ -255,7 +255,7 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_wide_kernel(ApplyArgs p)
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) raw[mb][i] = ld16(yu[mb][i] + (int64_t)u * 256);
+            for (int i = 0; i < 4; ++i) raw[mb][i] = ld16_stream(yu[mb][i] + (int64_t)u * 256);
     };
     auto finish_unit = [&](const u32x4_t (&yop)[MB][4], int buf, int u) {
         const char *fb = fac + buf * (128 * (32 * NB + 8));
@@ -293,7 +293,7 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_wide_kernel(ApplyArgs p)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const u32x4_t o = tr[(mb * 16 + 4 * i + q) * MFMA_TRS + c16];
-                if (row_ok[mb][i]) st16(yu[mb][i] + (int64_t)u * 256, o);
+                if (row_ok[mb][i]) st16_stream(yu[mb][i] + (int64_t)u * 256, o);
             }
     };
 

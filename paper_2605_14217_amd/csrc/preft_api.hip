@@ -179,9 +179,8 @@ void launch_mfma_nb(const ApplyArgs &a, int64_t S, hipStream_t stream)
     // rank >= 32: the factors outweigh a 16-row tile's activations, so more rows share them:
     // the row-split kernel with 8 wavefronts x 16 rows (a whole 128-row chunk per workgroup)
     const int wide_mb = g_rowblocks ? g_rowblocks : 1;
-    const int wide_waves = g_waves ? (g_waves == 8 ? 8 : 4) : ((NB >= 2 || a.T <= 65536) ? 8 : 4);
-    // column-split kernel.  rank <= 16: 8 wavefronts per 16-row tile on small batches, where a
-    // shorter workgroup lifetime shortens the kernel's tail, 4 on large ones; rank 32 (widths the
+    const int wide_waves = g_waves ? (g_waves == 8 ? 8 : 4) : 8;
+    // column-split kernel.  rank <= 16: 8 wavefronts per 16-row tile; rank 32 (widths the
     // row-split kernel does not take): 32-row tiles of 4 wavefronts
     const int mb = g_rowblocks ? g_rowblocks : (NB == 2 ? 2 : 1);
     const int waves = g_waves ? (g_waves == 8 ? 8 : 4) : (NB == 2 ? 4 : wide_waves);
@@ -224,7 +223,7 @@ void launch_mfma_packed(const ApplyArgs &a, int64_t S, hipStream_t stream)
     }
     // three outputs: 4 wavefronts per tile leave room for two workgroups per compute unit (measured
     // better on small and large batches); two outputs: as for a single projection
-    const int waves = g_waves ? (g_waves == 8 ? 8 : 4) : ((SLICES == 2 && a.T <= 65536) ? 8 : 4);
+    const int waves = g_waves ? (g_waves == 8 ? 8 : 4) : (SLICES == 2 ? 8 : 4);
     if (waves == 8)
         hipLaunchKernelGGL((mfma_tile_kernel<1, 1, 8, 0, false, SLICES>), dim3(tile_grid(a, S, 16)), dim3(512), 0,
                            stream, a);

@@ -90,8 +90,8 @@ __global__ __launch_bounds__(WAVES * 64) void valu_tile_kernel(ApplyArgs p)
         u32x4_t xv0[RB], xv1[RB], av0[RT], av1[RT];
 #pragma unroll
         for (int i = 0; i < RB; ++i) {
-            xv0[i] = ld16(xp[i] + (int64_t)c * 16);
-            xv1[i] = ld16(xp[i] + (int64_t)(c + 64) * 16);
+            xv0[i] = ld16_first<DIREFT>(xp[i] + (int64_t)c * 16);
+            xv1[i] = ld16_first<DIREFT>(xp[i] + (int64_t)(c + 64) * 16);
         }
 #pragma unroll
         for (int k = 0; k < RT; ++k) {
@@ -104,7 +104,7 @@ __global__ __launch_bounds__(WAVES * 64) void valu_tile_kernel(ApplyArgs p)
     for (; c < nvec_in; c += 64) {
         u32x4_t xv[RB], av[RT];
 #pragma unroll
-        for (int i = 0; i < RB; ++i) xv[i] = ld16(xp[i] + (int64_t)c * 16);
+        for (int i = 0; i < RB; ++i) xv[i] = ld16_first<DIREFT>(xp[i] + (int64_t)c * 16);
 #pragma unroll
         for (int k = 0; k < RT; ++k) av[k] = ld16(A[k / RANK] + ((int64_t)(k % RANK) * p.d_in + (int64_t)c * 8) * 2);
         shrink_step(xv, av);
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(WAVES * 64) void valu_tile_kernel(ApplyArgs p)
             }
             u32x4_t yv[RB];
 #pragma unroll
-            for (int i = 0; i < RB; ++i) yv[i] = ld16(yp[i] + (int64_t)c * 16);
+            for (int i = 0; i < RB; ++i) yv[i] = ld16_stream(yp[i] + (int64_t)c * 16);
 #pragma unroll
             for (int i = 0; i < RB; ++i) {
                 float out[8];
@@ -153,7 +153,7 @@ __global__ __launch_bounds__(WAVES * 64) void valu_tile_kernel(ApplyArgs p)
                     for (int k = 0; k < RANK; ++k) d = fmaf(w[col * RANK + k], z[i][SL * RANK + k], d);
                     out[col] += d;
                 }
-                st16(yp[i] + (int64_t)c * 16, Elem<bf16_tag>::pack(out));
+                st16_stream(yp[i] + (int64_t)c * 16, Elem<bf16_tag>::pack(out));
             }
         }
     };
