@@ -52,6 +52,9 @@ def test_knob_validation(lib):
     assert lib.preft_set_knob(preft.PREFT_KNOB_VARIANT, 7) == -1
     assert lib.preft_set_knob(preft.PREFT_KNOB_VARIANT, 5) == -1
     assert lib.preft_set_knob(preft.PREFT_KNOB_WAVES, 3) == -1
+    assert lib.preft_set_knob(preft.PREFT_KNOB_COLSPLIT, 17) == -1
+    assert lib.preft_set_knob(preft.PREFT_KNOB_COLSPLIT, -1) == -1
+    assert lib.preft_set_knob(preft.PREFT_KNOB_COLSPLIT, 0) >= 0
     prev = preft.preft_set_knob(preft.PREFT_KNOB_VARIANT, 1)
     assert preft.preft_set_knob(preft.PREFT_KNOB_VARIANT, prev) == 1
 
@@ -112,3 +115,41 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert direft(wsb=0) == -4
     assert lib.preft_schedule(fake, ws_bytes, fake, fake, fake, 4, 64, 2, preft.PREFT_SCHEDULE_READY, None) == -1
     assert lib.preft_schedule(fake, 8, fake, fake, fake, 4, 64, 2, 0, None) == -4
+
+
+def test_packed_and_loreft_arguments_are_rejected_before_any_launch(lib):
+    fake = 0x7f0000001000                         # never dereferenced: every call must fail first
+    ws_bytes = preft.preft_workspace_bytes(64, 4)
+    vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+
+    def packed(n=2, ys=(0x7f0000200000, 0x7f0000300000), ldy=(64, 64), d_out=(64, 64), x=0x7f0000100000, ldx=64,
+               T=64, d_in=64, rank=4, dtype=preft.PREFT_BF16, pools=(fake, fake), ws=fake, wsb=ws_bytes):
+        k = max(len(ys), 1)
+        return lib.preft_lora_apply_packed(
+            n, (vp * k)(*ys), (i64 * k)(*ldy), (i32 * k)(*d_out), x, ldx, T, d_in, fake, fake, fake, 4,
+            (vp * k)(*pools), (vp * k)(*pools), 2, rank, 1.0, dtype, 0, ws, wsb, None)
+
+    assert packed(n=0) == -1
+    assert packed(n=4, ys=(fake,) * 4, ldy=(64,) * 4, d_out=(64,) * 4, pools=(fake,) * 4) == -1
+    assert packed(rank=0) == -2
+    assert packed(dtype=9) == -1
+    assert packed(wsb=8) == -4
+    assert packed(d_out=(64, 60)) == -3                                   # width not a multiple of 16 bytes
+    assert packed(ys=(0x7f0000200000, 0x7f0000200000)) == -1              # the same output twice
+    assert packed(ys=(0x7f0000200000, 0x7f0000200040)) == -1              # columns that overlap (64 bytes apart, 128 wide)
+    assert packed(ys=(0x7f0000200000, 0x7f0000200080), ldy=(128, 64)) == -1   # overlapping buffers of different pitch
+    assert packed(ys=(0x7f0000200000, 0x7f0000100000)) == -1              # an output on top of x
+    assert packed(pools=(fake, None)) == -1
+    assert packed(T=0) == 0
+
+    def prepare(D=0x7f0000400000, Rt=0x7f0000500000, W=0x7f0000600000, R=0x7f0000700000, d=64, rank=4,
+                dtype=preft.PREFT_BF16):
+        return lib.preft_loreft_prepare(D, Rt, W, R, d, rank, dtype, None)
+
+    assert prepare(D=None) == -1
+    assert prepare(d=0) == -1
+    assert prepare(rank=0) == -2
+    assert prepare(dtype=3) == -1
+    assert prepare(W=0x7f0000600008) == -3
+    assert prepare(D=0x7f0000600000) == -1                                # D on top of W
+    assert prepare(Rt=0x7f0000400100) == -1                               # Rt inside D
