@@ -79,6 +79,9 @@ template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT, int SLICES = 1, bo
 __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) void mfma_tile_kernel(ApplyArgs p)
 {
     static_assert(!COLSPLIT || !DIREFT, "a tile of an in-place call belongs to one workgroup");
+    // x is read a second time by this workgroup (in place without a resident tile) or by the
+    // workgroups that share the tile (small-batch shape): then its loads stay cacheable
+    constexpr bool X_READ_AGAIN = (DIREFT && HUNITS == 0) || COLSPLIT;
     constexpr int R = 16 * MB;
     constexpr int NBT = NB * SLICES;                          // rank blocks of the shrink sweep
     constexpr bool PREFETCH_A = (NBT * MB <= 3);              // register budget
@@ -202,7 +205,7 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) raw[mb][i] = ld16_first<DIREFT && HUNITS == 0>(xu[mb][i] + off);
+            for (int i = 0; i < 4; ++i) raw[mb][i] = ld16_first<X_READ_AGAIN>(xu[mb][i] + off);
     };
     auto load_a_unit = [&](u32x4_t (&araw)[NBT][4], int u) {
         const int64_t off = (int64_t)(wave + u * WAVES) * 256;
@@ -282,7 +285,7 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
         const u32x4_t zero = {0u, 0u, 0u, 0u};
         const int64_t off = (int64_t)k_tail_step * 64;
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) htail[mb] = as_u32x4(step_to_mfma(col_ok ? ld16_first<DIREFT && HUNITS == 0>(xs[mb] + off) : zero));
+        for (int mb = 0; mb < MB; ++mb) htail[mb] = as_u32x4(step_to_mfma(col_ok ? ld16_first<X_READ_AGAIN>(xs[mb] + off) : zero));
 #pragma unroll
         for (int b = 0; b < NBT; ++b) {
             const bf16x8_t av = step_to_mfma(col_ok ? ld16(abase[b / NB] + off + aoff_s[b % NB]) : zero);
