@@ -6,6 +6,7 @@
  *
  *   LoRA    (paper Eq. 2):             y_t <- y_t + s * B_i (A_i x_t)
  *   DiReFT  (paper Eq. 3, App. C.2):   h_t <- h_t + s * W2_i^T (W1_i h_t + b_i)
+ *   LoReFT  (paper App. C.2):          h_t <- h_t + s * R_i^T (W_i h_t + b_i - R_i h_t)
  *
  * for every row t whose position lies in the adapter's position set (paper Eq. 1):
  * the prompt positions of its sequence only (PREFT_PREFILL_ONLY, paper Eq. 4) or every
