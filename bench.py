@@ -283,6 +283,54 @@ def main():
                                    "prefill_only_ms": round(ms_dec_pre, 4),
                                    "speedup_prefill_only": round(ms_dec_all / ms_dec_pre, 2)}
 
+    # ---- DiReFT at every layer (App. A.2): L residual streams, one call per layer or one call for all ----
+    if not args.no_extras:
+        L = int(max(2, min(32, 48e9 // (T * d_res * 2))))
+        hs = [h] + [h.clone() for _ in range(L - 1)]
+        per_layer = [(W1p, W2tp, bp)]
+        keep = []
+        for _ in range(L - 1):                      # every layer has factors of its own (distinct memory)
+            mats = [[m.clone() for m in group] for group in (W1, W2t, bb)]
+            keep.append(mats)
+            per_layer.append(tuple(preft.pointer_table(g_) for g_ in mats))
+        as_table = lambda ptrs: torch.tensor(ptrs, dtype=torch.int64, device=dev)
+        h_tab = preft.pointer_table(hs)
+        W1s, W2s, bs = (as_table([pl[i].data_ptr() for pl in per_layer]) for i in range(3))
+
+        def layers_step(mode, fused, tables=(ss, sa, sp), T_=T):
+            s0, s1, s2 = tables
+            preft.preft_schedule(ws, s0, s1, s2, T_, N, mode)
+            ready = mode | preft.PREFT_SCHEDULE_READY
+            if fused:
+                preft.preft_direft_apply_layers([x[:T_] for x in hs], h_tab, s0, s1, s2, W1s, W2s, bs, N, r,
+                                                direft_scale, ready, ws)
+            else:
+                for x, (a1, a2, a3) in zip(hs, per_layer):
+                    preft.preft_direft_apply(x[:T_], s0, s1, s2, a1, a2, a3, r, direft_scale, ready, ws)
+
+        it = max(3, K // 10)
+        ms_each = timed(lambda: layers_step(preft.PREFT_PREFILL_ONLY, False), it, 2)
+        ms_one = timed(lambda: layers_step(preft.PREFT_PREFILL_ONLY, True), it, 2)
+        dec = tab.decode_only()
+        dt = tuple(torch.from_numpy(a.copy()).to(dev) for a in (dec.seg_start, dec.seg_adapter, dec.seg_prefill_len))
+
+        def graphed_layers(fused):
+            layers_step(preft.PREFT_ALL_TOKENS, fused, dt, dec.T)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                layers_step(preft.PREFT_ALL_TOKENS, fused, dt, dec.T)
+            return g
+        ms_dec_each = timed(graphed_layers(False).replay, 50, 5)
+        ms_dec_one = timed(graphed_layers(True).replay, 50, 5)
+        out["direft_every_layer"] = {
+            "layers": L, "rank": r, "d": d_res,
+            "mixed_batch_prefill_only_ms": {"one_call_per_layer": round(ms_each, 4), "one_call": round(ms_one, 4)},
+            "frac_of_peak_one_call": round(L * db / ms_one / 1e6 / PEAK_HBM_GBPS, 4),
+            "decode_rows_all_token_ms": {"rows": dec.T, "one_call_per_layer": round(ms_dec_each, 4),
+                                         "one_call": round(ms_dec_one, 4)}}
+        del hs, keep, per_layer
+
     # ---- the configuration's other ranks: the same measurement in a child process each ----------
     if not (args.no_extras or args.no_other_ranks or args.variant or args.waves or args.rowblocks or args.colsplit
             or args.ldpad or args.only or args.no_packed):

@@ -85,6 +85,7 @@ enum {
 };
 
 #define PREFT_MAX_RANK 128
+#define PREFT_MAX_LAYERS 1024      /* residual streams per preft_direft_apply_layers call */
 #define PREFT_MAX_PACKED 3      /* projections one packed call may fuse */
 #define PREFT_MAX_PARTS 32      /* matrices per adapter a slot manager may hold */
 
@@ -174,6 +175,31 @@ int preft_direft_apply(void *h, int64_t ldh, int32_t T, int32_t d,
                        const void *const *b_pool, int32_t N,
                        int32_t rank, float scale, int dtype, int mode,
                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * DiReFT on n_layers residual streams in one launch: the paper intervenes at every layer
+ * (App. A.2), each layer with weights of its own, and an engine step of a few dozen rows is
+ * bound by launches, not bytes.  Layer l applies
+ *   h_layers[l][t, :] += scale * W2_{l,i}^T (W1_{l,i} h_layers[l][t, :] + b_{l,i})
+ * to its own buffer, exactly as preft_direft_apply(h_layers[l], ..., W1_pools[l], W2t_pools[l],
+ * b_pools[l], ...) would; the layers share T, d, ldh, the segment tables, rank, scale and one
+ * schedule.  The caller decides that the buffers may be processed side by side (states kept per
+ * layer, independent streams); buffers that overlap give undefined results.
+ *
+ * h_layers, W1_pools, W2t_pools and b_pools are DEVICE arrays of n_layers device pointers: the
+ * residual streams ([T, d], row stride ldh, each 16-byte aligned -- not checkable from the host)
+ * and, per layer, pointer tables as in preft_direft_apply.  b_pools may be NULL (no bias in any
+ * layer); an entry of it may be NULL (no bias in that layer).
+ * n_layers in 0..PREFT_MAX_LAYERS (0: nothing to do); everything else as preft_direft_apply.
+ * With the derived pools of preft_loreft_prepare the same call applies LoReFT.
+ */
+int preft_direft_apply_layers(void *const *h_layers, int64_t ldh, int32_t n_layers, int32_t T, int32_t d,
+                              const int32_t *seg_start, const int32_t *seg_adapter,
+                              const int32_t *seg_prefill_len, int32_t S,
+                              const void *const *const *W1_pools, const void *const *const *W2t_pools,
+                              const void *const *const *b_pools, int32_t N,
+                              int32_t rank, float scale, int dtype, int mode,
+                              void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * LoReFT (paper App. C.2): h[t, :] += scale * R_i^T (W_i h[t, :] + b_i - R_i h[t, :]), with

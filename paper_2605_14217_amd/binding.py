@@ -27,7 +27,7 @@ PREFT_KNOB_COLSPLIT = 3
 
 # every symbol include/preft.h declares
 ABI_SYMBOLS = ("preft_workspace_bytes", "preft_schedule", "preft_lora_apply", "preft_lora_apply_packed",
-               "preft_direft_apply",
+               "preft_direft_apply", "preft_direft_apply_layers",
                "preft_loreft_prepare", "preft_loreft_apply", "preft_slots_create", "preft_slots_destroy",
                "preft_slots_store", "preft_slots_acquire", "preft_slots_pool", "preft_slots_resident",
                "preft_slots_stats", "preft_schedule_counts", "preft_set_knob", "preft_strerror", "preft_version")
@@ -69,6 +69,9 @@ def load_library(path: Optional[str] = None):
     lib.preft_direft_apply.restype = c.c_int
     lib.preft_direft_apply.argtypes = [vp, i64, i32, i32, vp, vp, vp, i32, vp, vp, vp, i32, i32,
                                        c.c_float, c.c_int, c.c_int, vp, sz, vp]
+    lib.preft_direft_apply_layers.restype = c.c_int
+    lib.preft_direft_apply_layers.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp, i32, vp, vp, vp, i32, i32,
+                                              c.c_float, c.c_int, c.c_int, vp, sz, vp]
     lib.preft_loreft_prepare.restype = c.c_int
     lib.preft_loreft_prepare.argtypes = [vp, vp, vp, vp, i32, i32, c.c_int, vp]
     lib.preft_loreft_apply.restype = c.c_int
@@ -274,6 +277,35 @@ def preft_direft_apply(h: torch.Tensor, seg_start, seg_adapter, seg_prefill_len,
     matrices; W2t_pool: [d, rank] matrices (W2 transposed); b_pool: [rank] vectors or None."""
     _reft_apply("preft_direft_apply", h, seg_start, seg_adapter, seg_prefill_len, W1_pool, W2t_pool, b_pool, rank,
                 scale, mode, workspace, stream)
+
+
+def preft_direft_apply_layers(hs: Sequence[torch.Tensor], h_layers: torch.Tensor, seg_start, seg_adapter,
+                              seg_prefill_len, W1_pools: torch.Tensor, W2t_pools: torch.Tensor,
+                              b_pools: Optional[torch.Tensor], N: int, rank: int, scale: float, mode: int,
+                              workspace: torch.Tensor, stream=None) -> None:
+    """DiReFT on len(hs) residual streams in one launch.  hs: the [T, d] device tensors (equal shape,
+    stride and dtype); h_layers = pointer_table(hs) made once by the caller; W1_pools / W2t_pools /
+    b_pools: int64 device tensors of len(hs) entries, each the data_ptr() of that layer's pointer
+    table of N slots (b_pools None: no bias; an entry 0: no bias in that layer)."""
+    L = len(hs)
+    hp, ldh, T, d = _matrix(hs[0], "hs[0]")
+    for i, h in enumerate(hs):
+        if _matrix(h, f"hs[{i}]")[1:] != (ldh, T, d) or h.dtype != hs[0].dtype:
+            raise ValueError("the residual streams must agree in shape, row stride and dtype")
+    for t, name in ((h_layers, "h_layers"), (W1_pools, "W1_pools"), (W2t_pools, "W2t_pools"), (b_pools, "b_pools")):
+        if t is None and name == "b_pools":
+            continue
+        if t.dtype != torch.int64 or not t.is_cuda or not t.is_contiguous() or t.numel() != L:
+            raise ValueError(f"{name}: need a contiguous int64 device tensor of {L} pointers")
+    S = int(seg_adapter.numel())
+    rc = load_library().preft_direft_apply_layers(
+        h_layers.data_ptr(), ldh, L, T, d,
+        _table(seg_start, "seg_start", S + 1), _table(seg_adapter, "seg_adapter", S),
+        _table(seg_prefill_len, "seg_prefill_len", S), S,
+        W1_pools.data_ptr(), W2t_pools.data_ptr(), None if b_pools is None else b_pools.data_ptr(), int(N),
+        int(rank), float(scale), _dtype_code(hs[0]), int(mode),
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc, "preft_direft_apply_layers")
 
 
 def _reft_apply(entry: str, h, seg_start, seg_adapter, seg_prefill_len, W1_pool, W2t_pool, b_pool, rank, scale,

@@ -206,7 +206,26 @@ struct ApplyArgs {
         const void *const  *A_pool;
         const void *const  *Bt_pool;
     } more[2];
+    // several layers in one launch (in-place calls only): blockIdx.y picks the residual stream
+    // and the pools of its layer from these device tables; h_layers null: the one layer above
+    void *const               *h_layers = nullptr;      // [n_layers]
+    const void *const *const  *A_layers = nullptr;      // [n_layers] pointer tables as A_pool
+    const void *const *const  *Bt_layers = nullptr;
+    const void *const *const  *bias_layers = nullptr;   // null: no bias in any layer
+    int32_t                    n_layers = 1;
 };
+
+// Kernels of a many-layer in-place call: switch to the layer this workgroup belongs to
+// (uniform: scalar loads).
+__device__ __forceinline__ void select_layer(ApplyArgs &p)
+{
+    const int l = blockIdx.y;
+    p.y = p.h_layers[l];
+    p.x = p.y;
+    p.A_pool = p.A_layers[l];
+    p.Bt_pool = p.Bt_layers[l];
+    p.bias_pool = p.bias_layers ? p.bias_layers[l] : nullptr;
+}
 
 template <int SL> __device__ __forceinline__ void *slice_y(const ApplyArgs &p) { if constexpr (SL == 0) return p.y; else return p.more[SL - 1].y; }
 template <int SL> __device__ __forceinline__ int64_t slice_ldy(const ApplyArgs &p) { if constexpr (SL == 0) return p.ldy; else return p.more[SL - 1].ldy; }

@@ -76,7 +76,7 @@ constexpr int mfma_min_waves(int NB, int MB, int WAVES, int HUNITS)
 //
 // COLSPLIT (LoRA only): the small-batch shape, see below.
 template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT, int SLICES = 1, bool COLSPLIT = false>
-__global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) void mfma_tile_kernel(ApplyArgs p)
+__device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
 {
     static_assert(!COLSPLIT || !DIREFT, "a tile of an in-place call belongs to one workgroup");
     // x is read a second time by this workgroup (in place without a resident tile) or by the
@@ -555,6 +555,20 @@ __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) 
     expand_slice(std::integral_constant<int, 0>{});
     if constexpr (SLICES > 1) expand_slice(std::integral_constant<int, 1>{});
     if constexpr (SLICES > 2) expand_slice(std::integral_constant<int, 2>{});
+}
+
+template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT, int SLICES = 1, bool COLSPLIT = false>
+__global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) void mfma_tile_kernel(ApplyArgs p)
+{
+    mfma_tile_body<NB, MB, WAVES, HUNITS, DIREFT, SLICES, COLSPLIT>(p);
+}
+
+// the same for one of several residual streams (in-place calls): blockIdx.y is the layer
+template <int NB, int MB, int WAVES, int HUNITS>
+__global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) void mfma_tile_layers_kernel(ApplyArgs p)
+{
+    select_layer(p);
+    mfma_tile_body<NB, MB, WAVES, HUNITS, true, 1, false>(p);
 }
 
 }  // namespace preft

@@ -32,7 +32,7 @@ constexpr int wide_lds_bytes(int NB, int MB, int WAVES)
 }
 
 template <int NB, int MB, int WAVES, bool DIREFT>
-__global__ __launch_bounds__(WAVES * 64) void mfma_wide_kernel(ApplyArgs p)
+__device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
 {
     constexpr int R = 16 * MB * WAVES;
     constexpr int TPC = CHUNK_ROWS / R;
@@ -334,6 +334,20 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_wide_kernel(ApplyArgs p)
             finish_unit(yop, u & 1, u);
         }
     }
+}
+
+template <int NB, int MB, int WAVES, bool DIREFT>
+__global__ __launch_bounds__(WAVES * 64) void mfma_wide_kernel(ApplyArgs p)
+{
+    mfma_wide_body<NB, MB, WAVES, DIREFT>(p);
+}
+
+// the same for one of several residual streams (in-place calls): blockIdx.y is the layer
+template <int NB, int MB, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void mfma_wide_layers_kernel(ApplyArgs p)
+{
+    select_layer(p);
+    mfma_wide_body<NB, MB, WAVES, true>(p);
 }
 
 }  // namespace preft

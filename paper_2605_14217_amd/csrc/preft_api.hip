@@ -107,8 +107,11 @@ template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT>
 void launch_mfma(const ApplyArgs &a, int64_t S, hipStream_t stream)
 {
     constexpr int R = 16 * MB;
-    hipLaunchKernelGGL((mfma_tile_kernel<NB, MB, WAVES, HUNITS, DIREFT>), dim3(tile_grid(a, S, R)),
-                       dim3(WAVES * 64), 0, stream, a);
+    void (*kernel)(ApplyArgs) = mfma_tile_kernel<NB, MB, WAVES, HUNITS, DIREFT>;
+    if constexpr (DIREFT) {
+        if (a.h_layers) kernel = mfma_tile_layers_kernel<NB, MB, WAVES, HUNITS>;
+    }
+    hipLaunchKernelGGL(kernel, dim3(tile_grid(a, S, R), a.n_layers), dim3(WAVES * 64), 0, stream, a);
 }
 
 // streaming variant (activations read in both sweeps): LoRA, and DiReFT rows too wide to hold
@@ -160,15 +163,24 @@ bool launch_mfma_wide(const ApplyArgs &a, int64_t S, int mb, int waves, hipStrea
     {
         if (NB < 2 && g_variant != 4) return false;           // rank <= 16: only on request
         if ((a.d_in & 127) || (a.d_out & 127)) return false;
-        if (mb == 1) {
-            if (waves == 8) hipLaunchKernelGGL((mfma_wide_kernel<NB, 1, 8, DIREFT>), dim3(chunk_grid(a, S, 128)), dim3(512), 0, stream, a);
-            else            hipLaunchKernelGGL((mfma_wide_kernel<NB, 1, 4, DIREFT>), dim3(chunk_grid(a, S, 64)), dim3(256), 0, stream, a);
+        void (*kernel)(ApplyArgs);
+        int rows = 128, threads = 512;
+        constexpr bool L = DIREFT;                              // a.h_layers is set on in-place calls only
+        if (mb == 1 && waves != 8) {
+            kernel = mfma_wide_kernel<NB, 1, 4, DIREFT>;
+            if constexpr (L) { if (a.h_layers) kernel = mfma_wide_layers_kernel<NB, 1, 4>; }
+            rows = 64; threads = 256;
+        } else if (mb != 1 && NB <= 4) {
+            if constexpr (NB <= 4) {
+                kernel = mfma_wide_kernel<NB, 2, 4, DIREFT>;
+                if constexpr (L) { if (a.h_layers) kernel = mfma_wide_layers_kernel<NB, 2, 4>; }
+            }
+            threads = 256;
         } else {
-            if constexpr (NB <= 4)
-                hipLaunchKernelGGL((mfma_wide_kernel<NB, 2, 4, DIREFT>), dim3(chunk_grid(a, S, 128)), dim3(256), 0, stream, a);
-            else
-                hipLaunchKernelGGL((mfma_wide_kernel<NB, 1, 8, DIREFT>), dim3(chunk_grid(a, S, 128)), dim3(512), 0, stream, a);
+            kernel = mfma_wide_kernel<NB, 1, 8, DIREFT>;
+            if constexpr (L) { if (a.h_layers) kernel = mfma_wide_layers_kernel<NB, 1, 8>; }
         }
+        hipLaunchKernelGGL(kernel, dim3(chunk_grid(a, S, rows), a.n_layers), dim3(threads), 0, stream, a);
         return true;
     }
 }
@@ -247,15 +259,19 @@ void launch_valu(const ApplyArgs &a, int64_t S, hipStream_t stream)
 {
     constexpr int RB = RANK <= 4 ? 4 : 2;
     int waves = g_waves ? g_waves : 4;
-    if (waves == 4)
-        hipLaunchKernelGGL((valu_tile_kernel<RANK, RB, 4, DIREFT>), dim3(tile_grid(a, S, RB * 4)),
-                           dim3(256), 0, stream, a);
-    else if (waves == 2)
-        hipLaunchKernelGGL((valu_tile_kernel<RANK, RB, 2, DIREFT>), dim3(tile_grid(a, S, RB * 2)),
-                           dim3(128), 0, stream, a);
-    else
-        hipLaunchKernelGGL((valu_tile_kernel<RANK, RB, 1, DIREFT>), dim3(tile_grid(a, S, RB)),
-                           dim3(64), 0, stream, a);
+    void (*kernel)(ApplyArgs);
+    if (waves == 4) {
+        kernel = valu_tile_kernel<RANK, RB, 4, DIREFT>;
+        if constexpr (DIREFT) { if (a.h_layers) kernel = valu_tile_layers_kernel<RANK, RB, 4>; }
+    } else if (waves == 2) {
+        kernel = valu_tile_kernel<RANK, RB, 2, DIREFT>;
+        if constexpr (DIREFT) { if (a.h_layers) kernel = valu_tile_layers_kernel<RANK, RB, 2>; }
+    } else {
+        waves = 1;
+        kernel = valu_tile_kernel<RANK, RB, 1, DIREFT>;
+        if constexpr (DIREFT) { if (a.h_layers) kernel = valu_tile_layers_kernel<RANK, RB, 1>; }
+    }
+    hipLaunchKernelGGL(kernel, dim3(tile_grid(a, S, RB * waves), a.n_layers), dim3(64 * waves), 0, stream, a);
 }
 
 // packed projections at ranks 1..3 (vector-ALU kernel)
@@ -288,14 +304,22 @@ void launch_valu_rank(const ApplyArgs &a, int64_t S, hipStream_t stream)
 template <typename E, bool DIREFT>
 void launch_rows(const ApplyArgs &a, int64_t S, bool chunks_too, hipStream_t stream)
 {
+    void (*chunks_kernel)(ApplyArgs) = row_kernel_chunks<E, DIREFT>;
+    void (*short_kernel)(ApplyArgs) = row_kernel_short<E, DIREFT>;
+    if constexpr (DIREFT) {
+        if (a.h_layers) {
+            chunks_kernel = row_layers_kernel_chunks<E>;
+            short_kernel = row_layers_kernel_short<E>;
+        }
+    }
     if (chunks_too) {
-        hipLaunchKernelGGL((row_kernel_chunks<E, DIREFT>),
-                           dim3((unsigned)(chunk_capacity(a.T, S) * (CHUNK_ROWS / GROUP_ROWS))),
+        hipLaunchKernelGGL(chunks_kernel,
+                           dim3((unsigned)(chunk_capacity(a.T, S) * (CHUNK_ROWS / GROUP_ROWS)), a.n_layers),
                            dim3(ROW_THREADS), 0, stream, a);
     }
     int64_t g = ((gtile_capacity(a.T, S, a.N) * GTILE_ROWS + 7) / 8) * 8;     // a multiple of 8: one share per XCD
     if (g > 4096) g = 4096;
-    hipLaunchKernelGGL((row_kernel_short<E, DIREFT>), dim3((unsigned)g), dim3(ROW_THREADS), 0, stream, a);
+    hipLaunchKernelGGL(short_kernel, dim3((unsigned)g, a.n_layers), dim3(ROW_THREADS), 0, stream, a);
 }
 
 enum class Path { Rows, Valu, Mfma };
@@ -352,6 +376,24 @@ int check_matrix(const void *p, int64_t ld, int32_t width, int dtype)
     if (!p || width <= 0 || ld < width) return PREFT_EINVAL;
     if (!aligned16(p) || (width % per16) != 0 || (ld % per16) != 0) return PREFT_EALIGN;
     return PREFT_OK;
+}
+
+// the in-place launch shared by the one-layer and the many-layer DiReFT entry points; `a` names
+// the residual stream(s) and the pools
+int direft_launch(ApplyArgs a, int64_t ldh, int32_t T, int32_t d, const int32_t *seg_start,
+                  const int32_t *seg_adapter, const int32_t *seg_prefill_len, int32_t S, int32_t N, int32_t rank,
+                  float scale, int dtype, int mode, void *workspace, void *stream)
+{
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (!(mode & PREFT_SCHEDULE_READY)) {
+        const int rc = launch_schedule(workspace, seg_start, seg_adapter, seg_prefill_len, S, T, N, mode, st);
+        if (rc != PREFT_OK) return rc;
+    }
+    ScheduleView v = view_of(workspace, T, S);
+    a.ldy = ldh; a.ldx = ldh; a.T = T; a.d_in = d; a.d_out = d;
+    a.N = N; a.rank = rank; a.scale = scale;
+    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.gtiles = v.gtiles; a.gathered_only = 0; a.col_split = 1;
+    return launch_apply<true>(a, S, dtype, st);
 }
 
 }  // namespace
@@ -528,17 +570,36 @@ int preft_direft_apply(void *h, int64_t ldh, int32_t T, int32_t d, const int32_t
     if (T == 0 || S == 0) return PREFT_OK;
     if ((rc = check_matrix(h, ldh, d, dtype)) != PREFT_OK) return rc;
     if (!W1_pool || !W2t_pool) return PREFT_EINVAL;
-    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    if (!(mode & PREFT_SCHEDULE_READY)) {
-        rc = launch_schedule(workspace, seg_start, seg_adapter, seg_prefill_len, S, T, N, mode, st);
-        if (rc != PREFT_OK) return rc;
-    }
-    ScheduleView v = view_of(workspace, T, S);
     ApplyArgs a;
-    a.y = h; a.x = h; a.ldy = ldh; a.ldx = ldh; a.T = T; a.d_in = d; a.d_out = d;
-    a.A_pool = W1_pool; a.Bt_pool = W2t_pool; a.bias_pool = b_pool; a.N = N; a.rank = rank; a.scale = scale;
-    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.gtiles = v.gtiles; a.gathered_only = 0; a.col_split = 1;
-    return launch_apply<true>(a, S, dtype, st);
+    a.y = h; a.x = h; a.A_pool = W1_pool; a.Bt_pool = W2t_pool; a.bias_pool = b_pool;
+    return direft_launch(a, ldh, T, d, seg_start, seg_adapter, seg_prefill_len, S, N, rank, scale, dtype, mode,
+                         workspace, stream);
+}
+
+int preft_direft_apply_layers(void *const *h_layers, int64_t ldh, int32_t n_layers, int32_t T, int32_t d,
+                              const int32_t *seg_start, const int32_t *seg_adapter,
+                              const int32_t *seg_prefill_len, int32_t S, const void *const *const *W1_pools,
+                              const void *const *const *W2t_pools, const void *const *const *b_pools, int32_t N,
+                              int32_t rank, float scale, int dtype, int mode, void *workspace, size_t bytes,
+                              void *stream)
+{
+    if (dtype != PREFT_F32 && dtype != PREFT_BF16) return PREFT_EINVAL;
+    if (n_layers < 0 || n_layers > PREFT_MAX_LAYERS) return PREFT_EINVAL;
+    int rc = check_tables(workspace, bytes, seg_start, seg_adapter, seg_prefill_len, S, T, N, mode);
+    if (rc != PREFT_OK) return rc;
+    if (rank < 1 || rank > PREFT_MAX_RANK) return PREFT_EUNSUPPORTED;
+    if (T == 0 || S == 0 || n_layers == 0) return PREFT_OK;
+    if (!h_layers || !W1_pools || !W2t_pools) return PREFT_EINVAL;
+    // the residual streams themselves are named on the device: only their common shape is checked
+    const int per16 = dtype == PREFT_BF16 ? 8 : 4;
+    if (d <= 0 || ldh < d) return PREFT_EINVAL;
+    if ((d % per16) || (ldh % per16)) return PREFT_EALIGN;
+    ApplyArgs a;
+    a.y = nullptr; a.x = nullptr; a.A_pool = nullptr; a.Bt_pool = nullptr; a.bias_pool = nullptr;
+    a.h_layers = h_layers; a.A_layers = W1_pools; a.Bt_layers = W2t_pools; a.bias_layers = b_pools;
+    a.n_layers = n_layers;
+    return direft_launch(a, ldh, T, d, seg_start, seg_adapter, seg_prefill_len, S, N, rank, scale, dtype, mode,
+                         workspace, stream);
 }
 
 int preft_schedule_counts(const void *workspace, int32_t *counts, void *stream)

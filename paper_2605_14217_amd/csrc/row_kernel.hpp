@@ -234,7 +234,7 @@ __device__ __forceinline__ void group_apply(const ApplyArgs &p, int adapter, con
 // GROUP_ROWS rows, fewer when the batch has few short rows so that a decode-only step still
 // fills the chip; grid-stride over the groups.
 template <typename E, bool DIREFT>
-__global__ __launch_bounds__(ROW_THREADS) void row_kernel_short(ApplyArgs p)
+__device__ __forceinline__ void row_short_body(const ApplyArgs &p)
 {
     __shared__ float z[GROUP_ROWS * PREFT_MAX_RANK_DEV];
     const int grows = max(1, min(GROUP_ROWS, p.header[1] / 512));
@@ -258,7 +258,7 @@ __global__ __launch_bounds__(ROW_THREADS) void row_kernel_short(ApplyArgs p)
 
 // Generic fallback for chunks: one workgroup per GROUP_ROWS consecutive rows of a chunk.
 template <typename E, bool DIREFT>
-__global__ __launch_bounds__(ROW_THREADS) void row_kernel_chunks(ApplyArgs p)
+__device__ __forceinline__ void row_chunks_body(const ApplyArgs &p)
 {
     __shared__ float z[GROUP_ROWS * PREFT_MAX_RANK_DEV];
     constexpr int PER_CHUNK = CHUNK_ROWS / GROUP_ROWS;
@@ -272,6 +272,25 @@ __global__ __launch_bounds__(ROW_THREADS) void row_kernel_chunks(ApplyArgs p)
 #pragma unroll
     for (int j = 0; j < GROUP_ROWS; ++j) rows[j] = ch.y + first + min(j, count - 1);
     group_apply<E, DIREFT>(p, ch.x, rows, count, z);
+}
+
+template <typename E, bool DIREFT>
+__global__ __launch_bounds__(ROW_THREADS) void row_kernel_short(ApplyArgs p) { row_short_body<E, DIREFT>(p); }
+template <typename E, bool DIREFT>
+__global__ __launch_bounds__(ROW_THREADS) void row_kernel_chunks(ApplyArgs p) { row_chunks_body<E, DIREFT>(p); }
+
+// the same for one of several residual streams (in-place calls): blockIdx.y is the layer
+template <typename E>
+__global__ __launch_bounds__(ROW_THREADS) void row_layers_kernel_short(ApplyArgs p)
+{
+    select_layer(p);
+    row_short_body<E, true>(p);
+}
+template <typename E>
+__global__ __launch_bounds__(ROW_THREADS) void row_layers_kernel_chunks(ApplyArgs p)
+{
+    select_layer(p);
+    row_chunks_body<E, true>(p);
 }
 
 }  // namespace preft

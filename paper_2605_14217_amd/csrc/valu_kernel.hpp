@@ -32,7 +32,7 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc)
 }
 
 template <int RANK, int RB, int WAVES, bool DIREFT, int SLICES = 1>
-__global__ __launch_bounds__(WAVES * 64) void valu_tile_kernel(ApplyArgs p)
+__device__ __forceinline__ void valu_tile_body(const ApplyArgs &p)
 {
     constexpr int R = RB * WAVES;
     constexpr int RT = RANK * SLICES;                         // partial sums per row in the shrink sweep
@@ -160,6 +160,20 @@ __global__ __launch_bounds__(WAVES * 64) void valu_tile_kernel(ApplyArgs p)
     expand_slice(std::integral_constant<int, 0>{});
     if constexpr (SLICES > 1) expand_slice(std::integral_constant<int, 1>{});
     if constexpr (SLICES > 2) expand_slice(std::integral_constant<int, 2>{});
+}
+
+template <int RANK, int RB, int WAVES, bool DIREFT, int SLICES = 1>
+__global__ __launch_bounds__(WAVES * 64) void valu_tile_kernel(ApplyArgs p)
+{
+    valu_tile_body<RANK, RB, WAVES, DIREFT, SLICES>(p);
+}
+
+// the same for one of several residual streams (in-place calls): blockIdx.y is the layer
+template <int RANK, int RB, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void valu_tile_layers_kernel(ApplyArgs p)
+{
+    select_layer(p);
+    valu_tile_body<RANK, RB, WAVES, true, 1>(p);
 }
 
 }  // namespace preft

@@ -173,6 +173,42 @@ def run_direft_case(tab: wl.SegmentTable, pool: wl.DireftPool, h0: torch.Tensor,
     return worst, counts
 
 
+def run_direft_layers_case(tab: wl.SegmentTable, pools, h0s, dtype: str, scale: float, all_tokens: bool,
+                           bias_layers, pad_cols=0):
+    """One many-layer call on len(h0s) residual streams (layer l: pools[l], bias iff bias_layers[l]).
+    Every layer is compared with the oracle and, bit for bit, with a one-layer call on a copy."""
+    L, N, r, T = len(h0s), pools[0].N, pools[0].r, tab.T
+    mode = preft.PREFT_ALL_TOKENS if all_tokens else preft.PREFT_PREFILL_ONLY
+    ss, sa, sp = dev_tables(tab)
+    dev = [direft_pools_to_device(pools[l], None, bias_layers[l]) for l in range(L)]
+    bufs = [padded(h0s[l], pad_cols, 7.0) for l in range(L)]
+    hs = [b[1] for b in bufs]
+    singles = [padded(h0s[l], pad_cols, 7.0) for l in range(L)]
+    table = lambda ptrs: torch.tensor(ptrs, dtype=torch.int64, device="cuda")
+    W1s = table([dev[l][0].data_ptr() for l in range(L)])
+    W2s = table([dev[l][1].data_ptr() for l in range(L)])
+    bs = table([dev[l][2].data_ptr() if bias_layers[l] else 0 for l in range(L)]) if any(bias_layers) else None
+    ws = preft.new_workspace(T, tab.S)
+    preft.preft_direft_apply_layers(hs, preft.pointer_table(hs) if all(h.is_contiguous() for h in hs) else
+                                    table([h.data_ptr() for h in hs]), ss, sa, sp, W1s, W2s, bs, N, r, scale, mode, ws)
+    for l in range(L):
+        preft.preft_direft_apply(singles[l][1], ss, sa, sp, dev[l][0], dev[l][1], dev[l][2], r, scale,
+                                 mode | preft.PREFT_SCHEDULE_READY, ws)
+    torch.cuda.synchronize()
+    pos = ora.ALL_POSITIONS if all_tokens else ora.PROMPT_ONLY
+    row_adapter = ora.positions(T, tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, N, pos)
+    needed = set(np.unique(row_adapter[row_adapter >= 0]).tolist())
+    worst = 0.0
+    for l in range(L):
+        check_guards(bufs[l][0], T, h0s[l].shape[1], 7.0)
+        assert torch.equal(bits(hs[l]), bits(singles[l][1])), f"layer {l}: differs from the one-layer call"
+        pick = lambda mats: [mats[i].cpu() if i in needed else None for i in range(N)]
+        want = ora.direft(h0s[l].cpu(), tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, pick(pools[l].A),
+                          pick(pools[l].B), pick(pools[l].b) if bias_layers[l] else None, r, scale, pos)
+        worst = max(worst, compare(hs[l], h0s[l], want, row_adapter, dtype))
+    return worst
+
+
 def run_loreft_case(tab: wl.SegmentTable, W, R, b, h0: torch.Tensor, dtype: str, scale: float, all_tokens: bool,
                     pad_cols=0):
     """W, R: lists of [r,d] device tensors, b: list of [r] or None.  Derived factors come from

@@ -142,6 +142,23 @@ def test_packed_and_loreft_arguments_are_rejected_before_any_launch(lib):
     assert packed(pools=(fake, None)) == -1
     assert packed(T=0) == 0
 
+    def layers(hl=fake, ldh=64, L=3, T=64, d=64, S=4, rank=4, dtype=preft.PREFT_BF16, W1=fake, W2=fake, ws=fake,
+               wsb=ws_bytes, tables=fake):
+        return lib.preft_direft_apply_layers(hl, ldh, L, T, d, tables, tables, tables, S, W1, W2, None, 2, rank, 1.0,
+                                             dtype, 0, ws, wsb, None)
+
+    assert layers(L=-1) == -1
+    assert layers(L=1025) == -1
+    assert layers(L=0) == 0 and layers(T=0) == 0
+    assert layers(hl=None) == -1
+    assert layers(W1=None) == -1 and layers(W2=None) == -1
+    assert layers(rank=0) == -2
+    assert layers(dtype=4) == -1
+    assert layers(d=60) == -3 and layers(ldh=68) == -3
+    assert layers(ldh=32) == -1
+    assert layers(wsb=8) == -4
+    assert layers(tables=None) == -1
+
     def prepare(D=0x7f0000400000, Rt=0x7f0000500000, W=0x7f0000600000, R=0x7f0000700000, d=64, rank=4,
                 dtype=preft.PREFT_BF16):
         return lib.preft_loreft_prepare(D, Rt, W, R, d, rank, dtype, None)

@@ -596,3 +596,66 @@ def test_column_split_with_packed_projections_and_in_place_calls(colsplit):
     pool = wl.direft_pool(N, r, d, "bf16", device="cuda", seed=81)
     h = wl.activations(tab.T, d, "bf16", device="cuda", seed=82)
     run_direft_case(tab, pool, h, "bf16", 0.25, True)
+
+
+# ---------------------------------------------------------------------------------------
+# DiReFT on several layers' residual streams in one launch
+# ---------------------------------------------------------------------------------------
+LAYER_CASES = [
+    # (variant, dtype, rank, d, layers, waves, rowblocks): every kernel family an in-place call can take
+    (0, "bf16", 8, 1024, 3, 0, 0), (0, "bf16", 16, 4096, 2, 0, 0), (0, "bf16", 16, 8192, 2, 0, 0),   # resident tiles
+    (0, "bf16", 16, 1000, 3, 0, 0), (0, "bf16", 32, 1024, 2, 0, 0), (0, "bf16", 64, 512, 3, 0, 0),   # streamed, row-split
+    (0, "bf16", 2, 520, 4, 0, 0), (0, "bf16", 7, 256, 2, 0, 0), (VARIANT_VALU, "bf16", 4, 512, 2, 2, 0),
+    (VARIANT_ROW, "bf16", 12, 264, 3, 0, 0), (0, "f32", 4, 132, 5, 0, 0), (0, "bf16", 24, 264, 2, 0, 0),
+]
+
+
+@pytest.mark.parametrize("variant,dtype,rank,d,layers,waves,rowblocks", LAYER_CASES,
+                         ids=[f"v{c[0]}-{c[1]}-r{c[2]}-d{c[3]}-L{c[4]}" for c in LAYER_CASES])
+def test_direft_layers_match_the_oracle_and_the_one_layer_call(variant, dtype, rank, d, layers, waves, rowblocks):
+    from parity_util import run_direft_layers_case
+    N = 4
+    tab = _mixed_table(rank * 31 + d, N, max_len=40 if d > 4200 else 150, n_prompts=3 if d > 4200 else 5)
+    pools = [wl.direft_pool(N, rank, d, dtype, device="cuda", seed=100 + l) for l in range(layers)]
+    h0s = [wl.activations(tab.T, d, dtype, device="cuda", seed=200 + l) for l in range(layers)]
+    for all_tokens, bias_layers in ((False, [True] * layers), (True, [l % 2 == 0 for l in range(layers)]),
+                                    (False, [False] * layers)):
+        _set(variant, waves, rowblocks)
+        worst = run_direft_layers_case(tab, pools, h0s, dtype, 1.0 / np.sqrt(rank), all_tokens, bias_layers, pad_cols=8)
+        print(f"  layers={layers} all_tokens={all_tokens} bias={bias_layers} worst rel err {worst:.2e}")
+
+
+def test_direft_layers_leave_other_layers_and_decode_rows_alone():
+    """A call on layers 0 and 2 of three buffers leaves buffer 1 bit-identical; in prefill-only mode an
+    all-decode batch leaves every buffer bit-identical; zero layers is a no-op."""
+    from parity_util import bits, dev_tables, direft_pools_to_device
+    N, r, d = 3, 16, 2048
+    tab = _mixed_table(5, N)
+    hs0 = [wl.activations(tab.T, d, "bf16", device="cuda", seed=300 + l) for l in range(3)]
+    hs = [h.clone() for h in hs0]
+    dev = [direft_pools_to_device(wl.direft_pool(N, r, d, "bf16", device="cuda", seed=310 + l)) for l in range(2)]
+    table = lambda ptrs: torch.tensor(ptrs, dtype=torch.int64, device="cuda")
+    ss, sa, sp = dev_tables(tab)
+    ws = preft.new_workspace(tab.T, tab.S)
+    used = [hs[0], hs[2]]
+    args = (table([m[0].data_ptr() for m in dev]), table([m[1].data_ptr() for m in dev]),
+            table([m[2].data_ptr() for m in dev]), N, r, 1.0)
+    preft.preft_direft_apply_layers(used, preft.pointer_table(used), ss, sa, sp, *args, preft.PREFT_ALL_TOKENS, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(bits(hs[1]), bits(hs0[1]))
+    assert not torch.equal(bits(hs[0]), bits(hs0[0])) and not torch.equal(bits(hs[2]), bits(hs0[2]))
+    # all-decode batch, prefill-only: nothing moves
+    S = 12
+    dec = wl.SegmentTable(np.arange(S + 1, dtype=np.int32), np.arange(S, dtype=np.int32) % N, np.zeros(S, dtype=np.int32))
+    ss, sa, sp = dev_tables(dec)
+    small0 = [wl.activations(S, d, "bf16", device="cuda", seed=320 + l) for l in range(2)]
+    small = [h.clone() for h in small0]
+    ws = preft.new_workspace(S, S)
+    preft.preft_direft_apply_layers(small, preft.pointer_table(small), ss, sa, sp, *args, preft.PREFT_PREFILL_ONLY, ws)
+    torch.cuda.synchronize()
+    assert all(torch.equal(bits(a), bits(b)) for a, b in zip(small, small0))
+    lib = preft.load_library()
+    rc = lib.preft_direft_apply_layers(None, d, 0, S, d, ss.data_ptr(), sa.data_ptr(), sp.data_ptr(), S, None, None, None,
+                                       N, r, 1.0, preft.PREFT_BF16, 0, ws.data_ptr(), ws.numel() * ws.element_size(), None)
+    assert rc == 0
+
