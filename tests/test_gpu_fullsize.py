@@ -109,3 +109,44 @@ def test_fullsize_packed_lora(config, projs, rank, all_tokens):
                         cfg["lora_scale"], pos, rows=rows, gathered=True)
         worst = max(worst, compare(ys[i], y0s[i], want, owner, "bf16", rows=rows))
     print(f"  T={tab.T} S={tab.S} rows checked={len(rows)} outputs={len(projs)} worst {worst:.2e}")
+
+
+LAYERS = [("llama8b_direft", 16, 4, False), ("llama8b_lora", 8, 3, True), ("skewed70b", 32, 2, False)]
+
+
+@pytest.mark.parametrize("config,rank,layers,all_tokens", LAYERS,
+                         ids=[f"{c}-r{r}-L{n}-{'all' if a else 'prefill'}" for c, r, n, a in LAYERS])
+def test_fullsize_direft_layers(config, rank, layers, all_tokens):
+    """DiReFT on several layers' residual streams in one launch, as the benchmark's every-layer leg
+    issues it: every layer on sampled rows against the oracle, all inactive rows bit for bit."""
+    from oracle import preft_oracle as ora
+    from parity_util import compare, dev_tables, direft_pools_to_device
+    cfg = wl.CONFIGS[config]
+    N, d = cfg["N"], cfg["direft_d"]
+    tab = wl.make_segments(config, seed=0)
+    pools = [wl.direft_pool(N, rank, d, "bf16", device="cuda", seed=400 + l) for l in range(layers)]
+    dev = [direft_pools_to_device(pl) for pl in pools]
+    h0s = [wl.activations(tab.T, d, "bf16", device="cuda", seed=410 + l) for l in range(layers)]
+    hs = [h.clone() for h in h0s]
+    table = lambda ptrs: torch.tensor(ptrs, dtype=torch.int64, device="cuda")
+    ss, sa, sp = dev_tables(tab)
+    ws = preft.new_workspace(tab.T, tab.S)
+    mode = preft.PREFT_ALL_TOKENS if all_tokens else preft.PREFT_PREFILL_ONLY
+    scale = 1.0 / np.sqrt(rank)
+    preft.preft_direft_apply_layers(hs, preft.pointer_table(hs), ss, sa, sp, table([m[0].data_ptr() for m in dev]),
+                                    table([m[1].data_ptr() for m in dev]), table([m[2].data_ptr() for m in dev]),
+                                    N, rank, scale, mode, ws)
+    torch.cuda.synchronize()
+    rows = wl.sample_rows(tab, 2, max_rows=800)
+    idx = torch.from_numpy(np.asarray(rows)).to("cuda")
+    pos = ora.ALL_POSITIONS if all_tokens else ora.PROMPT_ONLY
+    owner = ora.positions(tab.T, tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, N, pos)
+    needed = set(np.unique(owner[rows][owner[rows] >= 0]).tolist())
+    worst = 0.0
+    for l, pl in enumerate(pools):
+        pick = lambda mats: [mats[j].cpu() if j in needed else None for j in range(N)]
+        want = ora.direft(h0s[l][idx].cpu(), tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, pick(pl.A), pick(pl.B),
+                          pick(pl.b), rank, scale, pos, rows=rows, gathered=True)
+        worst = max(worst, compare(hs[l], h0s[l], want, owner, "bf16", rows=rows))
+    print(f"  T={tab.T} layers={layers} rows checked={len(rows)} worst {worst:.2e}")
+
