@@ -382,6 +382,60 @@ def test_calls_are_graph_capturable_and_read_their_tables_on_the_device():
         assert not torch.equal(bits(got), bits(y0))
 
 
+def test_packed_and_many_layer_calls_are_graph_capturable():
+    """The same promise for the packed LoRA call and the many-layer DiReFT call: a captured graph,
+    replayed with the tables rewritten in place, matches the eager run every time."""
+    from parity_util import bits, dev_tables, direft_pools_to_device, lora_pools_to_device
+    N, d, r, L = 5, 512, 8, 3
+    rng = np.random.Generator(np.random.PCG64(78))
+    lens = np.array([200, 1, 1, 77, 1, 140, 2, 1, 33])
+    tabs = []
+    for k in range(3):
+        ids = rng.integers(-1, N, size=len(lens))
+        pre = np.where(rng.random(len(lens)) < 0.5, lens, (lens * rng.random(len(lens))).astype(np.int64))
+        tabs.append(wl.from_lengths(lens, ids, pre))
+    T, S = tabs[0].T, tabs[0].S
+    pools = [lora_pools_to_device(wl.lora_pool(N, r, d, n, "bf16", device="cuda", seed=80 + i)) for i, n in enumerate((256, 384))]
+    dev = [direft_pools_to_device(wl.direft_pool(N, r, d, "bf16", device="cuda", seed=85 + l)) for l in range(L)]
+    table = lambda ptrs: torch.tensor(ptrs, dtype=torch.int64, device="cuda")
+    W1s, W2s, bs = (table([m[i].data_ptr() for m in dev]) for i in range(3))
+    x = wl.activations(T, d, "bf16", device="cuda", seed=86)
+    y0 = wl.activations(T, 640, "bf16", device="cuda", seed=87)
+    h0s = [wl.activations(T, d, "bf16", device="cuda", seed=88 + l) for l in range(L)]
+    y, hs = y0.clone(), [h.clone() for h in h0s]
+    h_tab = preft.pointer_table(hs)
+    ss, sa, sp = dev_tables(tabs[0])
+    ws = preft.new_workspace(T, S)
+    mode = preft.PREFT_ALL_TOKENS
+
+    def body():
+        y.copy_(y0)
+        for h, h0 in zip(hs, h0s):
+            h.copy_(h0)
+        preft.preft_schedule(ws, ss, sa, sp, T, N, mode)
+        ready = mode | preft.PREFT_SCHEDULE_READY
+        preft.preft_lora_apply_packed([y[:, :256], y[:, 256:]], x, ss, sa, sp, [p[0] for p in pools],
+                                      [p[1] for p in pools], r, 2.0, ready, ws)
+        preft.preft_direft_apply_layers(hs, h_tab, ss, sa, sp, W1s, W2s, bs, N, r, 0.5, ready, ws)
+
+    body()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        body()
+    for k in (2, 0, 1, 2):
+        sa.copy_(torch.from_numpy(tabs[k].seg_adapter.copy()))
+        sp.copy_(torch.from_numpy(tabs[k].seg_prefill_len.copy()))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [y.clone()] + [h.clone() for h in hs]
+        body()
+        torch.cuda.synchronize()
+        for a, b in zip(got, [y] + hs):
+            assert torch.equal(bits(a), bits(b)), f"graph replay differs from the eager run (table {k})"
+        assert not torch.equal(bits(got[0]), bits(y0)) and not torch.equal(bits(got[1]), bits(h0s[0]))
+
+
 def test_fcfs_trace_steps_match_the_oracle():
     """Every engine step of a small first-come-first-served serving trace (App. E.1, E.3), in both
     modes: prompt steps mix whole prompts with decode rows, decode-only steps hold one row per
