@@ -32,11 +32,6 @@ if ROOT not in sys.path:
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E, published
 
 
-def direft_bytes(T_act, d, r, n_adapters, e=2):
-    """Algorithmic bytes of one DiReFT apply: h once in, once out; factors and bias once."""
-    return e * T_act * 2 * d + e * (2 * r * d + r) * n_adapters
-
-
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -199,13 +194,12 @@ def main():
     for i, g_ in enumerate(groups):
         m = g_["members"]
         # x once per launch, every output read and written once, every distinct adapter's factors once
-        b = 2 * T_act * (m[0]["d_in"] + 2 * sum(q["d_out"] for q in m)) \
-            + 2 * r * n_ad * sum(q["d_in"] + q["d_out"] for q in m)
+        b = wl.lora_algorithmic_bytes(T_act, m[0]["d_in"], [q["d_out"] for q in m], r, n_ad)
         breakdown[g_["name"]] = dict(us=round(mean_ms[i] * 1e3, 2), GBps=round(b / mean_ms[i] / 1e6, 1),
                                      frac=round(b / mean_ms[i] / 1e6 / PEAK_HBM_GBPS, 4))
         lora_b += b
         lora_t += mean_ms[i]
-    db = direft_bytes(T_act, d_res, r, n_ad)
+    db = wl.direft_algorithmic_bytes(T_act, d_res, r, n_ad)
     breakdown["direft"] = dict(us=round(mean_ms[-1] * 1e3, 2), GBps=round(db / mean_ms[-1] / 1e6, 1),
                                frac=round(db / mean_ms[-1] / 1e6 / PEAK_HBM_GBPS, 4))
     if projs:

@@ -64,6 +64,19 @@ class SegmentTable:
         return from_lengths(lens, self.seg_adapter[keep], np.zeros_like(lens))
 
 
+def lora_algorithmic_bytes(T_act: int, d_in: int, d_outs, r: int, n_adapters: int, e: int = 2) -> int:
+    """Bytes one LoRA launch has to move, whatever the kernel: every active row of x once, every
+    active row of each output once in and once out, and the two factors of every distinct active
+    adapter once per output.  d_outs: the outputs computed from the same x (one entry unless packed)."""
+    return e * T_act * (d_in + 2 * sum(d_outs)) + e * r * n_adapters * sum(d_in + n for n in d_outs)
+
+
+def direft_algorithmic_bytes(T_act: int, d: int, r: int, n_adapters: int, e: int = 2) -> int:
+    """Bytes one DiReFT launch has to move: every active row of h once in and once out; both
+    factors and the bias of every distinct active adapter once."""
+    return e * T_act * 2 * d + e * (2 * r * d + r) * n_adapters
+
+
 def from_lengths(lens, adapters, prefill_lens) -> SegmentTable:
     lens = np.asarray(lens, dtype=np.int64)
     start = np.zeros(len(lens) + 1, dtype=np.int64)
