@@ -188,14 +188,16 @@ bool launch_mfma_wide(const ApplyArgs &a, int64_t S, int mb, int waves, hipStrea
 template <int NB, bool DIREFT>
 void launch_mfma_nb(const ApplyArgs &a, int64_t S, hipStream_t stream)
 {
-    // rank >= 32: the factors outweigh a 16-row tile's activations, so more rows share them:
-    // the row-split kernel with 8 wavefronts x 16 rows (a whole 128-row chunk per workgroup)
+    // rank >= 32: the factors outweigh a 16-row tile's activations, so more rows share them: the
+    // row-split kernel.  Up to rank 64 with 4 wavefronts x 16 rows (two or three independent
+    // workgroups per compute unit and twice the tiles: measured 3-10 points ahead of 8 wavefronts on
+    // the 8B- and 70B-sized batches); above, 8 wavefronts (4 would leave one workgroup per unit)
     const int wide_mb = g_rowblocks ? g_rowblocks : 1;
-    const int wide_waves = g_waves ? (g_waves == 8 ? 8 : 4) : 8;
+    const int wide_waves = g_waves ? (g_waves == 8 ? 8 : 4) : (NB <= 4 ? 4 : 8);
     // column-split kernel.  rank <= 16: 8 wavefronts per 16-row tile; rank 32 (widths the
     // row-split kernel does not take): 32-row tiles of 4 wavefronts
     const int mb = g_rowblocks ? g_rowblocks : (NB == 2 ? 2 : 1);
-    const int waves = g_waves ? (g_waves == 8 ? 8 : 4) : (NB == 2 ? 4 : wide_waves);
+    const int waves = g_waves ? (g_waves == 8 ? 8 : 4) : (NB == 2 ? 4 : 8);
     if constexpr (DIREFT) {
         if (g_waves == 0 && g_variant != 4 && launch_mfma_resident<NB>(a, S, stream)) return;
         // rank 32: 32-row tiles of the column-split kernel (half the factor traffic per row of a
