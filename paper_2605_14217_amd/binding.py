@@ -135,7 +135,8 @@ def _check(rc: int, where: str):
 
 
 def pointer_table(mats: Sequence[torch.Tensor]) -> torch.Tensor:
-    """Device array of device pointers, one per adapter slot (the pool argument of the C ABI)."""
+    """Device array of device pointers, one per adapter slot (the pool argument of the C ABI).
+    The table only names the tensors: the caller keeps them alive while the table is in use."""
     dev = mats[0].device
     for m in mats:
         if not m.is_cuda or not m.is_contiguous():

@@ -713,3 +713,75 @@ def test_direft_layers_leave_other_layers_and_decode_rows_alone():
                                        N, r, 1.0, preft.PREFT_BF16, 0, ws.data_ptr(), ws.numel() * ws.element_size(), None)
     assert rc == 0
 
+
+# ---------------------------------------------------------------------------------------
+# exact arithmetic: small-integer data, every product and sum exact on both sides, so the kernel's
+# output must be the oracle's fp64 result rounded once to the storage type -- bit for bit
+# ---------------------------------------------------------------------------------------
+EXACT_CASES = [
+    # (dtype, variant, rank, d_in, d_out): one case per kernel family
+    ("bf16", VARIANT_AUTO, 16, 256, 384), ("bf16", VARIANT_AUTO, 8, 200, 72), ("bf16", VARIANT_VALU, 2, 136, 264),
+    ("bf16", VARIANT_AUTO, 32, 256, 256), ("bf16", VARIANT_AUTO, 64, 128, 384), ("bf16", VARIANT_ROW, 5, 64, 40),
+    ("f32", VARIANT_AUTO, 4, 132, 68), ("f32", VARIANT_AUTO, 9, 64, 64),
+]
+
+
+def _same_bits(got, rounded, exact, row_adapter, what):
+    from parity_util import bits
+    bad = (bits(got) != bits(rounded)).nonzero()
+    if len(bad):
+        lines = [f"row {int(t)} (adapter {int(row_adapter[t])}) col {int(j)}: got {float(got[t, j])}, "
+                 f"exact {float(exact[t, j])} -> {float(rounded[t, j])}" for t, j in bad[:8].tolist()]
+        raise AssertionError(f"{what}: {len(bad)} of {got.numel()} elements differ from the exactly rounded "
+                             "result\n" + "\n".join(lines))
+
+
+@pytest.mark.parametrize("dtype,variant,rank,d_in,d_out", EXACT_CASES,
+                         ids=[f"{c[0]}-v{c[1]}-r{c[2]}-{c[3]}x{c[4]}" for c in EXACT_CASES])
+def test_integer_data_gives_the_exactly_rounded_result(dtype, variant, rank, d_in, d_out):
+    from oracle import preft_oracle as ora
+    from parity_util import bits, dev_tables
+    N = 4
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    gen = torch.Generator(device="cpu").manual_seed(rank * 1000 + d_in)
+    ints = lambda shape, lo, hi: torch.randint(lo, hi + 1, shape, generator=gen).to(tdt).cuda()
+    tab = _mixed_table(rank + d_in + d_out, N, max_len=90)
+    T = tab.T
+    ss, sa, sp = dev_tables(tab)
+    ws = preft.new_workspace(T, tab.S)
+    mode = preft.PREFT_ALL_TOKENS
+    row_adapter = ora.positions(T, tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, N, ora.ALL_POSITIONS)
+    assert (row_adapter >= 0).sum() > 100
+
+    # LoRA: |x| <= 2, A in {-1,0,1}, B in {-1,0,1}, s = 0.5: |z| <= 2 d_in, halves; |delta| <= rank d_in
+    x, y0 = ints((T, d_in), -2, 2), ints((T, d_out), -3, 3)
+    A = [ints((rank, d_in), -1, 1) for _ in range(N)]
+    B = [ints((d_out, rank), -1, 1) for _ in range(N)]
+    y = y0.clone()
+    _set(variant)
+    preft.preft_lora_apply(y, x, ss, sa, sp, preft.pointer_table(A), preft.pointer_table(B), rank, 0.5, mode, ws)
+    torch.cuda.synchronize()
+    want = ora.lora(y0.cpu(), x.cpu(), tab.seg_start, tab.seg_adapter, tab.seg_prefill_len,
+                    [a.cpu() for a in A], [b.cpu() for b in B], rank, 0.5, ora.ALL_POSITIONS)
+    assert np.array_equal(want * 2, np.round(want * 2)), "the reference values should be multiples of 1/2"
+    assert np.abs(want).max() < 2 ** 15
+    rounded = torch.from_numpy(want).to(torch.float32).to(tdt)       # exact in fp32, then one rounding to nearest even
+    _same_bits(y.cpu(), rounded, want, row_adapter, "LoRA")
+    assert (y.cpu() != y0.cpu()).any()
+
+    # DiReFT on the d_in-wide stream: h' = h + s W2^T (W1 h + b)
+    h0 = ints((T, d_in), -2, 2)
+    W1 = [ints((rank, d_in), -1, 1) for _ in range(N)]
+    W2 = [ints((rank, d_in), -1, 1) for _ in range(N)]
+    b = [ints((rank,), -4, 4) for _ in range(N)]
+    h = h0.clone()
+    _set(variant)
+    W2t = [w.t().contiguous() for w in W2]                   # kept alive: the pointer table only names them
+    preft.preft_direft_apply(h, ss, sa, sp, preft.pointer_table(W1), preft.pointer_table(W2t),
+                             preft.pointer_table(b), rank, 0.5, mode, ws)
+    torch.cuda.synchronize()
+    want = ora.direft(h0.cpu(), tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, [w.cpu() for w in W1],
+                      [w.cpu() for w in W2], [v.cpu() for v in b], rank, 0.5, ora.ALL_POSITIONS)
+    rounded = torch.from_numpy(want).to(torch.float32).to(tdt)
+    _same_bits(h.cpu(), rounded, want, row_adapter, "DiReFT")
+
