@@ -768,6 +768,16 @@ def test_integer_data_gives_the_exactly_rounded_result(dtype, variant, rank, d_i
     rounded = torch.from_numpy(want).to(torch.float32).to(tdt)       # exact in fp32, then one rounding to nearest even
     _same_bits(y.cpu(), rounded, want, row_adapter, "LoRA")
     assert (y.cpu() != y0.cpu()).any()
+    # the same projection as a packed call on two column ranges of one output buffer
+    cut = (d_out // 16) * 8
+    y2 = y0.clone()
+    B_lo, B_hi = [m[:cut].contiguous() for m in B], [m[cut:].contiguous() for m in B]
+    Ap = preft.pointer_table(A)
+    _set(variant)
+    preft.preft_lora_apply_packed([y2[:, :cut], y2[:, cut:]], x, ss, sa, sp, [Ap, Ap],
+                                  [preft.pointer_table(B_lo), preft.pointer_table(B_hi)], rank, 0.5, mode, ws)
+    torch.cuda.synchronize()
+    _same_bits(y2.cpu(), rounded, want, row_adapter, "packed LoRA")
 
     # DiReFT on the d_in-wide stream: h' = h + s W2^T (W1 h + b)
     h0 = ints((T, d_in), -2, 2)
