@@ -795,3 +795,41 @@ def test_integer_data_gives_the_exactly_rounded_result(dtype, variant, rank, d_i
     rounded = torch.from_numpy(want).to(torch.float32).to(tdt)
     _same_bits(h.cpu(), rounded, want, row_adapter, "DiReFT")
 
+
+@pytest.mark.parametrize("dtype,rank,d", [("bf16", 16, 512), ("bf16", 2, 264), ("bf16", 32, 256), ("bf16", 64, 1024), ("f32", 4, 132)])
+def test_segment_permutation_moves_the_rows_and_nothing_else(dtype, rank, d):
+    """Batch items are independent (Sec. 1): with the segments in another order -- rows moving with
+    them -- every row comes out with the same bits, whatever tile it now shares with other rows."""
+    from parity_util import bits, dev_tables, direft_pools_to_device, lora_pools_to_device
+    N = 5
+    rng = np.random.Generator(np.random.PCG64(rank * 7 + d))
+    tab = _mixed_table(rank + d + 3, N, max_len=200)
+    lens = tab.seg_len
+    order = rng.permutation(tab.S)
+    ptab = wl.from_lengths(lens[order], tab.seg_adapter[order], tab.seg_prefill_len[order])
+    # row t of the permuted batch is row src[t] of the original
+    src = np.concatenate([np.arange(tab.seg_start[s], tab.seg_start[s + 1]) for s in order]).astype(np.int64)
+    assert sorted(src.tolist()) == list(range(tab.T))
+    idx = torch.from_numpy(src).cuda()
+    pool = wl.lora_pool(N, rank, d, d + 8, dtype, device="cuda", seed=3)
+    dpool = wl.direft_pool(N, rank, d, dtype, device="cuda", seed=4)
+    Ap, Bp, keep1 = lora_pools_to_device(pool)
+    W1p, W2tp, bp, keep2 = direft_pools_to_device(dpool)
+    x = wl.activations(tab.T, d, dtype, device="cuda", seed=5)
+    y0 = wl.activations(tab.T, d + 8, dtype, device="cuda", seed=6)
+    for mode in (preft.PREFT_PREFILL_ONLY, preft.PREFT_ALL_TOKENS):
+        outs = []
+        for t, rows in ((tab, None), (ptab, idx)):
+            ss, sa, sp = dev_tables(t)
+            ws = preft.new_workspace(t.T, t.S)
+            xx, yy = (x, y0.clone()) if rows is None else (x[rows].contiguous(), y0[rows].contiguous())
+            hh = xx.clone()
+            preft.preft_lora_apply(yy, xx, ss, sa, sp, Ap, Bp, rank, 2.0, mode, ws)
+            preft.preft_direft_apply(hh, ss, sa, sp, W1p, W2tp, bp, rank, 0.5, mode, ws)
+            torch.cuda.synchronize()
+            outs.append((yy, hh))
+        (ya, ha), (yb, hb) = outs
+        assert torch.equal(bits(ya[idx]), bits(yb)), "LoRA rows changed with the order of the segments"
+        assert torch.equal(bits(ha[idx]), bits(hb)), "DiReFT rows changed with the order of the segments"
+        assert not torch.equal(bits(ya), bits(y0))
+
