@@ -833,3 +833,30 @@ def test_segment_permutation_moves_the_rows_and_nothing_else(dtype, rank, d):
         assert torch.equal(bits(ha[idx]), bits(hb)), "DiReFT rows changed with the order of the segments"
         assert not torch.equal(bits(ya), bits(y0))
 
+
+@pytest.mark.parametrize("rank,d,same_bits", [(16, 1024, True), (8, 4096, True), (2, 520, True), (32, 512, False), (64, 256, False)])
+def test_direft_without_bias_is_the_lora_entry_on_a_copy_of_the_stream(rank, d, same_bits):
+    """Eq. 3 with b = 0 is Eq. 2 with A = W1, B = W2, x = h and y0 = h: the in-place entry and the
+    out-of-place entry must agree -- bit for bit where both take the same kernel family (one rounding
+    of the same fp32 sums), within two roundings of the output type elsewhere."""
+    from parity_util import bits, dev_tables, direft_pools_to_device
+    N = 4
+    tab = _mixed_table(rank + d, N, max_len=150)
+    dpool = wl.direft_pool(N, rank, d, "bf16", device="cuda", seed=12)
+    W1p, W2tp, _, keep = direft_pools_to_device(dpool, bias=False)
+    h0 = wl.activations(tab.T, d, "bf16", device="cuda", seed=13)
+    ss, sa, sp = dev_tables(tab)
+    ws = preft.new_workspace(tab.T, tab.S)
+    for mode in (preft.PREFT_PREFILL_ONLY, preft.PREFT_ALL_TOKENS):
+        h, y = h0.clone(), h0.clone()
+        preft.preft_direft_apply(h, ss, sa, sp, W1p, W2tp, None, rank, 0.75, mode, ws)
+        preft.preft_lora_apply(y, h0, ss, sa, sp, W1p, W2tp, rank, 0.75, mode, ws)
+        torch.cuda.synchronize()
+        if same_bits:
+            assert torch.equal(bits(h), bits(y))
+        else:
+            err = (h.float() - y.float()).abs().amax(dim=1)
+            ref = y.float().abs().amax(dim=1).clamp_min(1e-6)
+            assert float((err / ref).max()) <= 2.0 ** -7
+        assert not torch.equal(bits(h), bits(h0))
+
