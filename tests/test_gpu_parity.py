@@ -860,3 +860,29 @@ def test_direft_without_bias_is_the_lora_entry_on_a_copy_of_the_stream(rank, d, 
             assert float((err / ref).max()) <= 2.0 ** -7
         assert not torch.equal(bits(h), bits(h0))
 
+
+@pytest.mark.parametrize("dtype,rank,d", [("bf16", 16, 512), ("bf16", 3, 264), ("bf16", 32, 256), ("f32", 5, 68)])
+def test_all_positions_is_prompt_only_with_every_row_a_prompt_row(dtype, rank, d):
+    """Sec. 3.2: the all-position set is the prompt set of a sequence whose prompt is the whole
+    sequence.  Same schedule, same launches, same bits."""
+    from parity_util import bits, dev_tables, lora_pools_to_device
+    N = 4
+    tab = _mixed_table(rank * 3 + d, N, max_len=180)
+    full = wl.SegmentTable(tab.seg_start, tab.seg_adapter, tab.seg_len.astype(np.int32))
+    pool = wl.lora_pool(N, rank, d, d, dtype, device="cuda", seed=21)
+    Ap, Bp, keep = lora_pools_to_device(pool)
+    x = wl.activations(tab.T, d, dtype, device="cuda", seed=22)
+    y0 = wl.activations(tab.T, d, dtype, device="cuda", seed=23)
+    outs, counts = [], []
+    for t, mode in ((tab, preft.PREFT_ALL_TOKENS), (full, preft.PREFT_PREFILL_ONLY)):
+        ss, sa, sp = dev_tables(t)
+        ws = preft.new_workspace(t.T, t.S)
+        y = y0.clone()
+        preft.preft_lora_apply(y, x, ss, sa, sp, Ap, Bp, rank, 2.0, mode, ws)
+        torch.cuda.synchronize()
+        outs.append(y)
+        counts.append(preft.preft_schedule_counts(ws))
+    assert counts[0] == counts[1]
+    assert torch.equal(bits(outs[0]), bits(outs[1]))
+    assert not torch.equal(bits(outs[0]), bits(y0))
+
