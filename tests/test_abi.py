@@ -170,3 +170,37 @@ def test_packed_and_loreft_arguments_are_rejected_before_any_launch(lib):
     assert prepare(W=0x7f0000600008) == -3
     assert prepare(D=0x7f0000600000) == -1                                # D on top of W
     assert prepare(Rt=0x7f0000400100) == -1                               # Rt inside D
+
+
+def test_header_is_plain_c_and_the_documented_call_sequence_compiles(tmp_path):
+    """include/preft.h must be usable from C (no C++ in the boundary); the calling sequence shown
+    in the README is compiled against it with warnings as errors (never run: no GPU here)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("needs gcc")
+    src = tmp_path / "use.c"
+    src.write_text('''
+#include "preft.h"
+int step(void *y, void *x, void *h, void *ws, const int32_t *seg_start, const int32_t *seg_adapter,
+         const int32_t *seg_prefill_len, const void *const *A_pool, const void *const *B_pool,
+         const void *const *W1_pool, const void *const *W2t_pool, const void *const *b_pool, void *stream)
+{
+    const int32_t T = 1000, S = 10, N = 4, d_in = 512, d_out = 256, d = 512, rank = 16;
+    const int64_t ldx = 512, ldy = 256, ldh = 512;
+    size_t ws_bytes = preft_workspace_bytes(T, S);
+    int rc = preft_schedule(ws, ws_bytes, seg_start, seg_adapter, seg_prefill_len, S, T, N, PREFT_PREFILL_ONLY, stream);
+    int ready = PREFT_PREFILL_ONLY | PREFT_SCHEDULE_READY;
+    if (rc == PREFT_OK)
+        rc = preft_lora_apply(y, ldy, x, ldx, T, d_in, d_out, seg_start, seg_adapter, seg_prefill_len, S,
+                              A_pool, B_pool, N, rank, 2.0f, PREFT_BF16, ready, ws, ws_bytes, stream);
+    if (rc == PREFT_OK)
+        rc = preft_direft_apply(h, ldh, T, d, seg_start, seg_adapter, seg_prefill_len, S,
+                                W1_pool, W2t_pool, b_pool, N, rank, 1.0f, PREFT_BF16, ready, ws, ws_bytes, stream);
+    return rc;
+}
+''')
+    for std in ("c99", "c11"):
+        r = subprocess.run(["gcc", f"-std={std}", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
+                            "-I", os.path.join(ROOT, "include"), str(src)], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
