@@ -122,7 +122,10 @@ int preft_schedule(void *workspace, size_t workspace_bytes,
  *
  * y  [T, d_out]  in/out, row stride ldy elements.   x  [T, d_in]  in, row stride ldx.
  * x and y must not overlap.  d_in, d_out, ldx, ldy must be multiples of 16 bytes worth of
- * elements (8 for bf16, 4 for fp32) and x, y 16-byte aligned, else PREFT_EALIGN.
+ * elements (8 for bf16, 4 for fp32) and x, y 16-byte aligned, else PREFT_EALIGN.  That is the
+ * rule for correctness; for full speed rows should start on 128-byte boundaries (bases 128-byte
+ * aligned, ldx and ldy multiples of 64 bf16 elements): the kernels move rows in 256-byte pieces,
+ * and rows that start 16 bytes off a line cost about a fifth of the bandwidth.
  * rank in 1..PREFT_MAX_RANK.  scale is the paper's alpha (or alpha/r), already evaluated.
  * Unless mode carries PREFT_SCHEDULE_READY the call first runs the scheduler into
  * `workspace` (>= preft_workspace_bytes(T, S) bytes).
