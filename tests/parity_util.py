@@ -100,15 +100,17 @@ def direft_pools_to_device(pool: wl.DireftPool, perm=None, bias=True):
 
 
 def run_lora_case(tab: wl.SegmentTable, pool: wl.LoraPool, x: torch.Tensor, y0: torch.Tensor, dtype: str,
-                  scale: float, all_tokens: bool, pad_cols=0, rows=None, perm=None, reuse_schedule=False):
-    """Tensors live on the GPU; returns (worst error, schedule counts)."""
+                  scale: float, all_tokens: bool, pad_cols=0, rows=None, perm=None, reuse_schedule=False,
+                  pad_x=None, pad_y=None):
+    """Tensors live on the GPU; returns (worst error, schedule counts).  pad_cols (or pad_x / pad_y for
+    x and y separately): guard columns that widen the row pitch and must come back untouched."""
     N, r = pool.N, pool.r
     T = tab.T
     mode = preft.PREFT_ALL_TOKENS if all_tokens else preft.PREFT_PREFILL_ONLY
     ss, sa, sp = dev_tables(tab)
     Ap, Bp, keep = lora_pools_to_device(pool, perm)
-    ybuf, y = padded(y0, pad_cols, 7.0)
-    xbuf, xv = padded(x, pad_cols, -3.0)
+    ybuf, y = padded(y0, pad_cols if pad_y is None else pad_y, 7.0)
+    xbuf, xv = padded(x, pad_cols if pad_x is None else pad_x, -3.0)
     ws = preft.new_workspace(T, tab.S)
     if reuse_schedule:
         preft.preft_schedule(ws, ss, sa, sp, T, N, mode)

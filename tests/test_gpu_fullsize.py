@@ -24,19 +24,29 @@ def _reset(request):
     torch.cuda.empty_cache()
 
 
+# rows start every next-power-of-two elements (the layout bench.py times) unless the case says "dense"
 LORA = [
     ("llama8b_lora", "q", 16, False), ("llama8b_lora", "q", 16, True), ("llama8b_lora", "down", 8, False),
     ("llama8b_lora", "k", 1, False), ("llama8b_lora", "gate", 16, False),
     ("llama70b_lora", "q", 64, False), ("llama70b_lora", "q", 64, True), ("llama70b_lora", "gate", 16, False),
     ("llama70b_lora", "down", 1, False), ("llama70b_lora", "k", 16, True),
     ("skewed70b", "res", 32, False), ("skewed70b", "res", 32, True),
+    ("llama8b_lora", "gate", 16, False, "dense"), ("llama8b_lora", "down", 16, False, "dense"),
+    ("llama70b_lora", "down", 64, False, "dense"),
 ]
 
 
-@pytest.mark.parametrize("config,proj,rank,all_tokens", LORA,
-                         ids=[f"{c}-{p}-r{r}-{'all' if a else 'prefill'}" for c, p, r, a in LORA])
-def test_fullsize_lora(config, proj, rank, all_tokens):
+def _pow2_pad(width):
+    """Guard columns that bring a row to the next power of two: the row pitch bench.py uses by default."""
+    return (1 << (width - 1).bit_length()) - width
+
+
+@pytest.mark.parametrize("case", LORA, ids=["-".join([c[0], c[1], f"r{c[2]}", "all" if c[3] else "prefill", *c[4:]])
+                                            for c in LORA])
+def test_fullsize_lora(case):
     from parity_util import run_lora_case
+    config, proj, rank, all_tokens = case[:4]
+    dense = len(case) > 4
     cfg = wl.CONFIGS[config]
     d_in, d_out = cfg["lora_shapes"][proj]
     tab = wl.make_segments(config, seed=0)
@@ -44,7 +54,8 @@ def test_fullsize_lora(config, proj, rank, all_tokens):
     x = wl.activations(tab.T, d_in, "bf16", device="cuda", seed=51)
     y0 = wl.activations(tab.T, d_out, "bf16", device="cuda", seed=52)
     rows = wl.sample_rows(tab, 2, max_rows=1200)
-    worst, counts = run_lora_case(tab, pool, x, y0, "bf16", cfg["lora_scale"], all_tokens, rows=rows)
+    worst, counts = run_lora_case(tab, pool, x, y0, "bf16", cfg["lora_scale"], all_tokens, rows=rows,
+                                  pad_x=0 if dense else _pow2_pad(d_in), pad_y=0 if dense else _pow2_pad(d_out))
     print(f"  T={tab.T} S={tab.S} rows checked={len(rows)} worst {worst:.2e} counts {counts}")
 
 
@@ -86,8 +97,10 @@ def test_fullsize_packed_lora(config, projs, rank, all_tokens):
     tab = wl.make_segments(config, seed=0)
     x = wl.activations(tab.T, d_in, "bf16", device="cuda", seed=71)
     pools = [wl.lora_pool(N, rank, d_in, n, "bf16", device="cuda", seed=72 + i) for i, (_, n) in enumerate(shapes)]
+    from parity_util import check_guards, padded
     y0s = [wl.activations(tab.T, n, "bf16", device="cuda", seed=80 + i) for i, (_, n) in enumerate(shapes)]
-    ys = [y.clone() for y in y0s]
+    bufs = [padded(y, _pow2_pad(y.shape[1]), 7.0) for y in y0s]       # rows every next power of two, as bench.py lays them out
+    ys = [b[1] for b in bufs]
     tables = [lora_pools_to_device(pl) for pl in pools]
     ss, sa, sp = dev_tables(tab)
     ws = preft.new_workspace(tab.T, tab.S)
@@ -108,6 +121,7 @@ def test_fullsize_packed_lora(config, projs, rank, all_tokens):
         want = ora.lora(y0s[i][idx].cpu(), x_rows, tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, A, B, rank,
                         cfg["lora_scale"], pos, rows=rows, gathered=True)
         worst = max(worst, compare(ys[i], y0s[i], want, owner, "bf16", rows=rows))
+        check_guards(bufs[i][0], tab.T, y0s[i].shape[1], 7.0)
     print(f"  T={tab.T} S={tab.S} rows checked={len(rows)} outputs={len(projs)} worst {worst:.2e}")
 
 
