@@ -259,6 +259,18 @@ void launch_mfma_rank(const ApplyArgs &a, int64_t S, hipStream_t stream)
 template <int RANK, bool DIREFT>
 void launch_valu(const ApplyArgs &a, int64_t S, hipStream_t stream)
 {
+    // in place, rows of at most 4096 elements: 2 rows per wavefront stay in registers between the
+    // sweeps, so h is read once (d = 4096: 56-59 -> 62-72 % of peak at rank 1-3).  Wider rows
+    // would leave one row per wavefront, and the factors re-read for every row cost more than the
+    // second read of h (d = 8192, rank 3: 42 % against 60 %).
+    if constexpr (DIREFT) {
+        if (g_waves == 0 && g_rowblocks == 0 && a.d_in <= 4096) {
+            void (*resident)(ApplyArgs) = valu_tile_kernel<RANK, 2, 4, true, 1, 8>;
+            if (a.h_layers) resident = valu_tile_layers_kernel<RANK, 2, 4, 8>;
+            hipLaunchKernelGGL(resident, dim3(tile_grid(a, S, 8), a.n_layers), dim3(256), 0, stream, a);
+            return;
+        }
+    }
     constexpr int RB = RANK <= 4 ? 4 : 2;
     int waves = g_waves ? g_waves : 4;
     void (*kernel)(ApplyArgs);

@@ -15,6 +15,9 @@
 // A workgroup of WAVES wavefronts owns a tile of RB * WAVES consecutive rows of a chunk;
 // wavefronts never exchange data.
 //
+// HV > 0 (in place only): the wavefront's rows stay in registers between the sweeps, HV 16-byte
+// vectors per lane and row, so rows of up to 512 HV elements are read once and written once.
+//
 // SLICES > 1 (LoRA only): packed projections, as in mfma_tile_kernel: the outputs share x, so
 // one shrink sweep feeds SLICES * RANK partial sums per row and one expand sweep per output follows.
 #pragma once
@@ -31,10 +34,11 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc)
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), acc, false);
 }
 
-template <int RANK, int RB, int WAVES, bool DIREFT, int SLICES = 1>
+template <int RANK, int RB, int WAVES, bool DIREFT, int SLICES = 1, int HV = 0>
 __device__ __forceinline__ void valu_tile_body(const ApplyArgs &p)
 {
     constexpr int R = RB * WAVES;
+    static_assert(HV == 0 || DIREFT, "only an in-place call keeps its rows between the sweeps");
     constexpr int RT = RANK * SLICES;                         // partial sums per row in the shrink sweep
     static_assert(SLICES == 1 || !DIREFT, "packed projections are a LoRA feature");
     static_assert(CHUNK_ROWS % R == 0, "tile height must divide the chunk height");
@@ -85,7 +89,28 @@ __device__ __forceinline__ void valu_tile_body(const ApplyArgs &p)
                 for (int q = 0; q < 4; ++q)
                     z[i][k] = dot2_bf16(xv[i][q], av[k][q], z[i][k]);
     };
+    // HV > 0 (in place, rows of at most 512 HV elements): the wavefront keeps its RB rows in
+    // registers between the sweeps -- lane l holds the 16-byte vectors l, l + 64, ... of each row --
+    // so h is read once and written once.
+    u32x4_t hreg[RB][HV > 0 ? HV : 1];
     int c = lane;
+    if constexpr (HV > 0) {
+#pragma unroll
+        for (int v = 0; v < HV; ++v) {
+            const int cv = lane + 64 * v;
+            if (cv < nvec_in) {
+                u32x4_t xv[RB], av[RT];
+#pragma unroll
+                for (int i = 0; i < RB; ++i) xv[i] = ld16_stream(xp[i] + (int64_t)cv * 16);
+#pragma unroll
+                for (int k = 0; k < RT; ++k) av[k] = ld16(A[k / RANK] + ((int64_t)(k % RANK) * p.d_in + (int64_t)cv * 8) * 2);
+                shrink_step(xv, av);
+#pragma unroll
+                for (int i = 0; i < RB; ++i) hreg[i][v] = xv[i];
+            }
+        }
+        c = nvec_in;                                          // nothing left for the streamed loops
+    }
     for (; c + 64 < nvec_in; c += 128) {                      // two sweeps in flight
         u32x4_t xv0[RB], xv1[RB], av0[RT], av1[RT];
 #pragma unroll
@@ -126,6 +151,39 @@ __device__ __forceinline__ void valu_tile_body(const ApplyArgs &p)
 #pragma unroll
         for (int i = 0; i < RB; ++i) yp[i] = as_global(slice_y<SL>(p)) + rows[i] * ldy_b;
         const int nvec_out = slice_d_out<SL>(p) >> 3;
+        if constexpr (HV > 0) {
+#pragma unroll
+            for (int v = 0; v < HV; ++v) {
+                const int c = lane + 64 * v;
+                if (c < nvec_out) {
+                    float w[8 * RANK];
+                    gcptr_t wp = Bt + (int64_t)c * 8 * RANK * 2;
+#pragma unroll
+                    for (int j = 0; j < RANK; ++j) {
+                        const u32x4_t raw = ld16(wp + j * 16);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            w[j * 8 + 2 * q] = bf16_lo(raw[q]);
+                            w[j * 8 + 2 * q + 1] = bf16_hi(raw[q]);
+                        }
+                    }
+#pragma unroll
+                    for (int i = 0; i < RB; ++i) {
+                        float out[8];
+                        Elem<bf16_tag>::unpack(hreg[i][v], out);
+#pragma unroll
+                        for (int col = 0; col < 8; ++col) {
+                            float d = 0.f;
+#pragma unroll
+                            for (int k = 0; k < RANK; ++k) d = fmaf(w[col * RANK + k], z[i][SL * RANK + k], d);
+                            out[col] += d;
+                        }
+                        st16_stream(yp[i] + (int64_t)c * 16, Elem<bf16_tag>::pack(out));
+                    }
+                }
+            }
+            return;
+        }
         for (int c = lane; c < nvec_out; c += 64) {
             // 8 columns x RANK factors, contiguous: RANK 16-byte vectors
             float w[8 * RANK];
@@ -162,18 +220,18 @@ __device__ __forceinline__ void valu_tile_body(const ApplyArgs &p)
     if constexpr (SLICES > 2) expand_slice(std::integral_constant<int, 2>{});
 }
 
-template <int RANK, int RB, int WAVES, bool DIREFT, int SLICES = 1>
+template <int RANK, int RB, int WAVES, bool DIREFT, int SLICES = 1, int HV = 0>
 __global__ __launch_bounds__(WAVES * 64) void valu_tile_kernel(ApplyArgs p)
 {
-    valu_tile_body<RANK, RB, WAVES, DIREFT, SLICES>(p);
+    valu_tile_body<RANK, RB, WAVES, DIREFT, SLICES, HV>(p);
 }
 
 // the same for one of several residual streams (in-place calls): blockIdx.y is the layer
-template <int RANK, int RB, int WAVES>
+template <int RANK, int RB, int WAVES, int HV = 0>
 __global__ __launch_bounds__(WAVES * 64) void valu_tile_layers_kernel(ApplyArgs p)
 {
     select_layer(p);
-    valu_tile_body<RANK, RB, WAVES, true, 1>(p);
+    valu_tile_body<RANK, RB, WAVES, true, 1, HV>(p);
 }
 
 }  // namespace preft

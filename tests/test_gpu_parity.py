@@ -119,6 +119,10 @@ DIREFT_CASES = [
     (VARIANT_MFMA, 64, 4104, 0, 0), (VARIANT_MFMA, 16, 8200, 0, 0), (VARIANT_MFMA, 64, 8192, 0, 0),
     (VARIANT_MFMA, 128, 1024, 0, 0), (VARIANT_MFMA, 32, 16384, 0, 0),
     (VARIANT_WIDE, 32, 2048, 4, 2), (VARIANT_WIDE, 64, 1024, 8, 1), (VARIANT_WIDE, 20, 512, 4, 1), (VARIANT_WIDE, 128, 256, 4, 2),
+    # vector-ALU kernel with its rows held in registers (automatic shape up to 4096 columns): full
+    # and ragged vector counts per lane; one column group past the limit takes the streamed shape
+    (VARIANT_AUTO, 2, 4096, 0, 0), (VARIANT_AUTO, 3, 264, 0, 0), (VARIANT_AUTO, 6, 2056, 0, 0), (VARIANT_AUTO, 7, 8, 0, 0),
+    (VARIANT_AUTO, 1, 4088, 0, 0), (VARIANT_AUTO, 5, 4104, 0, 0), (VARIANT_VALU, 3, 4096, 4, 0),
 ]
 
 
