@@ -10,10 +10,12 @@
 // want: measured on this chip, 64-byte row pieces stream at ~4.8 TB/s at best, 256-byte
 // pieces at ~5.4 TB/s.  The matrix cores want the opposite order (lane l: row l%16), so a
 // unit is turned through a wavefront-private LDS buffer (4 x ds_write_b128, 4 x
-// ds_read_b128 per 16 rows x 128 columns, padded rows, no bank conflicts, no barrier:
-// the LDS executes one wavefront's operations in order).  The adapter factors come from
-// L2; they are loaded in 64-byte row pieces (4 neighbouring lanes per piece) and turned
-// with ds_bpermute.
+// ds_read_b128 per 16 rows x 128 columns, rows padded by 16 bytes, no barrier: the LDS
+// executes one wavefront's operations in order).  The adapter factors come from L2: the
+// shrink loads a rank block of the [r, d_in] factor like a unit of activations (4 ranks x
+// 256 bytes per instruction, turned through a second LDS buffer); the expand reads its
+// operand of the [d_out, r] factor directly, 8 bytes (4 ranks of one column) per lane.
+// Only the single 32-column steps of odd widths use 64-byte row pieces and ds_bpermute.
 //
 // Compute side.
 //   shrink (Eq. 2: z = A x;  Eq. 3: z = A h + b), per 32 columns of the row:
@@ -36,8 +38,9 @@
 // h tile in registers between the two sweeps: h is read from HBM once and written once.
 //
 // Both sweeps are software-pipelined by hand: the loads of unit u+1 are issued before the
-// MFMAs of unit u.  Widths that are not a multiple of 128 finish with up to four single
-// 32-column steps (64-byte row pieces, ds_bpermute).
+// MFMAs of unit u, and the streamed shapes with one rank block request the first unit of the
+// expand before the cross-wavefront sum of z.  Widths that are not a multiple of 128 finish
+// with up to four single 32-column steps (64-byte row pieces, ds_bpermute).
 #pragma once
 #include "common.hpp"
 
