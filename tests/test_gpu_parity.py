@@ -890,3 +890,46 @@ def test_all_positions_is_prompt_only_with_every_row_a_prompt_row(dtype, rank, d
     assert torch.equal(bits(outs[0]), bits(outs[1]))
     assert not torch.equal(bits(outs[0]), bits(y0))
 
+
+@pytest.mark.parametrize("seed", [11, 12])
+def test_randomised_shapes_ranks_pitches_and_modes(seed):
+    """A seeded sweep over valid inputs: every rank class, widths with and without tails, row
+    pitches with padding, both dtypes and modes, the small-batch shape forced on and off, one-layer
+    and many-layer in-place calls -- each case against the oracle with the guards checked."""
+    from parity_util import run_direft_case, run_direft_layers_case, run_lora_case
+    rng = np.random.Generator(np.random.PCG64(seed))
+    ranks = [1, 2, 3, 4, 5, 6, 7, 8, 9, 12, 16, 20, 24, 28, 32, 40, 48, 64, 96, 128]
+    widths = [8, 16, 24, 64, 72, 128, 136, 256, 264, 384, 512, 520, 640, 1000, 1024, 1032, 2048, 4096, 4104]
+    done = 0
+    for case in range(150):
+        dtype = "bf16" if rng.random() < 0.8 else "f32"
+        r = int(rng.choice(ranks))
+        d_in, d_out = int(rng.choice(widths)), int(rng.choice(widths))
+        if dtype == "f32":
+            d_in, d_out, r = min(d_in, 520), min(d_out, 520), min(r, 24)
+        N = int(rng.integers(1, 9))
+        tab = wl.random_segments(rng, int(rng.integers(1, 60)), N + 1, int(rng.integers(1, 300)))
+        if tab.T == 0 or tab.T * max(d_in, d_out) * r > 4e9:
+            continue
+        all_tokens = bool(rng.integers(0, 2))
+        pad = int(rng.choice([0, 8, 64, 1024]))
+        scale = float(rng.choice([1.0, 0.5, 2.0, 0.37]))
+        print(f"  case {case}: {dtype} r={r} {d_in}->{d_out} N={N} S={tab.S} T={tab.T} all={all_tokens} pad={pad}", flush=True)
+        _set()
+        preft.preft_set_knob(preft.PREFT_KNOB_COLSPLIT, int(rng.integers(1, 9)) if rng.random() < 0.3 else 0)
+        pool = wl.lora_pool(N, r, d_in, d_out, dtype, device="cuda", seed=case)
+        x = wl.activations(tab.T, d_in, dtype, device="cuda", seed=case + 1)
+        y0 = wl.activations(tab.T, d_out, dtype, device="cuda", seed=case + 2)
+        run_lora_case(tab, pool, x, y0, dtype, scale, all_tokens, pad_cols=pad, reuse_schedule=bool(rng.integers(0, 2)))
+        dp = wl.direft_pool(N, r, d_in, dtype, device="cuda", seed=case + 3)
+        run_direft_case(tab, dp, x, dtype, scale, all_tokens, pad_cols=pad, bias=bool(rng.integers(0, 2)))
+        if rng.random() < 0.3:
+            L = int(rng.integers(1, 4))
+            pools = [wl.direft_pool(N, r, d_in, dtype, device="cuda", seed=case + 10 + l) for l in range(L)]
+            hs = [wl.activations(tab.T, d_in, dtype, device="cuda", seed=case + 20 + l) for l in range(L)]
+            run_direft_layers_case(tab, pools, hs, dtype, scale, all_tokens,
+                                   [bool(rng.integers(0, 2)) for _ in range(L)], pad_cols=pad)
+        done += 1
+    preft.preft_set_knob(preft.PREFT_KNOB_COLSPLIT, 0)
+    assert done > 100
+
