@@ -80,10 +80,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     preft.load_library()
-    preft.preft_set_knob(preft.PREFT_KNOB_VARIANT, args.variant)
-    preft.preft_set_knob(preft.PREFT_KNOB_WAVES, args.waves)
-    preft.preft_set_knob(preft.PREFT_KNOB_ROWBLOCKS, args.rowblocks)
-    preft.preft_set_knob(preft.PREFT_KNOB_COLSPLIT, args.colsplit)
+    preft.set_test_flags(preft.test_flags(variant=args.variant, waves=args.waves, rowblocks=args.rowblocks,
+                                          colsplit=args.colsplit))
     dev = "cuda:0"
     torch.cuda.set_device(0)
 

@@ -25,8 +25,10 @@
  *                       segment of length 1 with prefill length 0; a prompt chunk has
  *                       prefill length == length.  Ignored in PREFT_ALL_TOKENS mode.
  * The tables are read on the device only; their contents are not validated on the host
- * (that would need a synchronisation).  Rows are clamped to [0,T) on the device, so a
- * malformed table cannot cause an out-of-range access, but its result is unspecified.
+ * (that would need a synchronisation).  Every segment is clamped to [0,T) on the device and
+ * every list of the schedule is cut back to its capacity, so a malformed table (offsets that
+ * decrease, segments that overlap) cannot cause an out-of-range access; its result is
+ * unspecified (a row named by two segments may be updated twice).
  *
  * Adapter pools: device arrays of N device pointers, one matrix per adapter, all of one
  * rank, row-major, in the activation dtype:
@@ -34,14 +36,15 @@
  *   B_pool[i]   [d_out, rank]  the paper's B as printed in Eq. 2
  *   W1_pool[i]  [rank, d]      the paper's A of Eq. 3
  *   W2t_pool[i] [d, rank]      the TRANSPOSE of the paper's B of Eq. 3 (rank contiguous)
- *   b_pool[i]   [rank]         the paper's b of Eq. 3; b_pool == NULL means b = 0
+ *   b_pool[i]   [rank]         the paper's b of Eq. 3; b_pool == NULL, or an entry
+ *                              b_pool[i] == NULL, means b = 0 (for that adapter)
  * Every matrix must be 16-byte aligned.  Pool slots are caller-owned and may be overwritten
  * in place between calls.  Only the slots named by active segments are dereferenced.
  *
  * Ownership / execution: every pointer is caller-owned device memory unless marked
- * "host".  The schedule and apply calls allocate nothing and keep no state between calls
- * (apart from the benchmarking knobs of preft_set_knob); only the optional slot manager at the
- * end of this header owns memory.  Calls only
+ * "host".  The schedule and apply calls allocate nothing and the library keeps no state
+ * between calls: whatever selects a kernel travels in the arguments of the call.  Only the
+ * optional slot manager at the end of this header owns memory.  Calls only
  * enqueue work on `stream` (a hipStream_t passed as void*, NULL = the default stream) and
  * return; they never synchronise.  All launch shapes depend on host-visible sizes only,
  * so a call may be captured into a HIP graph.
@@ -70,6 +73,35 @@ enum {
     PREFT_SCHEDULE_READY = 0x100   /* workspace already holds this batch's schedule      */
 };
 
+/*
+ * Test-only kernel selection, OR-ed into `mode` (bits 16..30).  A serving call leaves these
+ * bits zero and gets the library's own choice; tests and benchmarks use them to reach every
+ * kernel family on any input.  They change which kernel runs, never what is computed.  A value
+ * a kernel family does not offer selects its nearest shape; an undefined value is PREFT_EINVAL.
+ *   PREFT_TEST_VARIANT(v)    0 = automatic
+ *                            1 = per-row kernel everywhere
+ *                            2 = vector-ALU tile kernel where it applies (bf16, rank <= 8)
+ *                            3 = MFMA tile kernel, column-split shape (bf16, rank % 4 == 0)
+ *                            4 = MFMA tile kernel, row-split shape with the factors shared
+ *                                through LDS where it applies (widths multiples of 128), and
+ *                                no register-resident DiReFT
+ *   PREFT_TEST_WAVES(w)      wavefronts per tile workgroup: 0 = automatic, else 1, 2, 4 or 8
+ *                            (any non-zero value also makes DiReFT stream its tile instead
+ *                            of holding it in registers)
+ *   PREFT_TEST_ROWBLOCKS(b)  MFMA kernels: 16-row blocks per wavefront: 0 = automatic, 1 or 2
+ *   PREFT_TEST_COLSPLIT(c)   LoRA, MFMA column-split kernel: workgroups that share a tile, each
+ *                            writing its share of the output columns: 0 = automatic (4 for
+ *                            batches of up to 1024 rows, else 1), or 1..15
+ *   PREFT_TEST_RESIDENT(n)   in-place MFMA kernels: how much of a tile stays in registers between
+ *                            the two sweeps: 0 = automatic, 1 = nothing, 2 = all of it where a
+ *                            shape exists, 3 = half of a 32-row tile
+ */
+#define PREFT_TEST_VARIANT(v)   (((v) & 7) << 16)
+#define PREFT_TEST_WAVES(w)     (((w) & 15) << 19)
+#define PREFT_TEST_ROWBLOCKS(b) (((b) & 3) << 23)
+#define PREFT_TEST_COLSPLIT(c)  (((c) & 15) << 25)
+#define PREFT_TEST_RESIDENT(n)  (((n) & 3) << 29)
+
 /* dtype of activations AND adapter weights */
 enum { PREFT_F32 = 0, PREFT_BF16 = 1 };
 
@@ -81,7 +113,9 @@ enum {
                                /* width that is not a multiple of 16 bytes               */
     PREFT_EWORKSPACE   = -4,   /* workspace missing, misaligned or too small             */
     PREFT_EHIP         = -5,   /* the HIP runtime refused a launch, copy or allocation   */
-    PREFT_ECAPACITY    = -6    /* slot manager: more distinct adapters than slots        */
+    PREFT_ECAPACITY    = -6,   /* slot manager: more distinct adapters than slots        */
+    PREFT_ESCHEDULE    = -7    /* preft_schedule_counts: an apply call found a schedule  */
+                               /* built for another T, S, N or position set, and did nothing */
 };
 
 #define PREFT_MAX_RANK 128
@@ -106,8 +140,11 @@ size_t preft_workspace_bytes(int32_t T, int32_t S);
  * The schedule depends on (tables, S, T, N, position set) only -- not on dtype, rank or
  * widths -- so one schedule serves every projection and layer of an engine step: pass the
  * same workspace with mode | PREFT_SCHEDULE_READY to the apply calls that follow on the
- * same stream, with the same T, S, N and position set (the launch sizes of an apply call are
- * bounds computed from T, S and N; with other values part of the batch would be skipped).
+ * same stream, with the same T, S, N and position set.  The schedule records those four values
+ * and every apply kernel compares them with its own arguments first: a call that names another
+ * batch shape or position set does nothing at all (its launch sizes are bounds computed from
+ * T, S and N, so it could only process part of the batch, or the wrong rows) and marks the
+ * workspace, which preft_schedule_counts reports as PREFT_ESCHEDULE.
  *
  * mode: PREFT_PREFILL_ONLY or PREFT_ALL_TOKENS.
  */
@@ -176,7 +213,8 @@ int preft_lora_apply_packed(int32_t n_proj, void *const *y, const int64_t *ldy, 
  * bias term too.
  *
  * h [T, d] in/out, row stride ldh elements; alignment rules as for preft_lora_apply.
- * b_pool may be NULL (no bias); if not NULL every active slot must be a valid pointer.
+ * b_pool may be NULL (no bias for any adapter), and so may single entries of it (Eq. 3 with
+ * b = 0 for that adapter); every other entry named by an active segment must be a valid pointer.
  */
 int preft_direft_apply(void *h, int64_t ldh, int32_t T, int32_t d,
                        const int32_t *seg_start, const int32_t *seg_adapter,
@@ -293,32 +331,12 @@ int preft_slots_stats(const preft_slots_t *m, int64_t *stats);
  * Copies the schedule counters of a workspace to the host: counts[0] = multi-row work
  * units (chunks of up to 128 rows of one segment), counts[1] = rows of short segments (at most
  * 4 active rows, e.g. decode tokens), which run as gathered tiles, counts[2] = active rows.
- * `counts` is a host pointer to 3 int32.  This call synchronises `stream`; it is meant
- * for tests, statistics and debugging, never for the serving loop.
+ * `counts` is a host pointer to 3 int32.  Returns PREFT_ESCHEDULE (with the counts filled in) if,
+ * since the schedule was written, an apply call with PREFT_SCHEDULE_READY named another T, S, N
+ * or position set than the schedule's and therefore did nothing.  This call synchronises
+ * `stream`; it is meant for tests, statistics and debugging, never for the serving loop.
  */
 int preft_schedule_counts(const void *workspace, int32_t *counts, void *stream);
-
-/*
- * Tuning knobs for benchmarking and tests (process-wide, not thread-safe; the defaults
- * are what a serving loop should use).  Returns the previous value or PREFT_EINVAL.
- *   PREFT_KNOB_VARIANT   0 = automatic choice (default)
- *                        1 = per-row kernel everywhere
- *                        2 = vector-ALU tile kernel where it applies (bf16, rank <= 8)
- *                        3 = MFMA tile kernel, column-split shape (bf16, rank % 4 == 0)
- *                        4 = MFMA tile kernel, row-split shape with the factors shared through
- *                            LDS where it applies (rank > 16, widths multiples of 128),
- *                            and no register-resident DiReFT
- *   PREFT_KNOB_WAVES     wavefronts per tile workgroup: 0 = automatic, else 1, 2, 4 or 8
- *                        (a value a kernel does not offer selects its nearest shape; any
- *                        non-zero value also makes DiReFT stream its tile instead of
- *                        holding it in registers)
- *   PREFT_KNOB_ROWBLOCKS MFMA kernel: 16-row blocks per tile: 0 = automatic, 1 or 2
- *   PREFT_KNOB_COLSPLIT  LoRA, MFMA column-split kernel: workgroups that share a tile, each
- *                        writing its share of the output columns: 0 = automatic (4 for batches of
- *                        up to 1024 rows, else 1), or 1..16
- */
-enum { PREFT_KNOB_VARIANT = 0, PREFT_KNOB_WAVES = 1, PREFT_KNOB_ROWBLOCKS = 2, PREFT_KNOB_COLSPLIT = 3 };
-int preft_set_knob(int knob, int value);
 
 /* Static, NUL-terminated description of a return code (host pointer, never freed). */
 const char *preft_strerror(int code);

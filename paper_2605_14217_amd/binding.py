@@ -20,17 +20,57 @@ PREFT_SCHEDULE_READY = 0x100
 PREFT_F32 = 0
 PREFT_BF16 = 1
 PREFT_ECAPACITY = -6
-PREFT_KNOB_VARIANT = 0
-PREFT_KNOB_WAVES = 1
-PREFT_KNOB_ROWBLOCKS = 2
-PREFT_KNOB_COLSPLIT = 3
+PREFT_ESCHEDULE = -7
+
+
+def PREFT_TEST_VARIANT(v: int) -> int:
+    return (int(v) & 7) << 16
+
+
+def PREFT_TEST_WAVES(w: int) -> int:
+    return (int(w) & 15) << 19
+
+
+def PREFT_TEST_ROWBLOCKS(b: int) -> int:
+    return (int(b) & 3) << 23
+
+
+def PREFT_TEST_COLSPLIT(c: int) -> int:
+    return (int(c) & 15) << 25
+
+
+def PREFT_TEST_RESIDENT(n: int) -> int:
+    return (int(n) & 3) << 29
+
+
+def test_flags(variant: int = 0, waves: int = 0, rowblocks: int = 0, colsplit: int = 0, resident: int = 0) -> int:
+    """Test-only kernel selection bits of the C ABI's mode argument (PREFT_TEST_* in preft.h)."""
+    return (PREFT_TEST_VARIANT(variant) | PREFT_TEST_WAVES(waves) | PREFT_TEST_ROWBLOCKS(rowblocks)
+            | PREFT_TEST_COLSPLIT(colsplit) | PREFT_TEST_RESIDENT(resident))
+
+
+# Tests and benchmarks only: bits OR-ed into the mode argument of every schedule and apply call
+# made through this binding (see test_flags), so that a test can send its usual calls down a
+# chosen kernel family.  The library itself keeps no such state; 0 leaves every call as written.
+_extra_mode_bits = 0
+
+
+def set_test_flags(bits: int = 0) -> int:
+    """Sets the bits above (0: none) and returns the previous value."""
+    global _extra_mode_bits
+    prev, _extra_mode_bits = _extra_mode_bits, int(bits)
+    return prev
+
+
+def _mode(mode: int) -> int:
+    return int(mode) | _extra_mode_bits
 
 # every symbol include/preft.h declares
 ABI_SYMBOLS = ("preft_workspace_bytes", "preft_schedule", "preft_lora_apply", "preft_lora_apply_packed",
                "preft_direft_apply", "preft_direft_apply_layers",
                "preft_loreft_prepare", "preft_loreft_apply", "preft_slots_create", "preft_slots_destroy",
                "preft_slots_store", "preft_slots_acquire", "preft_slots_pool", "preft_slots_resident",
-               "preft_slots_stats", "preft_schedule_counts", "preft_set_knob", "preft_strerror", "preft_version")
+               "preft_slots_stats", "preft_schedule_counts", "preft_strerror", "preft_version")
 
 _lib = None
 
@@ -92,8 +132,6 @@ def load_library(path: Optional[str] = None):
     lib.preft_slots_stats.argtypes = [vp, c.POINTER(i64)]
     lib.preft_schedule_counts.restype = c.c_int
     lib.preft_schedule_counts.argtypes = [vp, c.POINTER(i32), vp]
-    lib.preft_set_knob.restype = c.c_int
-    lib.preft_set_knob.argtypes = [c.c_int, c.c_int]
     lib.preft_strerror.restype = c.c_char_p
     lib.preft_strerror.argtypes = [c.c_int]
     lib.preft_version.restype = c.c_int
@@ -167,13 +205,6 @@ def preft_strerror(code: int) -> str:
     return load_library().preft_strerror(int(code)).decode()
 
 
-def preft_set_knob(knob: int, value: int) -> int:
-    rc = int(load_library().preft_set_knob(int(knob), int(value)))
-    if rc < 0:
-        raise PreftError(rc, "preft_set_knob")
-    return rc
-
-
 def preft_workspace_bytes(T: int, S: int) -> int:
     return int(load_library().preft_workspace_bytes(int(T), int(S)))
 
@@ -196,7 +227,7 @@ def preft_schedule(workspace: torch.Tensor, seg_start, seg_adapter, seg_prefill_
 def preft_schedule_counts(workspace: torch.Tensor, stream=None):
     out = (ctypes.c_int32 * 3)()
     _check(load_library().preft_schedule_counts(workspace.data_ptr(), out, _stream(stream)),
-           "preft_schedule_counts")
+           "preft_schedule_counts")          # raises PREFT_ESCHEDULE if an apply call refused the schedule
     return int(out[0]), int(out[1]), int(out[2])
 
 
@@ -217,7 +248,7 @@ def preft_lora_apply(y: torch.Tensor, x: torch.Tensor, seg_start, seg_adapter, s
         yp, ldy, xp, ldx, T, d_in, d_out,
         _table(seg_start, "seg_start", S + 1), _table(seg_adapter, "seg_adapter", S),
         _table(seg_prefill_len, "seg_prefill_len", S), S,
-        A_pool.data_ptr(), B_pool.data_ptr(), N, int(rank), float(scale), _dtype_code(y), int(mode),
+        A_pool.data_ptr(), B_pool.data_ptr(), N, int(rank), float(scale), _dtype_code(y), _mode(mode),
         workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, "preft_lora_apply")
 
@@ -246,7 +277,7 @@ def preft_lora_apply_packed(ys: Sequence[torch.Tensor], x: torch.Tensor, seg_sta
         n, yp, ldy, d_out, xp, ldx, T, d_in,
         _table(seg_start, "seg_start", S + 1), _table(seg_adapter, "seg_adapter", S),
         _table(seg_prefill_len, "seg_prefill_len", S), S, Ap, Bp, N, int(rank), float(scale), _dtype_code(x),
-        int(mode), workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream))
+        _mode(mode), workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, "preft_lora_apply_packed")
 
 
@@ -304,7 +335,7 @@ def preft_direft_apply_layers(hs: Sequence[torch.Tensor], h_layers: torch.Tensor
         _table(seg_start, "seg_start", S + 1), _table(seg_adapter, "seg_adapter", S),
         _table(seg_prefill_len, "seg_prefill_len", S), S,
         W1_pools.data_ptr(), W2t_pools.data_ptr(), None if b_pools is None else b_pools.data_ptr(), int(N),
-        int(rank), float(scale), _dtype_code(hs[0]), int(mode),
+        int(rank), float(scale), _dtype_code(hs[0]), _mode(mode),
         workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, "preft_direft_apply_layers")
 
@@ -321,7 +352,7 @@ def _reft_apply(entry: str, h, seg_start, seg_adapter, seg_prefill_len, W1_pool,
         _table(seg_start, "seg_start", S + 1), _table(seg_adapter, "seg_adapter", S),
         _table(seg_prefill_len, "seg_prefill_len", S), S,
         W1_pool.data_ptr(), W2t_pool.data_ptr(), None if b_pool is None else b_pool.data_ptr(), N,
-        int(rank), float(scale), _dtype_code(h), int(mode),
+        int(rank), float(scale), _dtype_code(h), _mode(mode),
         workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, entry)
 

@@ -9,7 +9,10 @@ namespace preft {
 // Schedule (written by schedule_kernel, read by every apply kernel)
 //
 //   header   int32[16]   [0] number of chunks  [1] number of short rows  [2] active rows
-//                        [3] mode  [4] number of gathered tiles
+//                        [3] position set (1: every position)  [4] number of gathered tiles
+//                        [5] T  [6] S  [7] N of the batch the schedule was built for
+//                        [8] set to 1 by an apply kernel whose call names another batch shape
+//                            or position set than [3], [5..7]
 //   chunks   int4[]      {adapter, first row, rows (1..CHUNK_ROWS), segment}
 //   shorts   int2[]      {adapter, row}, sorted by adapter when the pool has <= SORT_MAX_N slots
 //   gtiles   int4[]      {adapter, first entry in shorts, entries (1..GTILE_ROWS), 0}
@@ -28,6 +31,8 @@ constexpr int GTILE_ROWS  = 16;     // >= SHORT_ROWS: a short segment always fit
 constexpr int GROUP_ROWS  = 4;      // rows the per-row kernel carries through one sweep of the factors
 constexpr int SORT_MAX_N  = 4096;   // pools up to this many slots get their short rows sorted by adapter
 constexpr int HEADER_INTS = 16;
+constexpr int HDR_CHUNKS = 0, HDR_SHORT_ROWS = 1, HDR_ACTIVE = 2, HDR_ALL = 3, HDR_GTILES = 4, HDR_T = 5, HDR_S = 6,
+              HDR_N = 7, HDR_MISMATCH = 8;
 constexpr int PREFT_MAX_RANK_DEV = 128;   // must equal PREFT_MAX_RANK of the public header
 
 struct ScheduleView {
@@ -191,7 +196,8 @@ struct ApplyArgs {
     const void *const  *bias_pool;       // [rank] each, or null
     int32_t             N, rank;
     float               scale;
-    const int32_t      *header;
+    int32_t             S, all_tokens;   // with T and N: what the schedule in `header` must have been built for
+    int32_t            *header;
     const int4         *chunks;
     const int2         *shorts;
     const int4         *gtiles;
@@ -214,6 +220,27 @@ struct ApplyArgs {
     const void *const *const  *bias_layers = nullptr;   // null: no bias in any layer
     int32_t                    n_layers = 1;
 };
+
+// First thing every apply kernel does: the schedule it is about to walk must be the one of this
+// call's batch (same T, S, N and position set).  A caller that passes PREFT_SCHEDULE_READY with a
+// workspace built for something else would otherwise skip rows or apply the wrong position set
+// without any sign: such a launch does nothing and raises the mismatch flag of the header instead
+// (one ordinary vector store; preft_schedule_counts reports it).  Uniform: four scalar loads of
+// the cache line the kernel reads anyway.
+__device__ __forceinline__ bool schedule_matches(const ApplyArgs &p)
+{
+    const bool ok = p.header[HDR_T] == p.T && p.header[HDR_S] == p.S && p.header[HDR_N] == p.N &&
+                    p.header[HDR_ALL] == p.all_tokens;
+    if (!ok && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
+        *reinterpret_cast<volatile int32_t *>(p.header + HDR_MISMATCH) = 1;
+    return ok;
+}
+
+// bias vector of an adapter, or null: no bias table, or a null entry in it (Eq. 3 with b = 0)
+__device__ __forceinline__ gcptr_t bias_of(const ApplyArgs &p, int adapter)
+{
+    return p.bias_pool ? as_global(p.bias_pool[adapter]) : nullptr;
+}
 
 // Kernels of a many-layer in-place call: switch to the layer this workgroup belongs to
 // (uniform: scalar loads).
@@ -280,8 +307,8 @@ template <int R>
 __device__ __forceinline__ int tile_units(const ApplyArgs &p, int *n_chunk_units)
 {
     constexpr int UPG = R >= GTILE_ROWS ? 1 : GTILE_ROWS / R;
-    *n_chunk_units = p.gathered_only ? 0 : p.header[0] * (CHUNK_ROWS / R);
-    return *n_chunk_units + p.header[4] * UPG;
+    *n_chunk_units = p.gathered_only ? 0 : p.header[HDR_CHUNKS] * (CHUNK_ROWS / R);
+    return *n_chunk_units + p.header[HDR_GTILES] * UPG;
 }
 
 }  // namespace preft

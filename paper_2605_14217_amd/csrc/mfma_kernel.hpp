@@ -102,6 +102,7 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
     // the output columns, so that a step of a few dozen rows is spread over the chip instead
     // of walking every column in one workgroup.  Never in place: another workgroup's writes
     // must not meet this one's reads.
+    if (!schedule_matches(p)) return;
     const int csplit = COLSPLIT ? p.col_split : 1;
     int n_chunk_units, cslice = 0;
     const int n_units = tile_units<R>(p, &n_chunk_units);
@@ -363,10 +364,12 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
         const int rank0 = 16 * (b % NB) + 4 * g;              // rank within the block's own slice
         const bool rank_ok = rank0 < r;                       // r % 4 == 0: all four or none
         float bias[4] = {0.f, 0.f, 0.f, 0.f};
-        if (DIREFT && p.bias_pool && rank_ok) {
-            gcptr_t bias_p = as_global(p.bias_pool[adapter]);
+        if (DIREFT && rank_ok) {
+            gcptr_t bias_p = bias_of(p, adapter);
+            if (bias_p) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) bias[v] = Elem<bf16_tag>::load1(bias_p, rank0 + v);
+                for (int v = 0; v < 4; ++v) bias[v] = Elem<bf16_tag>::load1(bias_p, rank0 + v);
+            }
         }
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {

@@ -46,7 +46,8 @@ __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
     u32x4_t *turn_all = reinterpret_cast<u32x4_t *>(lds_raw);
     char *fac = lds_raw + WAVES * MB * 16 * MFMA_TRS * 16;    // factor area (A units, later B units)
 
-    const int unit_id = xcd_unit(p.header[0] * TPC);
+    if (!schedule_matches(p)) return;
+    const int unit_id = xcd_unit(p.header[HDR_CHUNKS] * TPC);
     if (unit_id < 0) return;
     const int4 ch = p.chunks[unit_id / TPC];
     const int tile_row0 = (unit_id % TPC) * R;
@@ -183,10 +184,12 @@ __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
         const int rank0 = 16 * b + 4 * g;
         const bool rank_ok = rank0 < r;
         float bias[4] = {0.f, 0.f, 0.f, 0.f};
-        if (DIREFT && p.bias_pool && rank_ok) {
-            gcptr_t bias_p = as_global(p.bias_pool[adapter]);
+        if (DIREFT && rank_ok) {
+            gcptr_t bias_p = bias_of(p, adapter);
+            if (bias_p) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) bias[v] = Elem<bf16_tag>::load1(bias_p, rank0 + v);
+                for (int v = 0; v < 4; ++v) bias[v] = Elem<bf16_tag>::load1(bias_p, rank0 + v);
+            }
         }
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {

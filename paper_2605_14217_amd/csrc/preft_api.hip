@@ -15,10 +15,31 @@ namespace {
 
 using namespace preft;
 
-int g_variant = 0;      // PREFT_KNOB_VARIANT
-int g_waves = 0;        // PREFT_KNOB_WAVES
-int g_rowblocks = 0;    // PREFT_KNOB_ROWBLOCKS
-int g_colsplit = 0;     // PREFT_KNOB_COLSPLIT
+// Kernel selection for tests and benchmarks, carried by the mode argument of the call itself
+// (PREFT_TEST_* of the public header): the library keeps no state between calls.
+struct Knobs {
+    int variant, waves, rowblocks, colsplit, resident;
+};
+constexpr int MODE_TEST_MASK = 0x7fff0000;
+constexpr int MODE_MASK = PREFT_ALL_TOKENS | PREFT_SCHEDULE_READY | MODE_TEST_MASK;
+
+inline Knobs knobs_of(int mode)
+{
+    Knobs k;
+    k.variant   = (mode >> 16) & 7;
+    k.waves     = (mode >> 19) & 15;
+    k.rowblocks = (mode >> 23) & 3;
+    k.colsplit  = (mode >> 25) & 15;
+    k.resident  = (mode >> 29) & 3;
+    return k;
+}
+inline bool knobs_valid(const Knobs &k)
+{
+    if (k.variant > 4) return false;
+    if (k.waves != 0 && k.waves != 1 && k.waves != 2 && k.waves != 4 && k.waves != 8) return false;
+    if (k.rowblocks > 2) return false;
+    return true;
+}
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -51,7 +72,7 @@ int check_tables(const void *workspace, size_t bytes, const int32_t *seg_start, 
                  const int32_t *seg_prefill_len, int32_t S, int32_t T, int32_t N, int mode)
 {
     if (T < 0 || S < 0 || N < 0) return PREFT_EINVAL;
-    if ((mode & ~(PREFT_ALL_TOKENS | PREFT_SCHEDULE_READY)) != 0) return PREFT_EINVAL;
+    if ((mode & ~MODE_MASK) != 0 || !knobs_valid(knobs_of(mode))) return PREFT_EINVAL;
     if (T == 0 || S == 0) return PREFT_OK;
     if (!seg_start || !seg_adapter || !seg_prefill_len) return PREFT_EINVAL;
     if (!workspace || !aligned16(workspace) || bytes < workspace_bytes(T, S)) return PREFT_EWORKSPACE;
@@ -82,9 +103,9 @@ inline unsigned tile_grid(const ApplyArgs &a, int64_t S, int rows)
 }
 // Workgroups per tile for the LoRA column-split kernel: a batch of a few hundred rows has too
 // few tiles to occupy the chip, and one workgroup per tile would walk every output column alone.
-inline int choose_col_split(int32_t T)
+inline int choose_col_split(int32_t T, const Knobs &k)
 {
-    if (g_colsplit) return g_colsplit;
+    if (k.colsplit) return k.colsplit;
     return T <= 1024 ? 4 : 1;
 }
 
@@ -158,10 +179,10 @@ bool launch_mfma_resident(const ApplyArgs &a, int64_t S, hipStream_t stream)
 
 // row-split kernel with the factors shared through LDS (rank >= 32, widths multiples of 128)
 template <int NB, bool DIREFT>
-bool launch_mfma_wide(const ApplyArgs &a, int64_t S, int mb, int waves, hipStream_t stream)
+bool launch_mfma_wide(const ApplyArgs &a, int64_t S, int mb, int waves, const Knobs &k, hipStream_t stream)
 {
     {
-        if (NB < 2 && g_variant != 4) return false;           // rank <= 16: only on request
+        if (NB < 2 && k.variant != 4) return false;           // rank <= 16: only on request
         if ((a.d_in & 127) || (a.d_out & 127)) return false;
         void (*kernel)(ApplyArgs);
         int rows = 128, threads = 512;
@@ -186,25 +207,25 @@ bool launch_mfma_wide(const ApplyArgs &a, int64_t S, int mb, int waves, hipStrea
 }
 
 template <int NB, bool DIREFT>
-void launch_mfma_nb(const ApplyArgs &a, int64_t S, hipStream_t stream)
+void launch_mfma_nb(const ApplyArgs &a, int64_t S, const Knobs &k, hipStream_t stream)
 {
     // rank >= 32: the factors outweigh a 16-row tile's activations, so more rows share them: the
     // row-split kernel.  Up to rank 64 with 4 wavefronts x 16 rows (two or three independent
     // workgroups per compute unit and twice the tiles: measured 3-10 points ahead of 8 wavefronts on
     // the 8B- and 70B-sized batches); above, 8 wavefronts (4 would leave one workgroup per unit)
-    const int wide_mb = g_rowblocks ? g_rowblocks : 1;
-    const int wide_waves = g_waves ? (g_waves == 8 ? 8 : 4) : (NB <= 4 ? 4 : 8);
+    const int wide_mb = k.rowblocks ? k.rowblocks : 1;
+    const int wide_waves = k.waves ? (k.waves == 8 ? 8 : 4) : (NB <= 4 ? 4 : 8);
     // column-split kernel.  rank <= 16: 8 wavefronts per 16-row tile; rank 32 (widths the
     // row-split kernel does not take): 32-row tiles of 4 wavefronts
-    const int mb = g_rowblocks ? g_rowblocks : (NB == 2 ? 2 : 1);
-    const int waves = g_waves ? (g_waves == 8 ? 8 : 4) : (NB == 2 ? 4 : 8);
+    const int mb = k.rowblocks ? k.rowblocks : (NB == 2 ? 2 : 1);
+    const int waves = k.waves ? (k.waves == 8 ? 8 : 4) : (NB == 2 ? 4 : 8);
     if constexpr (DIREFT) {
-        if (g_waves == 0 && g_variant != 4 && launch_mfma_resident<NB>(a, S, stream)) return;
+        if (k.waves == 0 && k.variant != 4 && launch_mfma_resident<NB>(a, S, stream)) return;
         // rank 32: 32-row tiles of the column-split kernel (half the factor traffic per row of a
         // 16-row tile, and the tile's second read mostly still finds it in the memory-side cache)
         // measured ahead of the resident and row-split shapes at d = 4096 and d = 8192
         if constexpr (NB == 2) {
-            if (g_waves == 0 && g_variant == 0 && g_rowblocks == 0) {
+            if (k.waves == 0 && k.variant == 0 && k.rowblocks == 0) {
                 launch_mfma<2, 2, 4, 0, true>(a, S, stream);
                 return;
             }
@@ -216,7 +237,7 @@ void launch_mfma_nb(const ApplyArgs &a, int64_t S, hipStream_t stream)
             return;
         }
     }
-    if (g_variant != 3 && launch_mfma_wide<NB, DIREFT>(a, S, wide_mb, wide_waves, stream)) {
+    if (k.variant != 3 && launch_mfma_wide<NB, DIREFT>(a, S, wide_mb, wide_waves, k, stream)) {
         // the row-split kernel shares one adapter's factors among the 128 rows of a chunk;
         // gathered tiles (16 rows of an adapter) go to the column-split kernel
         ApplyArgs g = a;
@@ -229,7 +250,7 @@ void launch_mfma_nb(const ApplyArgs &a, int64_t S, hipStream_t stream)
 
 // packed projections (LoRA, rank <= 16): one shrink sweep over x, one expand sweep per output
 template <int SLICES>
-void launch_mfma_packed(const ApplyArgs &a, int64_t S, hipStream_t stream)
+void launch_mfma_packed(const ApplyArgs &a, int64_t S, const Knobs &k, hipStream_t stream)
 {
     if (a.col_split > 1) {
         launch_mfma_colsplit<1, SLICES>(a, S, stream);
@@ -237,7 +258,7 @@ void launch_mfma_packed(const ApplyArgs &a, int64_t S, hipStream_t stream)
     }
     // three outputs: 4 wavefronts per tile leave room for two workgroups per compute unit (measured
     // better on small and large batches); two outputs: as for a single projection
-    const int waves = g_waves ? (g_waves == 8 ? 8 : 4) : (SLICES == 2 ? 8 : 4);
+    const int waves = k.waves ? (k.waves == 8 ? 8 : 4) : (SLICES == 2 ? 8 : 4);
     if (waves == 8)
         hipLaunchKernelGGL((mfma_tile_kernel<1, 1, 8, 0, false, SLICES>), dim3(tile_grid(a, S, 16)), dim3(512), 0,
                            stream, a);
@@ -247,24 +268,24 @@ void launch_mfma_packed(const ApplyArgs &a, int64_t S, hipStream_t stream)
 }
 
 template <bool DIREFT>
-void launch_mfma_rank(const ApplyArgs &a, int64_t S, hipStream_t stream)
+void launch_mfma_rank(const ApplyArgs &a, int64_t S, const Knobs &k, hipStream_t stream)
 {
     const int nb = (a.rank + 15) / 16;
-    if (nb <= 1)      launch_mfma_nb<1, DIREFT>(a, S, stream);
-    else if (nb <= 2) launch_mfma_nb<2, DIREFT>(a, S, stream);
-    else if (nb <= 4) launch_mfma_nb<4, DIREFT>(a, S, stream);
-    else              launch_mfma_nb<8, DIREFT>(a, S, stream);
+    if (nb <= 1)      launch_mfma_nb<1, DIREFT>(a, S, k, stream);
+    else if (nb <= 2) launch_mfma_nb<2, DIREFT>(a, S, k, stream);
+    else if (nb <= 4) launch_mfma_nb<4, DIREFT>(a, S, k, stream);
+    else              launch_mfma_nb<8, DIREFT>(a, S, k, stream);
 }
 
 template <int RANK, bool DIREFT>
-void launch_valu(const ApplyArgs &a, int64_t S, hipStream_t stream)
+void launch_valu(const ApplyArgs &a, int64_t S, const Knobs &k, hipStream_t stream)
 {
     // in place, rows of at most 4096 elements: 2 rows per wavefront stay in registers between the
     // sweeps, so h is read once (d = 4096: 56-59 -> 62-72 % of peak at rank 1-3).  Wider rows
     // would leave one row per wavefront, and the factors re-read for every row cost more than the
     // second read of h (d = 8192, rank 3: 42 % against 60 %).
     if constexpr (DIREFT) {
-        if (g_waves == 0 && g_rowblocks == 0 && a.d_in <= 4096) {
+        if (k.waves == 0 && k.rowblocks == 0 && a.d_in <= 4096) {
             void (*resident)(ApplyArgs) = valu_tile_kernel<RANK, 2, 4, true, 1, 8>;
             if (a.h_layers) resident = valu_tile_layers_kernel<RANK, 2, 4, 8>;
             hipLaunchKernelGGL(resident, dim3(tile_grid(a, S, 8), a.n_layers), dim3(256), 0, stream, a);
@@ -272,7 +293,7 @@ void launch_valu(const ApplyArgs &a, int64_t S, hipStream_t stream)
         }
     }
     constexpr int RB = RANK <= 4 ? 4 : 2;
-    int waves = g_waves ? g_waves : 4;
+    int waves = k.waves ? k.waves : 4;
     void (*kernel)(ApplyArgs);
     if (waves == 4) {
         kernel = valu_tile_kernel<RANK, RB, 4, DIREFT>;
@@ -301,17 +322,17 @@ void launch_valu_packed(const ApplyArgs &a, int64_t S, hipStream_t stream)
 }
 
 template <bool DIREFT>
-void launch_valu_rank(const ApplyArgs &a, int64_t S, hipStream_t stream)
+void launch_valu_rank(const ApplyArgs &a, int64_t S, const Knobs &k, hipStream_t stream)
 {
     switch (a.rank) {
-    case 1: launch_valu<1, DIREFT>(a, S, stream); break;
-    case 2: launch_valu<2, DIREFT>(a, S, stream); break;
-    case 3: launch_valu<3, DIREFT>(a, S, stream); break;
-    case 4: launch_valu<4, DIREFT>(a, S, stream); break;
-    case 5: launch_valu<5, DIREFT>(a, S, stream); break;
-    case 6: launch_valu<6, DIREFT>(a, S, stream); break;
-    case 7: launch_valu<7, DIREFT>(a, S, stream); break;
-    default: launch_valu<8, DIREFT>(a, S, stream); break;
+    case 1: launch_valu<1, DIREFT>(a, S, k, stream); break;
+    case 2: launch_valu<2, DIREFT>(a, S, k, stream); break;
+    case 3: launch_valu<3, DIREFT>(a, S, k, stream); break;
+    case 4: launch_valu<4, DIREFT>(a, S, k, stream); break;
+    case 5: launch_valu<5, DIREFT>(a, S, k, stream); break;
+    case 6: launch_valu<6, DIREFT>(a, S, k, stream); break;
+    case 7: launch_valu<7, DIREFT>(a, S, k, stream); break;
+    default: launch_valu<8, DIREFT>(a, S, k, stream); break;
     }
 }
 
@@ -338,29 +359,29 @@ void launch_rows(const ApplyArgs &a, int64_t S, bool chunks_too, hipStream_t str
 
 enum class Path { Rows, Valu, Mfma };
 
-Path choose_path(int dtype, int rank)
+Path choose_path(int dtype, int rank, const Knobs &k)
 {
-    if (dtype != PREFT_BF16 || g_variant == 1) return Path::Rows;
+    if (dtype != PREFT_BF16 || k.variant == 1) return Path::Rows;
     const bool valu_ok = rank <= 8, mfma_ok = (rank % 4) == 0;
-    if (g_variant == 2 && valu_ok) return Path::Valu;
-    if ((g_variant == 3 || g_variant == 4) && mfma_ok) return Path::Mfma;
+    if (k.variant == 2 && valu_ok) return Path::Valu;
+    if ((k.variant == 3 || k.variant == 4) && mfma_ok) return Path::Mfma;
     if (mfma_ok) return Path::Mfma;
     if (valu_ok) return Path::Valu;
     return Path::Rows;
 }
 
 template <bool DIREFT>
-int launch_apply(const ApplyArgs &a, int64_t S, int dtype, hipStream_t stream)
+int launch_apply(const ApplyArgs &a, int64_t S, int dtype, const Knobs &k, hipStream_t stream)
 {
-    switch (choose_path(dtype, a.rank)) {
+    switch (choose_path(dtype, a.rank, k)) {
     case Path::Mfma: {                     // the tile kernels take chunks and gathered tiles alike
         ApplyArgs b = a;
-        if (!DIREFT) b.col_split = choose_col_split(a.T);
-        launch_mfma_rank<DIREFT>(b, S, stream);
+        if (!DIREFT) b.col_split = choose_col_split(a.T, k);
+        launch_mfma_rank<DIREFT>(b, S, k, stream);
         break;
     }
     case Path::Valu:
-        launch_valu_rank<DIREFT>(a, S, stream);
+        launch_valu_rank<DIREFT>(a, S, k, stream);
         break;
     default:
         if (dtype == PREFT_BF16) launch_rows<bf16_tag, DIREFT>(a, S, true, stream);
@@ -384,6 +405,15 @@ __global__ __launch_bounds__(256) void loreft_prepare_kernel(void *D, void *Rt, 
     }
 }
 
+// the fields of a launch that name the batch and its schedule
+void bind_schedule(ApplyArgs &a, void *workspace, int32_t T, int32_t S, int32_t N, int mode)
+{
+    const ScheduleView v = view_of(workspace, T, S);
+    a.T = T; a.S = S; a.N = N; a.all_tokens = (mode & PREFT_ALL_TOKENS) ? 1 : 0;
+    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.gtiles = v.gtiles;
+    a.gathered_only = 0; a.col_split = 1;
+}
+
 int check_matrix(const void *p, int64_t ld, int32_t width, int dtype)
 {
     const int per16 = dtype == PREFT_BF16 ? 8 : 4;
@@ -403,11 +433,10 @@ int direft_launch(ApplyArgs a, int64_t ldh, int32_t T, int32_t d, const int32_t 
         const int rc = launch_schedule(workspace, seg_start, seg_adapter, seg_prefill_len, S, T, N, mode, st);
         if (rc != PREFT_OK) return rc;
     }
-    ScheduleView v = view_of(workspace, T, S);
-    a.ldy = ldh; a.ldx = ldh; a.T = T; a.d_in = d; a.d_out = d;
-    a.N = N; a.rank = rank; a.scale = scale;
-    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.gtiles = v.gtiles; a.gathered_only = 0; a.col_split = 1;
-    return launch_apply<true>(a, S, dtype, st);
+    bind_schedule(a, workspace, T, S, N, mode);
+    a.ldy = ldh; a.ldx = ldh; a.d_in = d; a.d_out = d;
+    a.rank = rank; a.scale = scale;
+    return launch_apply<true>(a, S, dtype, knobs_of(mode), st);
 }
 
 }  // namespace
@@ -454,12 +483,11 @@ int preft_lora_apply(void *y, int64_t ldy, const void *x, int64_t ldx, int32_t T
         rc = launch_schedule(workspace, seg_start, seg_adapter, seg_prefill_len, S, T, N, mode, st);
         if (rc != PREFT_OK) return rc;
     }
-    ScheduleView v = view_of(workspace, T, S);
     ApplyArgs a;
-    a.y = y; a.x = x; a.ldy = ldy; a.ldx = ldx; a.T = T; a.d_in = d_in; a.d_out = d_out;
-    a.A_pool = A_pool; a.Bt_pool = B_pool; a.bias_pool = nullptr; a.N = N; a.rank = rank; a.scale = scale;
-    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.gtiles = v.gtiles; a.gathered_only = 0; a.col_split = 1;
-    return launch_apply<false>(a, S, dtype, st);
+    bind_schedule(a, workspace, T, S, N, mode);
+    a.y = y; a.x = x; a.ldy = ldy; a.ldx = ldx; a.d_in = d_in; a.d_out = d_out;
+    a.A_pool = A_pool; a.Bt_pool = B_pool; a.bias_pool = nullptr; a.rank = rank; a.scale = scale;
+    return launch_apply<false>(a, S, dtype, knobs_of(mode), st);
 }
 
 int preft_lora_apply_packed(int32_t n_proj, void *const *y, const int64_t *ldy, const int32_t *d_out, const void *x,
@@ -502,10 +530,11 @@ int preft_lora_apply_packed(int32_t n_proj, void *const *y, const int64_t *ldy, 
         if (rc != PREFT_OK) return rc;
     }
     const int ready = mode | PREFT_SCHEDULE_READY;
+    const Knobs k = knobs_of(mode);
     const bool fused_mfma = n_proj > 1 && dtype == PREFT_BF16 && rank <= 16 && (rank % 4) == 0 &&
-                            (g_variant == 0 || g_variant == 3);
-    const bool fused_valu = n_proj > 1 && dtype == PREFT_BF16 && rank <= 3 && (g_variant == 0 || g_variant == 2) &&
-                            (g_waves == 0 || g_waves == 4);
+                            (k.variant == 0 || k.variant == 3);
+    const bool fused_valu = n_proj > 1 && dtype == PREFT_BF16 && rank <= 3 && (k.variant == 0 || k.variant == 2) &&
+                            (k.waves == 0 || k.waves == 4);
     const bool fused = fused_mfma || fused_valu;
     if (!fused) {                                  // same result, one launch per projection
         for (int32_t i = 0; i < n_proj; ++i) {
@@ -515,19 +544,18 @@ int preft_lora_apply_packed(int32_t n_proj, void *const *y, const int64_t *ldy, 
         }
         return PREFT_OK;
     }
-    ScheduleView v = view_of(workspace, T, S);
     ApplyArgs a;
-    a.y = y[0]; a.x = x; a.ldy = ldy[0]; a.ldx = ldx; a.T = T; a.d_in = d_in; a.d_out = d_out[0];
-    a.A_pool = A_pools[0]; a.Bt_pool = B_pools[0]; a.bias_pool = nullptr; a.N = N; a.rank = rank; a.scale = scale;
-    a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.gtiles = v.gtiles; a.gathered_only = 0; a.col_split = 1;
+    bind_schedule(a, workspace, T, S, N, mode);
+    a.y = y[0]; a.x = x; a.ldy = ldy[0]; a.ldx = ldx; a.d_in = d_in; a.d_out = d_out[0];
+    a.A_pool = A_pools[0]; a.Bt_pool = B_pools[0]; a.bias_pool = nullptr; a.rank = rank; a.scale = scale;
     for (int32_t i = 1; i < n_proj; ++i) {
         a.more[i - 1].y = y[i]; a.more[i - 1].ldy = ldy[i]; a.more[i - 1].d_out = d_out[i];
         a.more[i - 1].A_pool = A_pools[i]; a.more[i - 1].Bt_pool = B_pools[i];
     }
     if (fused_mfma) {
-        a.col_split = choose_col_split(T);
-        if (n_proj == 2) launch_mfma_packed<2>(a, S, st);
-        else             launch_mfma_packed<3>(a, S, st);
+        a.col_split = choose_col_split(T, k);
+        if (n_proj == 2) launch_mfma_packed<2>(a, S, k, st);
+        else             launch_mfma_packed<3>(a, S, k, st);
     } else {
         if (n_proj == 2) launch_valu_packed<2>(a, S, st);
         else             launch_valu_packed<3>(a, S, st);
@@ -620,24 +648,12 @@ int preft_schedule_counts(const void *workspace, int32_t *counts, void *stream)
 {
     if (!workspace || !counts) return PREFT_EINVAL;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    if (hipMemcpyAsync(counts, workspace, 3 * sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess)
+    int32_t header[HEADER_INTS];
+    if (hipMemcpyAsync(header, workspace, sizeof(header), hipMemcpyDeviceToHost, st) != hipSuccess)
         return PREFT_EHIP;
-    return hipStreamSynchronize(st) == hipSuccess ? PREFT_OK : PREFT_EHIP;
-}
-
-int preft_set_knob(int knob, int value)
-{
-    int *slot = nullptr;
-    switch (knob) {
-    case PREFT_KNOB_VARIANT:   if (value < 0 || value > 4) return PREFT_EINVAL; slot = &g_variant; break;
-    case PREFT_KNOB_WAVES:     if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return PREFT_EINVAL; slot = &g_waves; break;
-    case PREFT_KNOB_ROWBLOCKS: if (value < 0 || value > 2) return PREFT_EINVAL; slot = &g_rowblocks; break;
-    case PREFT_KNOB_COLSPLIT:  if (value < 0 || value > 16) return PREFT_EINVAL; slot = &g_colsplit; break;
-    default: return PREFT_EINVAL;
-    }
-    const int prev = *slot;
-    *slot = value;
-    return prev;
+    if (hipStreamSynchronize(st) != hipSuccess) return PREFT_EHIP;
+    counts[0] = header[HDR_CHUNKS]; counts[1] = header[HDR_SHORT_ROWS]; counts[2] = header[HDR_ACTIVE];
+    return header[HDR_MISMATCH] ? PREFT_ESCHEDULE : PREFT_OK;
 }
 
 const char *preft_strerror(int code)
@@ -650,10 +666,11 @@ const char *preft_strerror(int code)
     case PREFT_EWORKSPACE:   return "workspace missing, misaligned or smaller than preft_workspace_bytes(T, S)";
     case PREFT_EHIP:         return "HIP runtime error (launch, copy or allocation)";
     case PREFT_ECAPACITY:    return "more distinct adapters in one batch than the slot manager has slots";
+    case PREFT_ESCHEDULE:    return "an apply call named another T, S, N or position set than the schedule in its workspace was built for; that call did nothing";
     default:                 return "unknown preft error code";
     }
 }
 
-int preft_version(void) { return 100; }
+int preft_version(void) { return 200; }
 
 }  // extern "C"

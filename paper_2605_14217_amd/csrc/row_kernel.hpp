@@ -108,7 +108,7 @@ __device__ __forceinline__ void group_apply(const ApplyArgs &p, int adapter, con
     const int r = p.rank;
     gcptr_t A  = as_global(p.A_pool[adapter]);
     gcptr_t Bt = as_global(p.Bt_pool[adapter]);
-    gcptr_t bias = (DIREFT && p.bias_pool) ? as_global(p.bias_pool[adapter]) : nullptr;
+    gcptr_t bias = DIREFT ? bias_of(p, adapter) : nullptr;        // null: no table, or a null entry
     gcptr_t xrow[G];
     gptr_t yrow[G];
 #pragma unroll
@@ -237,11 +237,12 @@ template <typename E, bool DIREFT>
 __device__ __forceinline__ void row_short_body(const ApplyArgs &p)
 {
     __shared__ float z[GROUP_ROWS * PREFT_MAX_RANK_DEV];
-    const int grows = max(1, min(GROUP_ROWS, p.header[1] / 512));
+    if (!schedule_matches(p)) return;
+    const int grows = max(1, min(GROUP_ROWS, p.header[HDR_SHORT_ROWS] / 512));
     const int per_tile = (GTILE_ROWS + grows - 1) / grows;
     // tiles are sorted by adapter: deal contiguous runs to the 8 XCDs (workgroup ids go round-robin
     // over them) so that the groups of one adapter meet in one L2
-    const int n = p.header[4] * per_tile;
+    const int n = p.header[HDR_GTILES] * per_tile;
     const int per_xcd = (n + 7) >> 3;
     const int first = (blockIdx.x & 7) * per_xcd, last = min(first + per_xcd, n);
     for (int e = first + (blockIdx.x >> 3); e < last; e += gridDim.x >> 3) {
@@ -262,8 +263,9 @@ __device__ __forceinline__ void row_chunks_body(const ApplyArgs &p)
 {
     __shared__ float z[GROUP_ROWS * PREFT_MAX_RANK_DEV];
     constexpr int PER_CHUNK = CHUNK_ROWS / GROUP_ROWS;
+    if (!schedule_matches(p)) return;
     const int c = blockIdx.x / PER_CHUNK;
-    if (c >= p.header[0]) return;
+    if (c >= p.header[HDR_CHUNKS]) return;
     const int4 ch = p.chunks[c];
     const int first = (blockIdx.x % PER_CHUNK) * GROUP_ROWS;
     if (first >= ch.z) return;

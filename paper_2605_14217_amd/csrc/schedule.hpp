@@ -54,6 +54,16 @@ __device__ __forceinline__ int32_t block_exclusive_scan(int32_t v, int32_t *lds 
     return base + incl - v;
 }
 
+// A gathered tile names entries [first, first + n) of the short-row list.  With well-formed
+// tables the list never outgrows its capacity (a row belongs to one segment); tables whose
+// segments overlap can make it do so, and the entries beyond the capacity are never written:
+// a tile is cut back to the entries that exist, so that no kernel indexes past the list.
+__device__ __forceinline__ int4 clamped_gtile(int32_t adapter, int32_t first, int32_t n, int32_t short_cap)
+{
+    if (first >= short_cap) return make_int4(adapter, 0, 0, 0);
+    return make_int4(adapter, first, min(n, short_cap - first), 0);
+}
+
 // One workgroup.  Thread i owns the contiguous slice of segments [i*per, (i+1)*per), so the
 // chunk list keeps segment order (consecutive chunks of one segment share an adapter, which
 // the tile kernels exploit for cache locality).  Short rows are counting-sorted by adapter
@@ -122,18 +132,22 @@ __global__ __launch_bounds__(SCHED_THREADS) void schedule_kernel(
             bin_cursor[a] = row_base;
             for (int32_t i = 0; i * grows < c; ++i, ++grp)
                 if (grp < out.short_cap)
-                    out.gtiles[grp] = make_int4(a, row_base + i * grows, min(grows, c - i * grows), 0);
+                    out.gtiles[grp] = clamped_gtile(a, row_base + i * grows, min(grows, c - i * grows), out.short_cap);
             row_base += c;
         }
         __syncthreads();
     }
 
     if (tid == 0) {
-        out.header[0] = min(tot_chunks, out.chunk_cap);
-        out.header[1] = min(tot_short, out.short_cap);
-        out.header[2] = tot_act;
-        out.header[3] = all_tokens;
-        out.header[4] = min(tot_gtiles, out.short_cap);
+        out.header[HDR_CHUNKS] = min(tot_chunks, out.chunk_cap);
+        out.header[HDR_SHORT_ROWS] = min(tot_short, out.short_cap);
+        out.header[HDR_ACTIVE] = tot_act;
+        out.header[HDR_ALL] = all ? 1 : 0;
+        out.header[HDR_GTILES] = min(tot_gtiles, out.short_cap);
+        out.header[HDR_T] = T;
+        out.header[HDR_S] = S;
+        out.header[HDR_N] = N;
+        out.header[HDR_MISMATCH] = 0;
     }
 
     // ---- pass 2: emission.  All lanes of a wave run the same number of iterations; a segment
@@ -149,7 +163,7 @@ __global__ __launch_bounds__(SCHED_THREADS) void schedule_kernel(
                 pos = atomicAdd(&bin_cursor[g.adapter], g.n_act);
             } else {
                 pos = short_off;
-                if (seg_off < out.short_cap) out.gtiles[seg_off] = make_int4(g.adapter, pos, g.n_act, 0);
+                if (seg_off < out.short_cap) out.gtiles[seg_off] = clamped_gtile(g.adapter, pos, g.n_act, out.short_cap);
                 short_off += g.n_act;
                 seg_off += 1;
             }

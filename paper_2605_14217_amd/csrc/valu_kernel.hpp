@@ -43,6 +43,7 @@ __device__ __forceinline__ void valu_tile_body(const ApplyArgs &p)
     static_assert(SLICES == 1 || !DIREFT, "packed projections are a LoRA feature");
     static_assert(CHUNK_ROWS % R == 0, "tile height must divide the chunk height");
 
+    if (!schedule_matches(p)) return;
     int n_chunk_units;
     const int unit = xcd_unit(tile_units<R>(p, &n_chunk_units));
     if (unit < 0) return;
@@ -134,10 +135,11 @@ __device__ __forceinline__ void valu_tile_body(const ApplyArgs &p)
         for (int k = 0; k < RT; ++k) av[k] = ld16(A[k / RANK] + ((int64_t)(k % RANK) * p.d_in + (int64_t)c * 8) * 2);
         shrink_step(xv, av);
     }
+    gcptr_t bias_p = DIREFT ? bias_of(p, adapter) : nullptr;
 #pragma unroll
     for (int k = 0; k < RT; ++k) {
         float bias = 0.f;
-        if (DIREFT && p.bias_pool) bias = Elem<bf16_tag>::load1(as_global(p.bias_pool[adapter]), k);
+        if (DIREFT && bias_p) bias = Elem<bf16_tag>::load1(bias_p, k);
 #pragma unroll
         for (int i = 0; i < RB; ++i) z[i][k] = (wave_sum(z[i][k]) + bias) * p.scale;
     }

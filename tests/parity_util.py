@@ -86,8 +86,9 @@ def lora_pools_to_device(pool: wl.LoraPool, perm=None):
     return preft.pointer_table(A_store), preft.pointer_table(B_store), (A_store, B_store)
 
 
-def direft_pools_to_device(pool: wl.DireftPool, perm=None, bias=True):
-    """W1 = paper's A [r,d]; W2t = transpose of the paper's B -> [d,r]; b [r]."""
+def direft_pools_to_device(pool: wl.DireftPool, perm=None, bias=True, null_bias=()):
+    """W1 = paper's A [r,d]; W2t = transpose of the paper's B -> [d,r]; b [r].  Adapters listed in
+    null_bias get a null entry in the bias table (no bias for them)."""
     N = pool.N
     order = list(range(N)) if perm is None else list(perm)
     W1, W2t, b = [None] * N, [None] * N, [None] * N
@@ -95,8 +96,12 @@ def direft_pools_to_device(pool: wl.DireftPool, perm=None, bias=True):
         W1[slot] = pool.A[slot].clone()
         W2t[slot] = pool.B[slot].t().contiguous()
         b[slot] = pool.b[slot].clone()
-    return (preft.pointer_table(W1), preft.pointer_table(W2t),
-            preft.pointer_table(b) if bias else None, (W1, W2t, b))
+    btab = None
+    if bias:
+        btab = preft.pointer_table(b)
+        for i in null_bias:
+            btab[i] = 0
+    return (preft.pointer_table(W1), preft.pointer_table(W2t), btab, (W1, W2t, b))
 
 
 def run_lora_case(tab: wl.SegmentTable, pool: wl.LoraPool, x: torch.Tensor, y0: torch.Tensor, dtype: str,
@@ -140,12 +145,13 @@ def run_lora_case(tab: wl.SegmentTable, pool: wl.LoraPool, x: torch.Tensor, y0: 
 
 
 def run_direft_case(tab: wl.SegmentTable, pool: wl.DireftPool, h0: torch.Tensor, dtype: str, scale: float,
-                    all_tokens: bool, pad_cols=0, rows=None, perm=None, bias=True, reuse_schedule=False):
+                    all_tokens: bool, pad_cols=0, rows=None, perm=None, bias=True, reuse_schedule=False,
+                    null_bias=()):
     N, r = pool.N, pool.r
     T = tab.T
     mode = preft.PREFT_ALL_TOKENS if all_tokens else preft.PREFT_PREFILL_ONLY
     ss, sa, sp = dev_tables(tab)
-    W1p, W2tp, bp, keep = direft_pools_to_device(pool, perm, bias)
+    W1p, W2tp, bp, keep = direft_pools_to_device(pool, perm, bias, null_bias)
     hbuf, h = padded(h0, pad_cols, 7.0)
     ws = preft.new_workspace(T, tab.S)
     if reuse_schedule:
@@ -162,7 +168,7 @@ def run_direft_case(tab: wl.SegmentTable, pool: wl.DireftPool, h0: torch.Tensor,
     needed = set(np.unique(sel[sel >= 0]).tolist())
     A_cpu = [pool.A[i].cpu() if i in needed else None for i in range(N)]
     B_cpu = [pool.B[i].cpu() if i in needed else None for i in range(N)]
-    b_cpu = [pool.b[i].cpu() if i in needed else None for i in range(N)] if bias else None
+    b_cpu = [pool.b[i].cpu() if (i in needed and i not in null_bias) else None for i in range(N)] if bias else None
     if rows is None:
         want = ora.direft(h0.cpu(), tab.seg_start, tab.seg_adapter, tab.seg_prefill_len,
                           A_cpu, B_cpu, b_cpu, r, scale, pos)

@@ -12,6 +12,7 @@ from paper_2605_14217_amd import binding
 from paper_2605_14217_amd import workloads as wl
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "preft.h")
 
 
 @pytest.fixture(scope="module")
@@ -42,21 +43,36 @@ def test_missing_library_fails_loudly(tmp_path):
 
 def test_version_and_error_strings(lib):
     assert preft.preft_version() >= 100
-    for code in (0, -1, -2, -3, -4, -5):
+    for code in (0, -1, -2, -3, -4, -5, -6, -7):
         assert preft.preft_strerror(code)
     assert "unknown" in preft.preft_strerror(-99)
 
 
-def test_knob_validation(lib):
-    assert lib.preft_set_knob(99, 0) == -1
-    assert lib.preft_set_knob(preft.PREFT_KNOB_VARIANT, 7) == -1
-    assert lib.preft_set_knob(preft.PREFT_KNOB_VARIANT, 5) == -1
-    assert lib.preft_set_knob(preft.PREFT_KNOB_WAVES, 3) == -1
-    assert lib.preft_set_knob(preft.PREFT_KNOB_COLSPLIT, 17) == -1
-    assert lib.preft_set_knob(preft.PREFT_KNOB_COLSPLIT, -1) == -1
-    assert lib.preft_set_knob(preft.PREFT_KNOB_COLSPLIT, 0) >= 0
-    prev = preft.preft_set_knob(preft.PREFT_KNOB_VARIANT, 1)
-    assert preft.preft_set_knob(preft.PREFT_KNOB_VARIANT, prev) == 1
+def test_kernel_selection_travels_in_the_call_not_in_the_library(lib):
+    """The library exports no knob: the test-only selection bits are part of `mode`, undefined values
+    are refused before anything is launched (host-side checks only: no GPU needed), and the macros of
+    the header and the helpers of the binding agree."""
+    assert not hasattr(lib, "preft_set_knob")
+    header = open(HEADER).read()
+    for name, shift, mask in (("VARIANT", 16, 7), ("WAVES", 19, 15), ("ROWBLOCKS", 23, 3), ("COLSPLIT", 25, 15),
+                              ("RESIDENT", 29, 3)):
+        m = re.search(r"#define PREFT_TEST_%s\(\w\)\s+\(\(\(\w\) & (\d+)\) << (\d+)\)" % name, header)
+        assert m and int(m.group(1)) == mask and int(m.group(2)) == shift, name
+        assert getattr(preft, "PREFT_TEST_" + name)(mask) == mask << shift
+    assert preft.test_flags(variant=3, waves=8, rowblocks=2, colsplit=5, resident=1) == \
+        (3 << 16) | (8 << 19) | (2 << 23) | (5 << 25) | (1 << 29)
+    c = ctypes
+    def schedule(mode):
+        # T > 0, S > 0 and null tables: a valid mode gets as far as the table check (EINVAL would
+        # come from there too), so use a workspace error to tell the two apart: null workspace
+        one = (c.c_int32 * 2)(0, 1)
+        return lib.preft_schedule(None, 0, one, one, one, 1, 1, 1, mode, None)
+    assert schedule(0) == -4 and schedule(1) == -4                      # EWORKSPACE: the mode passed
+    assert schedule(preft.test_flags(variant=4, waves=8, rowblocks=2, colsplit=15, resident=3)) == -4
+    assert schedule(preft.test_flags(variant=5)) == -1                   # undefined variant
+    assert schedule(preft.test_flags(waves=3)) == -1                     # not 0, 1, 2, 4, 8
+    assert schedule(preft.test_flags(rowblocks=3)) == -1
+    assert schedule(2) == -1 and schedule(0x200) == -1 and schedule(1 << 15) == -1   # undefined bits
 
 
 def test_workspace_is_large_enough_for_any_table(lib):

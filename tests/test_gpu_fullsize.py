@@ -17,8 +17,7 @@ pytestmark = pytest.mark.gpu
 @pytest.fixture(autouse=True)
 def _reset(request):
     print(f"\n[case] {request.node.name}", flush=True)
-    for k in (preft.PREFT_KNOB_VARIANT, preft.PREFT_KNOB_WAVES, preft.PREFT_KNOB_ROWBLOCKS, preft.PREFT_KNOB_COLSPLIT):
-        preft.preft_set_knob(k, 0)
+    preft.set_test_flags(0)
     yield
     gc.collect()
     torch.cuda.empty_cache()

@@ -20,16 +20,22 @@ def _announce_and_reset(request):
     print(f"\n[case] {request.node.name}", flush=True)
     sys.stdout.flush()
     yield
-    preft.preft_set_knob(preft.PREFT_KNOB_VARIANT, 0)
-    preft.preft_set_knob(preft.PREFT_KNOB_WAVES, 0)
-    preft.preft_set_knob(preft.PREFT_KNOB_ROWBLOCKS, 0)
-    preft.preft_set_knob(preft.PREFT_KNOB_COLSPLIT, 0)
+    preft.set_test_flags(0)
 
 
-def _set(variant=0, waves=0, rowblocks=0):
-    preft.preft_set_knob(preft.PREFT_KNOB_VARIANT, variant)
-    preft.preft_set_knob(preft.PREFT_KNOB_WAVES, waves)
-    preft.preft_set_knob(preft.PREFT_KNOB_ROWBLOCKS, rowblocks)
+_flags = dict(variant=0, waves=0, rowblocks=0, colsplit=0, resident=0)
+
+
+def _set(variant=0, waves=0, rowblocks=0, **more):
+    """Kernel selection for the calls that follow (test-only bits of the mode argument)."""
+    _flags.update(variant=variant, waves=waves, rowblocks=rowblocks, colsplit=0, resident=0)
+    _flags.update(more)
+    preft.set_test_flags(preft.test_flags(**_flags))
+
+
+def _set_colsplit(colsplit):
+    _flags.update(colsplit=colsplit)
+    preft.set_test_flags(preft.test_flags(**_flags))
 
 
 def _mixed_table(seed, N, n_prompts=6, max_len=300, n_decode=10):
@@ -314,6 +320,126 @@ def test_results_are_deterministic_and_schedule_reuse_matches():
         torch.cuda.synchronize()
         outs.append(y)
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+
+
+@pytest.mark.parametrize("variant,dtype,rank,d", [(0, "bf16", 16, 1024), (0, "bf16", 8, 4096), (0, "bf16", 32, 512),
+                                                  (0, "bf16", 64, 256), (VARIANT_MFMA, "bf16", 32, 264), (0, "bf16", 3, 520),
+                                                  (0, "bf16", 7, 256), (VARIANT_ROW, "bf16", 12, 264), (0, "f32", 4, 132)])
+def test_null_entries_of_the_bias_table_mean_no_bias_for_that_adapter(variant, dtype, rank, d):
+    """Eq. 3 with b = 0 for single adapters: a null entry in b_pool (the oracle gets no bias for them)."""
+    from parity_util import run_direft_case
+    N = 5
+    _set(variant)
+    tab = _mixed_table(1300 + rank, N)
+    pool = wl.direft_pool(N, rank, d, dtype, device="cuda", seed=131)
+    h = wl.activations(tab.T, d, dtype, device="cuda", seed=132)
+    for all_tokens in (False, True):
+        worst, _ = run_direft_case(tab, pool, h, dtype, 0.5, all_tokens, pad_cols=8, null_bias=(0, 3))
+        print(f"  variant={variant} {dtype} r={rank} d={d} all_tokens={all_tokens} worst {worst:.2e}")
+    # the bias matters in this test: with every entry present the result differs on adapter 0's rows
+    from parity_util import dev_tables, direft_pools_to_device
+    ss, sa, sp = dev_tables(tab)
+    outs = []
+    for nulls in ((), (0, 3)):
+        W1p, W2tp, bp, keep = direft_pools_to_device(pool, None, True, nulls)
+        hh = h.clone()
+        preft.preft_direft_apply(hh, ss, sa, sp, W1p, W2tp, bp, rank, 0.5, preft.PREFT_ALL_TOKENS,
+                                 preft.new_workspace(tab.T, tab.S))
+        torch.cuda.synchronize()
+        outs.append(hh)
+    assert not torch.equal(outs[0], outs[1])
+
+
+@pytest.mark.parametrize("N", [3, 5000])          # short rows sorted by adapter / listed per segment
+def test_overlapping_segments_stay_inside_the_buffers(N):
+    """Malformed tables: offsets that go back and forth name the same rows many times, so the lists of
+    the schedule would outgrow the capacities computed from T and S.  The result is unspecified, but
+    every access must stay inside the buffers: guard rows and row padding come back untouched and
+    the schedule's counters stay within their capacities."""
+    from parity_util import GUARD_ROWS, check_guards, padded
+    d, r = 256, 16
+    for T, starts in ((4, [0, 4] * 40 + [0, 4]), (300, [0, 300, 0, 3, 100, 1, 2, 300] * 6 + [300]),
+                      (64, list(np.tile([0, 2, 64, 1], 30)) + [64])):
+        starts = np.asarray(starts, dtype=np.int32)
+        S = len(starts) - 1
+        tab = wl.SegmentTable(starts, (np.arange(S) % min(N, 7)).astype(np.int32), np.full(S, 1000, dtype=np.int32))
+        ss, sa, sp = (torch.from_numpy(a.copy()).cuda() for a in (tab.seg_start, tab.seg_adapter, tab.seg_prefill_len))
+        pool = wl.lora_pool(7, r, d, d, "bf16", device="cuda", seed=3)
+        tabA = preft.pointer_table([pool.A[i].contiguous() for i in range(7)])
+        tabB = preft.pointer_table([pool.B[i].contiguous() for i in range(7)])
+        if N > 7:                                   # a large pool whose used slots are the first seven
+            tabA = torch.cat([tabA, torch.zeros(N - 7, dtype=torch.int64, device="cuda")])
+            tabB = torch.cat([tabB, torch.zeros(N - 7, dtype=torch.int64, device="cuda")])
+        else:
+            tabA, tabB = tabA[:N].contiguous(), tabB[:N].contiguous()
+            tab.seg_adapter[:] = tab.seg_adapter % N
+            sa = torch.from_numpy(tab.seg_adapter.copy()).cuda()
+        x = wl.activations(T, d, "bf16", device="cuda", seed=31)
+        ws = preft.new_workspace(T, S)
+        cap_short = min(4 * S, T) + 1
+        for variant in (0, VARIANT_ROW, VARIANT_VALU):
+            _set(variant)
+            for mode in (preft.PREFT_PREFILL_ONLY, preft.PREFT_ALL_TOKENS):
+                ybuf, y = padded(wl.activations(T, d, "bf16", device="cuda", seed=32), 8, 7.0)
+                hbuf, h = padded(x, 8, 7.0)
+                preft.preft_lora_apply(y, x, ss, sa, sp, tabA, tabB, r, 1.0, mode, ws)
+                preft.preft_direft_apply(h, ss, sa, sp, tabA, tabB, None, r, 1.0, mode | preft.PREFT_SCHEDULE_READY, ws)
+                torch.cuda.synchronize()
+                counts = preft.preft_schedule_counts(ws)
+                assert counts[1] <= cap_short, counts
+                check_guards(ybuf, T, d, 7.0)
+                check_guards(hbuf, T, d, 7.0)
+                assert bool(torch.isfinite(y.float()).all())
+        print(f"  N={N} T={T} S={S} counts {counts}")
+
+
+def test_a_schedule_built_for_another_batch_is_refused_not_misread():
+    """PREFT_SCHEDULE_READY with a workspace whose schedule was built for another position set, T, S
+    or N: the apply call must do nothing, and preft_schedule_counts must say so."""
+    from parity_util import bits, dev_tables, direft_pools_to_device, lora_pools_to_device
+    N, d, r = 4, 512, 16
+    tab = _mixed_table(77, N)
+    ss, sa, sp = dev_tables(tab)
+    pool = wl.lora_pool(N, r, d, d, "bf16", device="cuda", seed=7)
+    dp = wl.direft_pool(N, r, d, "bf16", device="cuda", seed=8)
+    Ap, Bp, keep = lora_pools_to_device(pool)
+    W1p, W2tp, bp, keep2 = direft_pools_to_device(dp)
+    x = wl.activations(tab.T, d, "bf16", device="cuda", seed=71)
+    y0 = wl.activations(tab.T, d, "bf16", device="cuda", seed=72)
+    ws = preft.new_workspace(tab.T, tab.S)
+    ready = preft.PREFT_SCHEDULE_READY
+    for variant in (0, VARIANT_ROW, VARIANT_WIDE):
+        _set(variant)
+        # another position set
+        preft.preft_schedule(ws, ss, sa, sp, tab.T, N, preft.PREFT_ALL_TOKENS)
+        y, h = y0.clone(), x.clone()
+        preft.preft_lora_apply(y, x, ss, sa, sp, Ap, Bp, r, 2.0, preft.PREFT_PREFILL_ONLY | ready, ws)
+        preft.preft_direft_apply(h, ss, sa, sp, W1p, W2tp, bp, r, 1.0, preft.PREFT_PREFILL_ONLY | ready, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(bits(y), bits(y0)) and torch.equal(bits(h), bits(x))
+        with pytest.raises(preft.PreftError) as e:
+            preft.preft_schedule_counts(ws)
+        assert e.value.code == preft.PREFT_ESCHEDULE
+        # another pool size (N), another row count (T: one row fewer, the tables still describe tab.T rows)
+        preft.preft_schedule(ws, ss, sa, sp, tab.T, N, preft.PREFT_PREFILL_ONLY)
+        assert preft.preft_schedule_counts(ws)[2] > 0                      # a fresh schedule clears the mark
+        preft.preft_lora_apply(y, x, ss, sa, sp, Ap[:N - 1].contiguous(), Bp[:N - 1].contiguous(), r, 2.0, ready, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(bits(y), bits(y0))
+        with pytest.raises(preft.PreftError):
+            preft.preft_schedule_counts(ws)
+        preft.preft_schedule(ws, ss, sa, sp, tab.T, N, preft.PREFT_PREFILL_ONLY)
+        preft.preft_direft_apply(h[:-1], ss, sa, sp, W1p, W2tp, bp, r, 1.0, ready, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(bits(h), bits(x))
+        with pytest.raises(preft.PreftError):
+            preft.preft_schedule_counts(ws)
+        # and the matching call still works
+        preft.preft_schedule(ws, ss, sa, sp, tab.T, N, preft.PREFT_PREFILL_ONLY)
+        preft.preft_lora_apply(y, x, ss, sa, sp, Ap, Bp, r, 2.0, ready, ws)
+        torch.cuda.synchronize()
+        assert not torch.equal(bits(y), bits(y0))
+        preft.preft_schedule_counts(ws)
 
 
 def test_gpu_side_error_codes():
@@ -626,12 +752,13 @@ def test_packed_projections_reject_overlapping_outputs():
 # ---------------------------------------------------------------------------------------
 # small batches: several workgroups share a tile, each writes its share of the columns
 # ---------------------------------------------------------------------------------------
-@pytest.mark.parametrize("colsplit", [1, 2, 3, 5, 8, 16])
+@pytest.mark.parametrize("colsplit", [1, 2, 3, 5, 8, 15])
 @pytest.mark.parametrize("r,d_in,d_out", [(16, 512, 1024), (8, 1000, 264), (64, 512, 520), (4, 256, 128)])
 def test_column_split_over_workgroups(colsplit, r, d_in, d_out):
     from parity_util import run_lora_case
     N = 5
-    preft.preft_set_knob(preft.PREFT_KNOB_COLSPLIT, colsplit)
+    _set()
+    _set_colsplit(colsplit)
     tab = _mixed_table(700 + r, N, n_prompts=3, max_len=90, n_decode=12)
     pool = wl.lora_pool(N, r, d_in, d_out, "bf16", device="cuda", seed=71)
     x = wl.activations(tab.T, d_in, "bf16", device="cuda", seed=72)
@@ -645,7 +772,8 @@ def test_column_split_over_workgroups(colsplit, r, d_in, d_out):
 def test_column_split_with_packed_projections_and_in_place_calls(colsplit):
     """Packed outputs are split per output; DiReFT (in place) never splits a tile over workgroups."""
     from parity_util import run_direft_case
-    preft.preft_set_knob(preft.PREFT_KNOB_COLSPLIT, colsplit)
+    _set()
+    _set_colsplit(colsplit)
     for all_tokens in (False, True):
         worst = _packed_case("bf16", 16, 512, [512, 128, 264], True, 800 + colsplit, all_tokens, S=12, max_len=60)
         print(f"  colsplit={colsplit} packed all_tokens={all_tokens} worst {worst:.2e}")
@@ -916,7 +1044,7 @@ def test_randomised_shapes_ranks_pitches_and_modes(seed):
         scale = float(rng.choice([1.0, 0.5, 2.0, 0.37]))
         print(f"  case {case}: {dtype} r={r} {d_in}->{d_out} N={N} S={tab.S} T={tab.T} all={all_tokens} pad={pad}", flush=True)
         _set()
-        preft.preft_set_knob(preft.PREFT_KNOB_COLSPLIT, int(rng.integers(1, 9)) if rng.random() < 0.3 else 0)
+        _set_colsplit(int(rng.integers(1, 9)) if rng.random() < 0.3 else 0)
         pool = wl.lora_pool(N, r, d_in, d_out, dtype, device="cuda", seed=case)
         x = wl.activations(tab.T, d_in, dtype, device="cuda", seed=case + 1)
         y0 = wl.activations(tab.T, d_out, dtype, device="cuda", seed=case + 2)
@@ -930,6 +1058,6 @@ def test_randomised_shapes_ranks_pitches_and_modes(seed):
             run_direft_layers_case(tab, pools, hs, dtype, scale, all_tokens,
                                    [bool(rng.integers(0, 2)) for _ in range(L)], pad_cols=pad)
         done += 1
-    preft.preft_set_knob(preft.PREFT_KNOB_COLSPLIT, 0)
+    _set()
     assert done > 100
 
