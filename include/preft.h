@@ -114,8 +114,10 @@ enum {
     PREFT_EWORKSPACE   = -4,   /* workspace missing, misaligned or too small             */
     PREFT_EHIP         = -5,   /* the HIP runtime refused a launch, copy or allocation   */
     PREFT_ECAPACITY    = -6,   /* slot manager: more distinct adapters than slots        */
-    PREFT_ESCHEDULE    = -7    /* preft_schedule_counts: an apply call found a schedule  */
+    PREFT_ESCHEDULE    = -7,   /* preft_schedule_counts: an apply call found a schedule  */
                                /* built for another T, S, N or position set, and did nothing */
+    PREFT_ETOOLARGE    = -8    /* preft_direft_apply_static: the batch's schedule does   */
+                               /* not fit the static area                                */
 };
 
 #define PREFT_MAX_RANK 128
@@ -223,6 +225,32 @@ int preft_direft_apply(void *h, int64_t ldh, int32_t T, int32_t d,
                        const void *const *b_pool, int32_t N,
                        int32_t rank, float scale, int dtype, int mode,
                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * preft_direft_apply for callers that cannot allocate and have no workspace to hand over: code
+ * under HIP-graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation,
+ * same arguments and same results, bit for bit, as preft_direft_apply -- except that the schedule is
+ * kept in a static area of device memory inside the library (PREFT_STATIC_SCRATCH_BYTES bytes,
+ * which every GPU the library runs on holds until the process ends) instead of a caller workspace.
+ * The call allocates and frees nothing, on the host or the device.
+ *
+ * Limit: preft_workspace_bytes(T, S) <= PREFT_STATIC_SCRATCH_BYTES (every batch of up to 32 768
+ * rows, whatever S; T = 262 144 rows in up to 8192 segments), else PREFT_ETOOLARGE, checked
+ * before anything touches the device.
+ * All calls on one GPU share that GPU's area, which keeps the previous call's schedule: a call
+ * rewrites everything it reads from it (nothing there has to start at zero), and with
+ * PREFT_SCHEDULE_READY it reuses the schedule the previous static call on this GPU left, under the
+ * same T, S, N and position-set check as any apply call.  Two calls that overlap in time on one GPU
+ * (different streams, different threads) race on the area: order them.  The first call on a device
+ * looks up the area's address (no allocation); under graph capture make one call before capturing.
+ */
+#define PREFT_STATIC_SCRATCH_BYTES (1u << 20)
+int preft_direft_apply_static(void *h, int64_t ldh, int32_t T, int32_t d,
+                              const int32_t *seg_start, const int32_t *seg_adapter,
+                              const int32_t *seg_prefill_len, int32_t S,
+                              const void *const *W1_pool, const void *const *W2t_pool,
+                              const void *const *b_pool, int32_t N,
+                              int32_t rank, float scale, int dtype, int mode, void *stream);
 
 /*
  * DiReFT on n_layers residual streams in one launch: the paper intervenes at every layer

@@ -8,8 +8,8 @@ library has not been built (``python -m paper_2605_14217_amd.build``).
 from .binding import (  # noqa: F401
     PREFT_ALL_TOKENS, PREFT_PREFILL_ONLY, PREFT_SCHEDULE_READY, PREFT_BF16, PREFT_F32,
     PREFT_TEST_VARIANT, PREFT_TEST_WAVES, PREFT_TEST_ROWBLOCKS, PREFT_TEST_COLSPLIT, PREFT_TEST_RESIDENT,
-    test_flags, set_test_flags, PREFT_ESCHEDULE,
-    PreftError, load_library, pointer_table, preft_direft_apply, preft_direft_apply_layers, preft_lora_apply, preft_lora_apply_packed, preft_loreft_apply,
+    test_flags, set_test_flags, PREFT_ESCHEDULE, PREFT_ETOOLARGE, PREFT_STATIC_SCRATCH_BYTES,
+    PreftError, load_library, pointer_table, preft_direft_apply, preft_direft_apply_static, preft_direft_apply_layers, preft_lora_apply, preft_lora_apply_packed, preft_loreft_apply,
     preft_loreft_prepare, preft_schedule,
     preft_schedule_counts, preft_strerror, preft_version, preft_workspace_bytes,
     new_workspace, preft_slots_create, preft_slots_destroy, preft_slots_store, preft_slots_acquire,

@@ -21,6 +21,8 @@ PREFT_F32 = 0
 PREFT_BF16 = 1
 PREFT_ECAPACITY = -6
 PREFT_ESCHEDULE = -7
+PREFT_ETOOLARGE = -8
+PREFT_STATIC_SCRATCH_BYTES = 1 << 20
 
 
 def PREFT_TEST_VARIANT(v: int) -> int:
@@ -67,7 +69,7 @@ def _mode(mode: int) -> int:
 
 # every symbol include/preft.h declares
 ABI_SYMBOLS = ("preft_workspace_bytes", "preft_schedule", "preft_lora_apply", "preft_lora_apply_packed",
-               "preft_direft_apply", "preft_direft_apply_layers",
+               "preft_direft_apply", "preft_direft_apply_static", "preft_direft_apply_layers",
                "preft_loreft_prepare", "preft_loreft_apply", "preft_slots_create", "preft_slots_destroy",
                "preft_slots_store", "preft_slots_acquire", "preft_slots_pool", "preft_slots_resident",
                "preft_slots_stats", "preft_schedule_counts", "preft_strerror", "preft_version")
@@ -109,6 +111,9 @@ def load_library(path: Optional[str] = None):
     lib.preft_direft_apply.restype = c.c_int
     lib.preft_direft_apply.argtypes = [vp, i64, i32, i32, vp, vp, vp, i32, vp, vp, vp, i32, i32,
                                        c.c_float, c.c_int, c.c_int, vp, sz, vp]
+    lib.preft_direft_apply_static.restype = c.c_int
+    lib.preft_direft_apply_static.argtypes = [vp, i64, i32, i32, vp, vp, vp, i32, vp, vp, vp, i32, i32,
+                                              c.c_float, c.c_int, c.c_int, vp]
     lib.preft_direft_apply_layers.restype = c.c_int
     lib.preft_direft_apply_layers.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp, i32, vp, vp, vp, i32, i32,
                                               c.c_float, c.c_int, c.c_int, vp, sz, vp]
@@ -309,6 +314,25 @@ def preft_direft_apply(h: torch.Tensor, seg_start, seg_adapter, seg_prefill_len,
     matrices; W2t_pool: [d, rank] matrices (W2 transposed); b_pool: [rank] vectors or None."""
     _reft_apply("preft_direft_apply", h, seg_start, seg_adapter, seg_prefill_len, W1_pool, W2t_pool, b_pool, rank,
                 scale, mode, workspace, stream)
+
+
+def preft_direft_apply_static(h: torch.Tensor, seg_start, seg_adapter, seg_prefill_len,
+                              W1_pool: torch.Tensor, W2t_pool: torch.Tensor, b_pool: Optional[torch.Tensor],
+                              rank: int, scale: float, mode: int, stream=None) -> None:
+    """preft_direft_apply without a workspace: the schedule lives in the library's static device area
+    (for callers that cannot allocate).  The call itself allocates nothing."""
+    hp, ldh, T, d = _matrix(h, "h")
+    S = int(seg_adapter.numel())
+    N = int(W1_pool.numel())
+    if W2t_pool.numel() != N or (b_pool is not None and b_pool.numel() != N):
+        raise ValueError("pools must be pointer tables of equal length")
+    rc = load_library().preft_direft_apply_static(
+        hp, ldh, T, d,
+        _table(seg_start, "seg_start", S + 1), _table(seg_adapter, "seg_adapter", S),
+        _table(seg_prefill_len, "seg_prefill_len", S), S,
+        W1_pool.data_ptr(), W2t_pool.data_ptr(), None if b_pool is None else b_pool.data_ptr(), N,
+        int(rank), float(scale), _dtype_code(h), _mode(mode), _stream(stream))
+    _check(rc, "preft_direft_apply_static")
 
 
 def preft_direft_apply_layers(hs: Sequence[torch.Tensor], h_layers: torch.Tensor, seg_start, seg_adapter,

@@ -9,7 +9,15 @@
 #include "schedule.hpp"
 #include "valu_kernel.hpp"
 
+#include <mutex>
+
 static_assert(preft::PREFT_MAX_RANK_DEV == PREFT_MAX_RANK, "device and public rank limits differ");
+
+// Schedule area of preft_direft_apply_static: device memory that exists without any allocation call.
+// Each GPU the library runs on holds its own copy at its own address until the process ends.  In
+// host code the name below is only a stand-in for the symbol: the address a kernel can use comes
+// from hipGetSymbolAddress (static_scratch_of), once per device.
+static __device__ __align__(256) unsigned char scratch[PREFT_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -61,6 +69,26 @@ ScheduleView view_of(void *workspace, int64_t T, int64_t S)
     v.gtiles = reinterpret_cast<int4 *>(after_chunks);                  // 16-byte aligned
     v.shorts = reinterpret_cast<int2 *>(after_chunks + (size_t)v.short_cap * sizeof(int4));
     return v;
+}
+
+// Device address of this GPU's copy of `scratch` (looked up on the first call per device, with that
+// device current; no allocation).
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[MAX_DEVICES] = {};
+
+int static_scratch_of(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return PREFT_EHIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return PREFT_EHIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return PREFT_OK;
 }
 
 int check_launch()
@@ -618,6 +646,27 @@ int preft_direft_apply(void *h, int64_t ldh, int32_t T, int32_t d, const int32_t
                          workspace, stream);
 }
 
+int preft_direft_apply_static(void *h, int64_t ldh, int32_t T, int32_t d, const int32_t *seg_start,
+                              const int32_t *seg_adapter, const int32_t *seg_prefill_len, int32_t S,
+                              const void *const *W1_pool, const void *const *W2t_pool, const void *const *b_pool,
+                              int32_t N, int32_t rank, float scale, int dtype, int mode, void *stream)
+{
+    // sizes first (host arithmetic only): the schedule of this batch must fit the static area
+    if (T < 0 || S < 0) return PREFT_EINVAL;
+    if (workspace_bytes(T, S) > (size_t)PREFT_STATIC_SCRATCH_BYTES) return PREFT_ETOOLARGE;
+    if (dtype != PREFT_F32 && dtype != PREFT_BF16) return PREFT_EINVAL;
+    if (T == 0 || S == 0) {     // nothing to do: same answers as preft_direft_apply, without touching the device
+        const int rc = check_tables(nullptr, 0, seg_start, seg_adapter, seg_prefill_len, S, T, N, mode);
+        if (rc != PREFT_OK) return rc;
+        return (rank < 1 || rank > PREFT_MAX_RANK) ? PREFT_EUNSUPPORTED : PREFT_OK;
+    }
+    void *area = nullptr;
+    const int rc = static_scratch_of(&area);
+    if (rc != PREFT_OK) return rc;
+    return preft_direft_apply(h, ldh, T, d, seg_start, seg_adapter, seg_prefill_len, S, W1_pool, W2t_pool, b_pool, N,
+                              rank, scale, dtype, mode, area, (size_t)PREFT_STATIC_SCRATCH_BYTES, stream);
+}
+
 int preft_direft_apply_layers(void *const *h_layers, int64_t ldh, int32_t n_layers, int32_t T, int32_t d,
                               const int32_t *seg_start, const int32_t *seg_adapter,
                               const int32_t *seg_prefill_len, int32_t S, const void *const *const *W1_pools,
@@ -666,6 +715,7 @@ const char *preft_strerror(int code)
     case PREFT_EWORKSPACE:   return "workspace missing, misaligned or smaller than preft_workspace_bytes(T, S)";
     case PREFT_EHIP:         return "HIP runtime error (launch, copy or allocation)";
     case PREFT_ECAPACITY:    return "more distinct adapters in one batch than the slot manager has slots";
+    case PREFT_ETOOLARGE:    return "batch too large for the static schedule area of preft_direft_apply_static (preft_workspace_bytes(T, S) exceeds PREFT_STATIC_SCRATCH_BYTES)";
     case PREFT_ESCHEDULE:    return "an apply call named another T, S, N or position set than the schedule in its workspace was built for; that call did nothing";
     default:                 return "unknown preft error code";
     }

@@ -129,6 +129,20 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert direft(h=None) == -1
     assert direft(W2=None) == -1
     assert direft(wsb=0) == -4
+
+    def static(T=64, S=4, dtype=preft.PREFT_BF16, rank=4, mode=0, tables=fake):
+        return lib.preft_direft_apply_static(fake, 64, T, 64, tables, tables, tables, S, fake, fake, None, 2, rank,
+                                             1.0, dtype, mode, None)
+
+    # the allocation-free entry point checks its size limit on the host, before anything else
+    assert preft.preft_workspace_bytes(262144, 8192) <= preft.PREFT_STATIC_SCRATCH_BYTES
+    assert preft.preft_workspace_bytes(32768, 1 << 20) <= preft.PREFT_STATIC_SCRATCH_BYTES
+    assert static(T=10_000_000, S=100_000) == preft.PREFT_ETOOLARGE == -8
+    assert static(T=70_000, S=70_000) == -8
+    assert static(T=-1) == -1 and static(S=-1) == -1
+    assert static(T=0) == 0 and static(S=0) == 0
+    assert static(T=0, rank=0) == -2 and static(T=0, mode=2) == -1
+    assert static(dtype=7) == -1
     assert lib.preft_schedule(fake, ws_bytes, fake, fake, fake, 4, 64, 2, preft.PREFT_SCHEDULE_READY, None) == -1
     assert lib.preft_schedule(fake, 8, fake, fake, fake, 4, 64, 2, 0, None) == -4
 
