@@ -295,6 +295,25 @@ void launch_mfma_packed(const ApplyArgs &a, int64_t S, const Knobs &k, hipStream
                            stream, a);
 }
 
+// packed projections at rank 32..64 (widths multiples of 128): the row-split kernel with one sweep
+// over x for all outputs.  It takes the chunks; the gathered tiles (all-token mode: decode rows)
+// go to one launch of the column-split kernel per output.
+template <int NB>
+void launch_mfma_wide_packed(const ApplyArgs &a, int n_proj, int64_t S, hipStream_t stream)
+{
+    void (*kernel)(ApplyArgs) = n_proj == 2 ? mfma_wide_kernel<NB, 1, 4, false, 2> : mfma_wide_kernel<NB, 1, 4, false, 3>;
+    hipLaunchKernelGGL(kernel, dim3(chunk_grid(a, S, 64)), dim3(256), 0, stream, a);
+    for (int i = 0; i < n_proj; ++i) {
+        ApplyArgs g = a;
+        if (i > 0) {
+            g.y = a.more[i - 1].y; g.ldy = a.more[i - 1].ldy; g.d_out = a.more[i - 1].d_out;
+            g.A_pool = a.more[i - 1].A_pool; g.Bt_pool = a.more[i - 1].Bt_pool;
+        }
+        g.gathered_only = 1;
+        launch_mfma_stream<NB, false>(g, S, 1, 4, stream);
+    }
+}
+
 template <bool DIREFT>
 void launch_mfma_rank(const ApplyArgs &a, int64_t S, const Knobs &k, hipStream_t stream)
 {
@@ -563,7 +582,11 @@ int preft_lora_apply_packed(int32_t n_proj, void *const *y, const int64_t *ldy, 
                             (k.variant == 0 || k.variant == 3);
     const bool fused_valu = n_proj > 1 && dtype == PREFT_BF16 && rank <= 3 && (k.variant == 0 || k.variant == 2) &&
                             (k.waves == 0 || k.waves == 4);
-    const bool fused = fused_mfma || fused_valu;
+    bool fused_wide = n_proj > 1 && dtype == PREFT_BF16 && rank > 16 && rank <= 64 && (rank % 4) == 0 &&
+                      (k.variant == 0 || k.variant == 4) && k.waves == 0 && k.rowblocks == 0 && (d_in % 128) == 0 &&
+                      choose_col_split(T, k) == 1;
+    for (int32_t i = 0; i < n_proj && fused_wide; ++i) fused_wide = (d_out[i] % 128) == 0;
+    const bool fused = fused_mfma || fused_valu || fused_wide;
     if (!fused) {                                  // same result, one launch per projection
         for (int32_t i = 0; i < n_proj; ++i) {
             rc = preft_lora_apply(y[i], ldy[i], x, ldx, T, d_in, d_out[i], seg_start, seg_adapter, seg_prefill_len, S,
@@ -580,7 +603,10 @@ int preft_lora_apply_packed(int32_t n_proj, void *const *y, const int64_t *ldy, 
         a.more[i - 1].y = y[i]; a.more[i - 1].ldy = ldy[i]; a.more[i - 1].d_out = d_out[i];
         a.more[i - 1].A_pool = A_pools[i]; a.more[i - 1].Bt_pool = B_pools[i];
     }
-    if (fused_mfma) {
+    if (fused_wide) {
+        if (rank <= 32) launch_mfma_wide_packed<2>(a, n_proj, S, st);
+        else            launch_mfma_wide_packed<4>(a, n_proj, S, st);
+    } else if (fused_mfma) {
         a.col_split = choose_col_split(T, k);
         if (n_proj == 2) launch_mfma_packed<2>(a, S, k, st);
         else             launch_mfma_packed<3>(a, S, k, st);

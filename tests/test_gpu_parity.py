@@ -661,13 +661,14 @@ def test_loreft_prepare_rejects_bad_arguments():
 # ---------------------------------------------------------------------------------------
 # packed projections: several LoRA outputs from one x
 # ---------------------------------------------------------------------------------------
-def _packed_case(dtype, r, d_in, d_outs, fused_buffer, seed, all_tokens, S=30, max_len=150):
+def _packed_case(dtype, r, d_in, d_outs, fused_buffer, seed, all_tokens, S=30, max_len=150, min_rows=0):
     from oracle import preft_oracle as ora
     from parity_util import bits, compare, dev_tables, lora_pools_to_device
     N = 5
     rng = np.random.Generator(np.random.PCG64(seed))
     tab = wl.random_segments(rng, S, N + 1, max_len)
     T = tab.T
+    assert T >= min_rows, f"the case needs at least {min_rows} rows, the table has {T}"
     x = wl.activations(T, d_in, dtype, device="cuda", seed=seed + 1)
     pools = [wl.lora_pool(N, r, d_in, n, dtype, device="cuda", seed=seed + 10 + i) for i, n in enumerate(d_outs)]
     if fused_buffer:            # one [T, sum d_out (+ padding)] buffer, outputs are column ranges of it
@@ -705,7 +706,7 @@ def _packed_case(dtype, r, d_in, d_outs, fused_buffer, seed, all_tokens, S=30, m
     ("bf16", 8, 1000, (264, 520), False),            # widths with 32- and 8-column tails, separate buffers
     ("bf16", 4, 256, (256, 256, 256), False),
     ("bf16", 16, 4096, (4096, 1024, 1024), True),    # Llama-3.1-8B q, k, v
-    ("bf16", 32, 512, (512, 128), True),             # rank above the fused path: one launch per projection
+    ("bf16", 32, 512, (512, 136), True),             # rank 32 with a width the row-split kernel does not take: one launch each
     ("bf16", 3, 512, (512, 128, 128), False),        # ranks 1..3: fused by the vector-ALU kernel
     ("bf16", 1, 4096, (4096, 1024, 1024), True),
     ("bf16", 2, 520, (1408, 264), False),
@@ -717,6 +718,53 @@ def test_packed_projections_match_the_oracle(dtype, r, d_in, d_outs, fused_buffe
     for all_tokens in (False, True):
         worst = _packed_case(dtype, r, d_in, list(d_outs), fused_buffer, 300 + r, all_tokens)
         print(f"  packed {dtype} r={r} {d_in}->{d_outs} fused_buffer={fused_buffer} all_tokens={all_tokens} worst {worst:.2e}")
+
+
+@pytest.mark.parametrize("r,d_in,d_outs,fused_buffer", [
+    (32, 512, (512, 128, 128), True), (64, 1024, (1024, 128, 128), False), (64, 256, (1536, 1536), True),
+    (48, 384, (128, 256), False), (20, 128, (256, 128, 384), True), (64, 8192, (1024, 1024), False),
+])
+def test_packed_projections_in_the_row_split_kernel(r, d_in, d_outs, fused_buffer):
+    """Rank 20..64 with widths that are multiples of 128 on a batch of more than 1024 rows: one launch
+    of the row-split kernel reads x once for all outputs (chunks); decode rows of the all-token mode
+    take the column-split kernel per output."""
+    for all_tokens in (False, True):
+        worst = _packed_case("bf16", r, d_in, list(d_outs), fused_buffer, 500 + r, all_tokens, S=70, max_len=220,
+                             min_rows=1025)
+        print(f"  packed r={r} {d_in}->{d_outs} fused_buffer={fused_buffer} all_tokens={all_tokens} worst {worst:.2e}")
+
+
+@pytest.mark.parametrize("rank,d_in,d_outs", [(32, 256, (256, 128, 128)), (64, 128, (384, 128)), (64, 384, (128, 128, 256))])
+def test_packed_row_split_kernel_gives_the_exactly_rounded_result(rank, d_in, d_outs):
+    """Small-integer data (every product and sum exact on both sides): the packed launch must equal
+    the oracle's result rounded once to bf16, bit for bit, on every output."""
+    from oracle import preft_oracle as ora
+    from parity_util import dev_tables
+    N = 4
+    gen = torch.Generator(device="cpu").manual_seed(rank * 100 + d_in)
+    ints = lambda shape, lo, hi: torch.randint(lo, hi + 1, shape, generator=gen).to(torch.bfloat16).cuda()
+    tab = _mixed_table(rank + d_in, N, n_prompts=8, max_len=400, n_decode=30)
+    T = tab.T
+    assert T > 1024
+    ss, sa, sp = dev_tables(tab)
+    ws = preft.new_workspace(T, tab.S)
+    x = ints((T, d_in), -2, 2)
+    A = [[ints((rank, d_in), -1, 1) for _ in range(N)] for _ in d_outs]
+    B = [[ints((n, rank), -1, 1) for _ in range(N)] for n in d_outs]
+    y0s = [ints((T, n), -3, 3) for n in d_outs]
+    for mode, pos in ((preft.PREFT_ALL_TOKENS, ora.ALL_POSITIONS), (preft.PREFT_PREFILL_ONLY, ora.PROMPT_ONLY)):
+        row_adapter = ora.positions(T, tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, N, pos)
+        ys = [y.clone() for y in y0s]
+        preft.preft_lora_apply_packed(ys, x, ss, sa, sp, [preft.pointer_table(a) for a in A],
+                                      [preft.pointer_table(b) for b in B], rank, 0.5, mode, ws)
+        torch.cuda.synchronize()
+        for i in range(len(d_outs)):
+            want = ora.lora(y0s[i].cpu(), x.cpu(), tab.seg_start, tab.seg_adapter, tab.seg_prefill_len,
+                            [a.cpu() for a in A[i]], [b.cpu() for b in B[i]], rank, 0.5, pos)
+            assert np.abs(want).max() < 2 ** 15
+            rounded = torch.from_numpy(want).to(torch.float32).to(torch.bfloat16)
+            _same_bits(ys[i].cpu(), rounded, want, row_adapter, f"packed row-split output {i}")
+            assert (ys[i].cpu() != y0s[i].cpu()).any()
 
 
 def test_packed_projections_reject_overlapping_outputs():
