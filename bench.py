@@ -1,27 +1,34 @@
 #!/usr/bin/env python3
 """Benchmark of the prefill-only adapter-apply hot path on one MI355X.
 
-A "step" is one pass of the whole path over one synthetic batch of the Llama-3.1-8B LoRA
-configuration (32 prompts of U[256,2048] rows + 224 decode rows, 64 adapters, bf16):
+A "step" is one pass of the whole path over one synthetic batch: the adapter work of one decoder
+layer on that batch,
 
     1 x token-segment scheduler                              (preft_schedule)
-    7 x segmented multi-adapter LoRA, rank R, prefill-only   (q, k, v, o, gate, up, down)
-    1 x segmented multi-adapter DiReFT, rank R, prefill-only (residual stream d = 4096)
+    7 x segmented multi-adapter LoRA, rank R, prefill-only   (q, k, v, o, gate, up, down; q,k,v and
+                                                              gate,up go out as packed launches)
+    1 x segmented multi-adapter DiReFT, rank R, prefill-only (the residual stream)
 
-i.e. the adapter work of one decoder layer on that batch.  Every projection has its own
-activation buffers (about 6 GB per step in total), so every launch streams cold data from HBM;
-adapter weights are warm (steady-state serving).  `value` = active (prefill) rows per second
-through the step.
+The default workload is the largest single-GPU configuration, `llama70b_lora` (512 prompts with
+lognormal lengths + 3584 decode rows, 512 adapters, unsharded Llama-3.1-70B layer shapes, bf16) at
+its heaviest rank, 64.  Every projection has its own activation buffers (about 100 GB in total),
+so every launch streams cold data from HBM; adapter weights are warm (steady-state serving).
+`value` = active (prompt) rows per second through the step.  Rows are laid out densely (row pitch
+= width); `--pitch pow2` pads wide rows to the next power of two, which this chip streams faster.
 
-The same JSON line also carries: the HBM roofline of the dominant kernel (the LoRA tile kernel,
-timed per launch with HIP events on the launch stream inside the timed region), the all-token
-(conventional PEFT) time for the same batch, the batch's decode rows alone as a decode-only
-step in both modes, and the CPU oracle timed on a sample of the same batch.
+The same JSON line carries: the HBM roofline of the dominant kernel (timed per launch with HIP
+events on the launch stream inside the timed region; median over the steps), the all-token
+(conventional PEFT) time of the same batch, the batch's decode rows alone as a decode-only step in
+both modes, DiReFT at every layer, a serving-trace replay, the CPU oracle timed on a sample of the
+same batch, and -- each measured in a short child process of this same script -- the same step on
+the other configurations (`llama8b_lora` rank 16, `llama8b_direft` rank 16, `skewed70b` rank 32),
+at the configuration's other ranks and with the power-of-two row pitch.
 """
 import argparse
+import hashlib
 import json
-import math
 import os
+import subprocess
 import sys
 import time
 
@@ -30,32 +37,49 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E, published
+METRIC = "prefill tokens/s through multi-adapter LoRA/DiReFT apply; % of peak HBM GB/s"
+DEFAULT_RANK = {"llama70b_lora": 64, "llama8b_lora": 16, "llama8b_direft": 16, "skewed70b": 32, "tiny": 4}
+TRAFFIC_PROFILE = os.path.join("profiles", "lora_row_split_kernel_llama70b_rank64_hbm_traffic.txt")
 
 
-def main():
+def kernel_sources_sha256():
+    """Hash of the kernel sources: a committed counter summary applies to the kernels it was taken from."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2605_14217_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hpp", ".hip")):
+            h.update(name.encode())
+            with open(os.path.join(csrc, name), "rb") as f:
+                h.update(f.read())
+    return h.hexdigest()
+
+
+def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--rank", type=int, default=16, help="adapter rank (the configuration lists 1, 8, 16)")
-    ap.add_argument("--config", default="llama8b_lora")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="llama70b_lora")
+    ap.add_argument("--rank", type=int, default=0, help="adapter rank (0: the configuration's heaviest)")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--pitch", choices=["dense", "pow2"], default="dense",
+                    help="row pitch of the activation buffers: their width (default) or the next power of two "
+                         "(28672-wide rows every 32768 elements; measured 5-10 %% faster on MI355X)")
+    ap.add_argument("--sub", action="store_true",
+                    help="short form used for the child processes: main measurement, all-token and decode-only legs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extras", action="store_true", help="skip the all-token / decode-only legs")
+    ap.add_argument("--no-extras", action="store_true", help="only the timed region (what the rocprofv3 summaries profile)")
+    ap.add_argument("--no-children", action="store_true", help="skip the other configurations, ranks and row pitch")
+    ap.add_argument("--no-trace", action="store_true", help="skip the serving-trace replay leg")
+    ap.add_argument("--no-packed", action="store_true",
+                    help="one launch per projection instead of packed q,k,v and gate,up launches")
+    ap.add_argument("--only", default="", help="experiment: comma-separated subset of projections")
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--waves", type=int, default=0)
     ap.add_argument("--rowblocks", type=int, default=0)
-    ap.add_argument("--colsplit", type=int, default=0, help="workgroups per tile on small batches (0: automatic)")
+    ap.add_argument("--colsplit", type=int, default=0)
+    ap.add_argument("--resident", type=int, default=0)
     ap.add_argument("--ldpad", type=int, default=0, help="experiment: extra elements of row stride on every buffer")
-    ap.add_argument("--pitch", choices=["dense", "pow2"], default="pow2",
-                    help="row pitch of the activation buffers: the next power of two (default: 14336-wide rows "
-                         "every 16384 elements, measured 7-10 %% faster on MI355X) or their width")
-    ap.add_argument("--only", default="", help="experiment: comma-separated subset of projections")
-    ap.add_argument("--no-packed", action="store_true",
-                    help="one launch per projection instead of packed q,k,v and gate,up launches")
-    ap.add_argument("--no-trace", action="store_true", help="skip the serving-trace replay leg")
-    ap.add_argument("--no-other-ranks", action="store_true",
-                    help="skip the short runs at the configuration's other ranks")
     ap.add_argument("--trace-requests", type=int, default=1000)
     ap.add_argument("--trace-batch", type=int, default=32)
     ap.add_argument("--trace-adapters", type=int, default=32)
@@ -63,13 +87,17 @@ def main():
     ap.add_argument("--trace-slots", type=int, default=0,
                     help="serve the trace through the adapter slot manager with this many device slots "
                          "(0: every adapter resident); --trace-adapters may then exceed the configuration's pool")
-    args = ap.parse_args()
+    ap.add_argument("--cpu-rows-per-segment", type=int, default=32,
+                    help="random rows per prompt in the sample the CPU oracle is timed on")
+    return ap.parse_args()
 
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU only (the path has no cross-GPU step); run with --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
 
+def experiment_flags(args):
+    return bool(args.variant or args.waves or args.rowblocks or args.colsplit or args.resident or args.ldpad or args.only
+                or args.no_packed)
+
+
+def run(args):
     import numpy as np
     import torch
 
@@ -81,12 +109,13 @@ def main():
         sys.exit(2)
     preft.load_library()
     preft.set_test_flags(preft.test_flags(variant=args.variant, waves=args.waves, rowblocks=args.rowblocks,
-                                          colsplit=args.colsplit))
+                                          colsplit=args.colsplit, resident=args.resident))
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
     cfg = wl.CONFIGS[args.config]
-    N, r, d_res = cfg["N"], args.rank, cfg["direft_d"]
+    r = args.rank or DEFAULT_RANK[args.config]
+    N, d_res = cfg["N"], cfg["direft_d"]
     scale = cfg["lora_scale"]
     tab = wl.make_segments(args.config, seed=args.seed)
     T, S = tab.T, tab.S
@@ -97,16 +126,19 @@ def main():
 
     # ---- buffers and pools --------------------------------------------------------------
     projs = []
+
     def act(T_, d_, seed_):
-        t = wl.activations(T_, d_, "bf16", device=dev, seed=seed_)
         pitch = d_ + args.ldpad
         if args.pitch == "pow2":                       # row pitch = next power of two (a caller's layout choice)
             pitch = 1 << (d_ - 1).bit_length()
         if pitch != d_:
-            buf = torch.empty((T_, pitch), dtype=t.dtype, device=dev)
-            buf[:, :d_].copy_(t)
+            buf = torch.empty((T_, pitch), dtype=torch.bfloat16, device=dev)
+            step_rows = max(1, (1 << 28) // pitch)     # filled piecewise: no second full-size temporary
+            for lo in range(0, T_, step_rows):
+                hi = min(T_, lo + step_rows)
+                buf[lo:hi, :d_].copy_(wl.activations(hi - lo, d_, "bf16", device=dev, seed=seed_ * 131 + lo))
             return buf[:, :d_]
-        return t
+        return wl.activations(T_, d_, "bf16", device=dev, seed=seed_)
 
     for i, (name, (d_in, d_out)) in enumerate(cfg["lora_shapes"].items()):
         if args.only and name not in args.only.split(","):
@@ -126,10 +158,10 @@ def main():
     direft_scale = 1.0
 
     # launches of a step: projections that read the same x (q,k,v; gate,up) go out as one packed call
-    # (the library fuses such a call into one launch for rank 1-4, 8, 12, 16; other ranks stay one
-    # call and one launch per projection, accounted per projection)
+    # (one launch that reads x once for bf16 ranks 1-4, 8, 12, 16 and, widths being multiples of 128,
+    # 20-64; other ranks stay one call that issues one launch per projection)
     packs = {"q": "qkv", "k": "qkv", "v": "qkv", "gate": "gate_up", "up": "gate_up"}
-    packed = not args.no_packed and (r <= 3 or (r % 4 == 0 and r <= 16))
+    packed = not args.no_packed and (r <= 3 or (r % 4 == 0 and r <= 64))
     groups = []
     for p in projs:
         key = packs.get(p["name"]) if packed else None
@@ -139,7 +171,6 @@ def main():
             groups.append(dict(key=key, members=[p]))
     for g_ in groups:
         g_["name"] = "+".join(m["name"] for m in g_["members"])
-
     singles = [dict(key=None, members=[p], name=p["name"]) for p in projs]
 
     def step(mode, tables=(ss, sa, sp), T_=T, events=None, groups=groups, pools=None):
@@ -191,49 +222,55 @@ def main():
     ms_per_step = (time.perf_counter() - t0) / K * 1e3
     counts = preft.preft_schedule_counts(ws)
 
-    per_launch_ms = np.array([[a.elapsed_time(b) for (a, b) in evk] for evk in ev])     # [K, 8]
-    mean_ms = per_launch_ms.mean(axis=0)
-    breakdown = {}
+    per_launch_ms = np.array([[a.elapsed_time(b) for (a, b) in evk] for evk in ev])     # [K, launches]
+    med_ms = np.median(per_launch_ms, axis=0)             # median over the K timed steps
+    breakdown, launch_bytes = {}, {}
     lora_b, lora_t = 0.0, 0.0
     for i, g_ in enumerate(groups):
         m = g_["members"]
         # x once per launch, every output read and written once, every distinct adapter's factors once
         b = wl.lora_algorithmic_bytes(T_act, m[0]["d_in"], [q["d_out"] for q in m], r, n_ad)
-        breakdown[g_["name"]] = dict(us=round(mean_ms[i] * 1e3, 2), GBps=round(b / mean_ms[i] / 1e6, 1),
-                                     frac=round(b / mean_ms[i] / 1e6 / PEAK_HBM_GBPS, 4))
+        launch_bytes[g_["name"]] = b
+        breakdown[g_["name"]] = dict(us=round(med_ms[i] * 1e3, 2), GBps=round(b / med_ms[i] / 1e6, 1),
+                                     frac=round(b / med_ms[i] / 1e6 / PEAK_HBM_GBPS, 4))
         lora_b += b
-        lora_t += mean_ms[i]
+        lora_t += med_ms[i]
     db = wl.direft_algorithmic_bytes(T_act, d_res, r, n_ad)
-    breakdown["direft"] = dict(us=round(mean_ms[-1] * 1e3, 2), GBps=round(db / mean_ms[-1] / 1e6, 1),
-                               frac=round(db / mean_ms[-1] / 1e6 / PEAK_HBM_GBPS, 4))
-    if projs:
-        achieved = lora_b / lora_t / 1e6                                                 # GB/s
-        roofline = dict(bound="hbm", kernel=f"lora tile kernel ({len(groups)} launches per step: "
-                                            + ",".join(g_["name"] for g_ in groups) + ")",
-                        achieved=round(achieved, 1), peak=PEAK_HBM_GBPS, unit="GB/s",
-                        frac=round(achieved / PEAK_HBM_GBPS, 4), traffic=None,
-                        bytes_per_launch=int(lora_b / len(groups)), us_per_launch=round(lora_t / len(groups) * 1e3, 2))
-    else:
-        achieved = db / mean_ms[-1] / 1e6
-        roofline = dict(bound="hbm", kernel="direft tile kernel (1 launch per step)",
-                        achieved=round(achieved, 1), peak=PEAK_HBM_GBPS, unit="GB/s",
-                        frac=round(achieved / PEAK_HBM_GBPS, 4), traffic=None,
-                        bytes_per_launch=int(db), us_per_launch=round(mean_ms[-1] * 1e3, 2))
+    launch_bytes["direft"] = db
+    breakdown["direft"] = dict(us=round(med_ms[-1] * 1e3, 2), GBps=round(db / med_ms[-1] / 1e6, 1),
+                               frac=round(db / med_ms[-1] / 1e6 / PEAK_HBM_GBPS, 4))
+    # the dominant kernel: the launch that takes the largest share of the step
+    names = [g_["name"] for g_ in groups] + ["direft"]
+    dom = names[int(np.argmax(med_ms))]
+    achieved = launch_bytes[dom] / (breakdown[dom]["us"] * 1e-6) / 1e9
+    roofline = dict(bound="hbm", kernel=f"the {dom} launch" + (" (packed: one read of x)" if "+" in dom else ""),
+                    achieved=round(achieved, 1), peak=PEAK_HBM_GBPS, unit="GB/s", frac=round(achieved / PEAK_HBM_GBPS, 4),
+                    traffic=None, bytes_per_launch=int(launch_bytes[dom]), us_per_launch=breakdown[dom]["us"],
+                    timing="median of the timed steps, HIP events on the launch stream")
+    lora_frac = round(lora_b / lora_t / 1e6 / PEAK_HBM_GBPS, 4) if projs else None
 
-    # HBM traffic of the dominant kernel comes from two rocprofv3 --pmc runs of this same command;
-    # their summary is committed under profiles/ and quoted here when the configuration matches.
-    if projs and args.config == "llama8b_lora" and r == 16 and args.pitch == "pow2" and not (
-            args.variant or args.waves or args.rowblocks or args.ldpad or args.only or not packed):
+    # HBM traffic of the dominant kernel: two rocprofv3 --pmc runs of this same command, summarised under
+    # profiles/.  A quoted figure, not one of this run: it is attached only while the kernel sources are
+    # the ones the counters were taken from (hash recorded in the summary).
+    if args.config == "llama70b_lora" and r == 64 and args.pitch == "dense" and not experiment_flags(args):
         try:
-            with open(os.path.join(ROOT, "profiles", "lora_tile_kernel_llama8b_rank16_hbm_traffic.txt")) as f:
+            fields = {}
+            with open(os.path.join(ROOT, TRAFFIC_PROFILE)) as f:
                 for line in f:
-                    if line.startswith("traffic_bytes_per_launch"):
-                        roofline["traffic"] = int(line.split("=")[1])
-        except OSError:
+                    key = line.split("=")[0].strip()
+                    if "=" in line and key in ("traffic_bytes_per_launch", "kernel_sources_sha256", "launch"):
+                        fields[key] = line.split("=", 1)[1].strip()
+            if fields.get("kernel_sources_sha256") == kernel_sources_sha256() and fields.get("launch") == dom:
+                roofline["traffic"] = int(fields["traffic_bytes_per_launch"])
+                roofline["traffic_source"] = (TRAFFIC_PROFILE + ": rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
+                                              "command on these kernel sources (quoted, not measured in this run)")
+            else:
+                roofline["traffic_source"] = TRAFFIC_PROFILE + " was taken from other kernel sources: not quoted"
+        except (OSError, ValueError, KeyError):
             pass
 
     out = {
-        "metric": "prefill tokens/s through multi-adapter LoRA/DiReFT apply; % of peak HBM GB/s",
+        "metric": METRIC,
         "value": round(T_act / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
@@ -243,128 +280,104 @@ def main():
                                f"+ DiReFT d={d_res}, rank {r}, prefill-only",
                    "T": T, "S": S, "active_rows": T_act, "decode_rows": int(T - T_act), "adapters": N,
                    "distinct_active_adapters": n_ad, "rank": r, "seed": args.seed,
-                   "row_pitch": ("next power of two (rows of 14336 or 28672 elements start every 16384 or 32768; "
-                                 "the padding is never touched)" if args.pitch == "pow2" else "dense")
-                                + (f" + {args.ldpad}" if args.ldpad else ""),
+                   "row_pitch": ("dense (row pitch = width)" if args.pitch == "dense" else
+                                 "next power of two (rows of 14336 or 28672 elements start every 16384 or 32768; "
+                                 "the padding is never touched)") + (f" + {args.ldpad}" if args.ldpad else ""),
                    "schedule": {"chunks": counts[0], "short_rows": counts[1]}},
         "roofline": roofline,
         "pct_peak_hbm": round(100 * achieved / PEAK_HBM_GBPS, 2),
+        "lora_launches_frac": lora_frac,
         "breakdown": breakdown,
     }
+    if args.no_extras:
+        return out, None
 
     # ---- practical ceiling: a plain device copy ------------------------------------------------
-    src = wl.activations(T, 14336, "bf16", device=dev, seed=1)
+    src = wl.activations(min(T, 65536), 14336, "bf16", device=dev, seed=1)
     dst = torch.empty_like(src)
     ms = timed(lambda: dst.copy_(src), 20, 3)
     out["copy_GBps"] = round(2 * src.numel() * 2 / ms / 1e6, 1)
     out["copy_bytes_each_way"] = int(src.numel() * 2)       # known size: calibrates the HBM byte counters
-    del dst
+    del dst, src
 
     # ---- conventional baseline and the decode-only step ----------------------------------------
-    if not args.no_extras:
-        ms_all = timed(lambda: step(preft.PREFT_ALL_TOKENS), max(5, K // 4), 3)
-        dec = tab.decode_only()
-        dt = tuple(torch.from_numpy(a.copy()).to(dev) for a in (dec.seg_start, dec.seg_adapter, dec.seg_prefill_len))
-        def graphed(mode):                 # one engine step as a HIP graph: no host launch gaps
+    n_light = max(3, K // 4)
+    ms_all = timed(lambda: step(preft.PREFT_ALL_TOKENS), n_light, 2)
+    dec = tab.decode_only()
+    dt = tuple(torch.from_numpy(a.copy()).to(dev) for a in (dec.seg_start, dec.seg_adapter, dec.seg_prefill_len))
+
+    def graphed(mode):                 # one engine step as a HIP graph: no host launch gaps
+        step(mode, dt, dec.T)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
             step(mode, dt, dec.T)
-            torch.cuda.synchronize()
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g):
-                step(mode, dt, dec.T)
-            return g
-        g_all, g_pre = graphed(preft.PREFT_ALL_TOKENS), graphed(preft.PREFT_PREFILL_ONLY)
-        ms_dec_all = timed(g_all.replay, 50, 5)
-        ms_dec_pre = timed(g_pre.replay, 50, 5)
-        out["all_token"] = {"ms_per_step": round(ms_all, 4), "speedup_prefill_only": round(ms_all / ms_per_step, 4)}
-        if len(groups) != len(singles):
-            ms_single = timed(lambda: step(preft.PREFT_PREFILL_ONLY, groups=singles), max(5, K // 4), 3)
-            out["one_launch_per_projection"] = {"ms_per_step": round(ms_single, 4),
-                                                "speedup_packed": round(ms_single / ms_per_step, 4)}
-        out["decode_only_step"] = {"rows": dec.T, "all_token_ms": round(ms_dec_all, 4),
-                                   "prefill_only_ms": round(ms_dec_pre, 4),
-                                   "speedup_prefill_only": round(ms_dec_all / ms_dec_pre, 2)}
+        return g
+    g_all, g_pre = graphed(preft.PREFT_ALL_TOKENS), graphed(preft.PREFT_PREFILL_ONLY)
+    ms_dec_all = timed(g_all.replay, 50, 5)
+    ms_dec_pre = timed(g_pre.replay, 50, 5)
+    out["all_token"] = {"ms_per_step": round(ms_all, 4), "speedup_prefill_only": round(ms_all / ms_per_step, 4)}
+    if len(groups) != len(singles):
+        ms_single = timed(lambda: step(preft.PREFT_PREFILL_ONLY, groups=singles), n_light, 2)
+        out["one_launch_per_projection"] = {"ms_per_step": round(ms_single, 4),
+                                            "speedup_packed": round(ms_single / ms_per_step, 4)}
+    out["decode_only_step"] = {"rows": dec.T, "all_token_ms": round(ms_dec_all, 4),
+                               "prefill_only_ms": round(ms_dec_pre, 4),
+                               "speedup_prefill_only": round(ms_dec_all / ms_dec_pre, 2)}
+    if args.sub:
+        return out, None
 
     # ---- DiReFT at every layer (App. A.2): L residual streams, one call per layer or one call for all ----
-    if not args.no_extras:
-        L = int(max(2, min(32, 48e9 // (T * d_res * 2))))
-        hs = [h] + [h.clone() for _ in range(L - 1)]
-        per_layer = [(W1p, W2tp, bp)]
-        keep = []
-        for _ in range(L - 1):                      # every layer has factors of its own (distinct memory)
-            mats = [[m.clone() for m in group] for group in (W1, W2t, bb)]
-            keep.append(mats)
-            per_layer.append(tuple(preft.pointer_table(g_) for g_ in mats))
-        as_table = lambda ptrs: torch.tensor(ptrs, dtype=torch.int64, device=dev)
-        h_tab = preft.pointer_table(hs)
-        W1s, W2s, bs = (as_table([pl[i].data_ptr() for pl in per_layer]) for i in range(3))
+    L = int(max(2, min(32, 48e9 // (T * d_res * 2))))
+    hs = [h] + [h.clone() for _ in range(L - 1)]
+    per_layer = [(W1p, W2tp, bp)]
+    keep = []
+    for _ in range(L - 1):                      # every layer has factors of its own (distinct memory)
+        mats = [[m.clone() for m in group] for group in (W1, W2t, bb)]
+        keep.append(mats)
+        per_layer.append(tuple(preft.pointer_table(g_) for g_ in mats))
+    as_table = lambda ptrs: torch.tensor(ptrs, dtype=torch.int64, device=dev)
+    h_tab = preft.pointer_table(hs)
+    W1s, W2s, bs = (as_table([pl[i].data_ptr() for pl in per_layer]) for i in range(3))
 
-        def layers_step(mode, fused, tables=(ss, sa, sp), T_=T):
-            s0, s1, s2 = tables
-            preft.preft_schedule(ws, s0, s1, s2, T_, N, mode)
-            ready = mode | preft.PREFT_SCHEDULE_READY
-            if fused:
-                preft.preft_direft_apply_layers([x[:T_] for x in hs], h_tab, s0, s1, s2, W1s, W2s, bs, N, r,
-                                                direft_scale, ready, ws)
-            else:
-                for x, (a1, a2, a3) in zip(hs, per_layer):
-                    preft.preft_direft_apply(x[:T_], s0, s1, s2, a1, a2, a3, r, direft_scale, ready, ws)
+    def layers_step(mode, fused, tables=(ss, sa, sp), T_=T):
+        s0, s1, s2 = tables
+        preft.preft_schedule(ws, s0, s1, s2, T_, N, mode)
+        ready = mode | preft.PREFT_SCHEDULE_READY
+        if fused:
+            preft.preft_direft_apply_layers([x[:T_] for x in hs], h_tab, s0, s1, s2, W1s, W2s, bs, N, r,
+                                            direft_scale, ready, ws)
+        else:
+            for x, (a1, a2, a3) in zip(hs, per_layer):
+                preft.preft_direft_apply(x[:T_], s0, s1, s2, a1, a2, a3, r, direft_scale, ready, ws)
 
-        it = max(3, K // 10)
-        ms_each = timed(lambda: layers_step(preft.PREFT_PREFILL_ONLY, False), it, 2)
-        ms_one = timed(lambda: layers_step(preft.PREFT_PREFILL_ONLY, True), it, 2)
-        dec = tab.decode_only()
-        dt = tuple(torch.from_numpy(a.copy()).to(dev) for a in (dec.seg_start, dec.seg_adapter, dec.seg_prefill_len))
+    it = max(3, K // 10)
+    ms_each = timed(lambda: layers_step(preft.PREFT_PREFILL_ONLY, False), it, 2)
+    ms_one = timed(lambda: layers_step(preft.PREFT_PREFILL_ONLY, True), it, 2)
 
-        def graphed_layers(fused):
+    def graphed_layers(fused):
+        layers_step(preft.PREFT_ALL_TOKENS, fused, dt, dec.T)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
             layers_step(preft.PREFT_ALL_TOKENS, fused, dt, dec.T)
-            torch.cuda.synchronize()
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g):
-                layers_step(preft.PREFT_ALL_TOKENS, fused, dt, dec.T)
-            return g
-        ms_dec_each = timed(graphed_layers(False).replay, 50, 5)
-        ms_dec_one = timed(graphed_layers(True).replay, 50, 5)
-        out["direft_every_layer"] = {
-            "layers": L, "rank": r, "d": d_res,
-            "mixed_batch_prefill_only_ms": {"one_call_per_layer": round(ms_each, 4), "one_call": round(ms_one, 4)},
-            "frac_of_peak_one_call": round(L * db / ms_one / 1e6 / PEAK_HBM_GBPS, 4),
-            "decode_rows_all_token_ms": {"rows": dec.T, "one_call_per_layer": round(ms_dec_each, 4),
-                                         "one_call": round(ms_dec_one, 4)}}
-        del hs, keep, per_layer
-
-    # ---- the configuration's other ranks: the same measurement in a child process each ----------
-    if not (args.no_extras or args.no_other_ranks or args.variant or args.waves or args.rowblocks or args.colsplit
-            or args.ldpad or args.only or args.no_packed):
-        import subprocess
-
-        def child(rk, pitch):
-            cmd = [sys.executable, os.path.abspath(__file__), "--config", args.config, "--rank", str(rk), "--seed",
-                   str(args.seed), "--steps", str(max(5, K // 4)), "--warmup", "3", "--no-extras", "--no-cpu-baseline",
-                   "--pitch", pitch]
-            res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, text=True, timeout=600)
-            lines = [l for l in res.stdout.splitlines() if l.startswith("{")]
-            if res.returncode != 0 or not lines:
-                return {"error": f"child exited with {res.returncode}"}
-            d_ = json.loads(lines[-1])
-            return {"value": d_["value"], "ms_per_step": d_["ms_per_step"], "roofline_frac": d_["roofline"]["frac"],
-                    "frac_per_launch": {k_: v_["frac"] for k_, v_ in d_["breakdown"].items()}}
-
-        others = {}
-        for rk in cfg["ranks"]:
-            if rk == r:
-                continue
-            others[str(rk)] = child(rk, args.pitch)
-        if others:
-            out["other_ranks"] = others
-        if args.pitch != "dense":          # the same step with every buffer's rows packed densely
-            out["dense_rows"] = child(r, "dense")
+        return g
+    ms_dec_each = timed(graphed_layers(False).replay, 50, 5)
+    ms_dec_one = timed(graphed_layers(True).replay, 50, 5)
+    out["direft_every_layer"] = {
+        "layers": L, "rank": r, "d": d_res,
+        "mixed_batch_prefill_only_ms": {"one_call_per_layer": round(ms_each, 4), "one_call": round(ms_one, 4)},
+        "frac_of_peak_one_call": round(L * db / ms_one / 1e6 / PEAK_HBM_GBPS, 4),
+        "decode_rows_all_token_ms": {"rows": dec.T, "one_call_per_layer": round(ms_dec_each, 4),
+                                     "one_call": round(ms_dec_one, 4)}}
+    del hs, keep, per_layer, h_tab
 
     # ---- serving-weighted comparison: first-come-first-served trace of the paper's microbenchmark --
     # (App. E.1, E.3): every engine step's adapter work, in both modes.  Decode-only steps are
     # HIP-graph replays (the paper's engine runs under graph capture too); steps that hold a
     # prompt are launched eagerly.  Only the adapter kernels run: the ratio says how the adapter
     # cost splits over a serving run, it is not an end-to-end throughput ratio.
-    if not args.no_trace and not args.no_extras:
+    if not args.no_trace:
         paged = args.trace_slots > 0
         n_trace_adapters = args.trace_adapters if paged else min(args.trace_adapters, N)
         req = wl.request_stream(args.trace_requests, n_trace_adapters, args.trace_mix, l_max=2048, seed=args.seed)
@@ -435,6 +448,7 @@ def main():
         n_steps = sum(rep for _, rep in epochs)
         n_dec_steps = sum(rep for t_, rep in epochs if not t_.seg_prefill_len.any())
         out["fcfs_trace"] = {
+            "shapes": f"{args.config} layer, rank {r}",
             "requests": len(req.prompt_len), "in_flight": Bmax, "mix": args.trace_mix,
             "adapters": int(n_trace_adapters), "l_max": 2048,
             "engine_steps": int(n_steps), "decode_only_steps": int(n_dec_steps),
@@ -454,40 +468,108 @@ def main():
                                                  "MB_copied": round(stats["bytes_copied"] / 1e6, 1)}
             preft.preft_slots_destroy(mgr)
 
-    # ---- CPU oracle on a sample of the same batch ---------------------------------------------
+    # ---- CPU oracle on a deterministic row sample of the same batch ---------------------------
+    # every prompt's first and last row and --cpu-rows-per-segment random rows of it (decode rows are
+    # not active in prefill-only mode); the sampled rows go through the whole step on the host cores
+    cpu_job = None
     if not args.no_cpu_baseline:
-        from oracle import preft_oracle as ora
-        budget_rows = 1 << 30          # the whole batch: a few seconds on the machine's cores
-        keep, rows_kept = [], 0
-        for s in np.argsort(-tab.seg_prefill_len, kind="stable"):
-            if tab.seg_prefill_len[s] == 0 or rows_kept >= budget_rows:
-                break
-            keep.append(int(s))
-            rows_kept += int(tab.seg_len[s])
-        keep = sorted(keep)
-        sub = wl.from_lengths(tab.seg_len[keep], tab.seg_adapter[keep], tab.seg_prefill_len[keep])
-        idx = torch.from_numpy(np.concatenate([np.arange(tab.seg_start[s], tab.seg_start[s + 1]) for s in keep])).to(dev)
-        used = set(int(a) for a in sub.seg_adapter)
-        cpu_in = []
-        for p in projs:
-            cpu_in.append((p["x"][idx].cpu(), p["y"][idx].cpu(),
-                           [p["pool"].A[j].cpu() if j in used else None for j in range(N)],
-                           [p["pool"].B[j].cpu() if j in used else None for j in range(N)]))
-        h_cpu = h[idx].cpu()
-        dA = [dpool.A[j].cpu() if j in used else None for j in range(N)]
-        dB = [dpool.B[j].cpu() if j in used else None for j in range(N)]
-        db_ = [dpool.b[j].cpu() if j in used else None for j in range(N)]
-        t0 = time.perf_counter()
-        for (x_c, y_c, A_c, B_c) in cpu_in:
-            ora.lora(y_c, x_c, sub.seg_start, sub.seg_adapter, sub.seg_prefill_len, A_c, B_c, r, scale, ora.PROMPT_ONLY)
-        ora.direft(h_cpu, sub.seg_start, sub.seg_adapter, sub.seg_prefill_len, dA, dB, db_, r, direft_scale,
-                   ora.PROMPT_ONLY)
-        dt_cpu = time.perf_counter() - t0
-        out["cpu_baseline"] = {"value": round(sub.T / dt_cpu, 1), "unit": "tokens/s", "cores": ora.threads(),
-                               "kind": "oracle",
-                               "sample": f"{len(keep)} prompts of the batch ({sub.T} of {T_act} active rows), full step "
-                                         f"({len(projs)} LoRA projections + DiReFT), fp64 loops, {dt_cpu:.1f} s wall"}
+        rows = wl.sample_rows(tab, args.cpu_rows_per_segment, seed=args.seed)
+        owner = np.repeat(np.arange(S), tab.seg_len)
+        rel = rows - tab.seg_start[owner[rows]]
+        rows = rows[(rel < tab.seg_prefill_len[owner[rows]]) & (tab.seg_adapter[owner[rows]] >= 0)]   # active ones
+        idx = torch.from_numpy(rows).to(dev)
+        used = set(int(a) for a in np.unique(tab.seg_adapter[owner[rows]]))
+        pick = lambda mats: [mats[j].cpu() if j in used else None for j in range(N)]
+        cpu_job = dict(rows=rows,
+                       lora=[(p["x"][idx].cpu(), p["y"][idx].cpu(), pick(p["pool"].A), pick(p["pool"].B)) for p in projs],
+                       h=h[idx].cpu(), dA=pick(dpool.A), dB=pick(dpool.B), db=pick(dpool.b))
 
+        cpu_job.update(tab=tab, r=r, scale=scale, direft_scale=direft_scale, T_act=T_act, n_projs=len(projs),
+                       per_segment=args.cpu_rows_per_segment)
+    return out, cpu_job
+
+
+def cpu_baseline(job):
+    """The fp64 oracle, as it stands, on the sampled rows: the whole step on the host cores."""
+    from oracle import preft_oracle as ora
+    tab, r = job["tab"], job["r"]
+    t0 = time.perf_counter()
+    for (x_c, y_c, A_c, B_c) in job["lora"]:
+        ora.lora(y_c, x_c, tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, A_c, B_c, r, job["scale"], ora.PROMPT_ONLY,
+                 rows=job["rows"], gathered=True)
+    ora.direft(job["h"], tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, job["dA"], job["dB"], job["db"], r,
+               job["direft_scale"], ora.PROMPT_ONLY, rows=job["rows"], gathered=True)
+    dt_cpu = time.perf_counter() - t0
+    n_rows = len(job["rows"])
+    return {"value": round(n_rows / dt_cpu, 1), "unit": "tokens/s", "cores": ora.threads(), "kind": "oracle",
+            "sample": f"sampled: {n_rows} of the {job['T_act']} active rows (first and last row of every prompt + "
+                      f"{job['per_segment']} random rows per prompt), full step ({job['n_projs']} LoRA projections + "
+                      f"DiReFT, rank {r}), fp64 loops, {dt_cpu:.1f} s wall; value = sampled rows per second"}
+
+
+def child(argv, timeout=900):
+    """The same measurement in a fresh process; returns its JSON line reduced to the figures quoted."""
+    cmd = [sys.executable, os.path.abspath(__file__), "--sub", "--no-cpu-baseline"] + argv
+    try:
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, text=True, timeout=timeout)
+    except subprocess.TimeoutExpired:
+        return {"error": "child timed out"}
+    lines = [l for l in res.stdout.splitlines() if l.startswith("{")]
+    if res.returncode != 0 or not lines:
+        return {"error": f"child exited with {res.returncode}"}
+    d_ = json.loads(lines[-1])
+    rec = {"workload": d_["config"]["workload"].split(":")[0], "rank": d_["config"]["rank"],
+           "active_rows": d_["config"]["active_rows"], "row_pitch": d_["config"]["row_pitch"].split(" (")[0],
+           "value": d_["value"], "ms_per_step": d_["ms_per_step"], "steps": d_["steps"],
+           "dominant_launch": d_["roofline"]["kernel"], "roofline_frac": d_["roofline"]["frac"],
+           "lora_launches_frac": d_["lora_launches_frac"],
+           "frac_per_launch": {k_: v_["frac"] for k_, v_ in d_["breakdown"].items()},
+           "us_per_launch": {k_: v_["us"] for k_, v_ in d_["breakdown"].items()}}
+    if "all_token" in d_:
+        rec["all_token_ms_per_step"] = d_["all_token"]["ms_per_step"]
+        rec["decode_only_step"] = d_["decode_only_step"]
+    return rec
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (the path has no cross-GPU step); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    out, cpu_job = run(args)
+    # run() has returned: its buffers are released, the GPU is free for the child processes below
+    if cpu_job is not None:
+        import gc
+        import torch
+        gc.collect()
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(cpu_job)
+
+    # ---- the other configurations, ranks and row pitch: the same measurement in a child process each ----
+    if not (args.sub or args.no_extras or args.no_children or experiment_flags(args)):
+        from paper_2605_14217_amd import workloads as wl
+        K = args.steps
+        others = {}
+        for cfg_name in ("llama8b_lora", "llama8b_direft", "skewed70b"):
+            if cfg_name == args.config:
+                continue
+            steps = K if cfg_name.startswith("llama8b") else max(5, K // 4)
+            others[cfg_name] = child(["--config", cfg_name, "--seed", str(args.seed), "--steps", str(steps), "--warmup", "3",
+                                      "--pitch", args.pitch])
+        out["other_configurations"] = others
+        r_main = args.rank or DEFAULT_RANK[args.config]
+        ranks = {}
+        for rk in wl.CONFIGS[args.config]["ranks"]:
+            if rk != r_main:
+                ranks[str(rk)] = child(["--config", args.config, "--rank", str(rk), "--seed", str(args.seed), "--steps",
+                                        str(max(5, K // 4)), "--warmup", "2", "--pitch", args.pitch])
+        if ranks:
+            out["other_ranks"] = ranks
+        other_pitch = "pow2" if args.pitch == "dense" else "dense"
+        out["pow2_row_pitch" if other_pitch == "pow2" else "dense_rows"] = child(
+            ["--config", args.config, "--rank", str(r_main), "--seed", str(args.seed), "--steps", str(max(5, K // 4)),
+             "--warmup", "2", "--pitch", other_pitch])
     print(json.dumps(out))
 
 

@@ -91,7 +91,9 @@ enum {
  *   PREFT_TEST_ROWBLOCKS(b)  MFMA kernels: 16-row blocks per wavefront: 0 = automatic, 1 or 2
  *   PREFT_TEST_COLSPLIT(c)   LoRA, MFMA column-split kernel: workgroups that share a tile, each
  *                            writing its share of the output columns: 0 = automatic (4 for
- *                            batches of up to 1024 rows, else 1), or 1..15
+ *                            batches of up to 1024 rows, else 1), or 1..15.  Together with
+ *                            variant 4 it names the column groups of the row-split kernel
+ *                            instead: 0 = automatic, 1 or 2
  *   PREFT_TEST_RESIDENT(n)   in-place MFMA kernels: how much of a tile stays in registers between
  *                            the two sweeps: 0 = automatic, 1 = nothing, 2 = all of it where a
  *                            shape exists, 3 = half of a 32-row tile

@@ -1,26 +1,35 @@
 // MFMA tile kernel for larger ranks (bf16, rank % 4 == 0, 32 <= rank <= 128 in practice),
-// widths that are multiples of 128.
+// widths that are multiples of 128 * CW.
 //
 // From rank 32 up the adapter factors outweigh a 16-row tile's activations (rank r costs
-// r/16 factor bytes per activation byte), so here the wavefronts of a workgroup split the
-// *rows* -- wavefront w owns rows 16 MB w .. of a tile of 16 MB WAVES rows (up to a whole
-// 128-row chunk) -- and share the factors: for every 128-column unit the workgroup loads the
-// unit of A (r ranks x 256 bytes) or of B (128 columns x r factors, contiguous in the
-// [d_out, r] layout) once, with fully coalesced 16-byte loads, into a double-buffered LDS
-// area, and every wavefront reads its MFMA operands from there (padded strides, no bank
-// conflicts).  Factor traffic from L2 drops to r / (16 MB WAVES) of the activation traffic.
+// r/16 factor bytes per activation byte), so here several 16-row blocks share the factors: a
+// workgroup of RW x CW wavefronts owns a tile of 16 MB RW rows (up to a whole 128-row chunk);
+// wavefront (rb, cg) owns row block rb and, of every group of CW adjacent 128-column units,
+// unit cg.  In each step the workgroup loads the CW units of A (r ranks x 256 bytes each) or of
+// B (128 columns x r factors each, contiguous in the [d_out, r] layout) once, with fully
+// coalesced 16-byte loads, into a double-buffered LDS area, and every wavefront reads its MFMA
+// operands from there (padded strides, no bank conflicts).  Factor traffic from L2 drops to
+// r / (16 MB RW) of the activation traffic.
 //
-// Each wavefront walks all columns of its own rows, so z needs no cross-wavefront sum and
-// stays in registers.  Activations take the same path as in mfma_tile_kernel: 4 rows x 256
-// bytes per instruction, turned through a wavefront-private LDS buffer, next unit's loads in
-// flight while the current unit is multiplied.  One barrier per unit publishes the next
-// factor unit.  MFMA operand layouts as in mfma_tile_kernel, except that MFMA e of the
-// expand takes the columns 2m + e of a 32-column step (lane (row, g) then owns outputs
-// 8g + 2v + e), which makes the LDS reads of the B unit conflict-free.
+// Why column groups.  Measured on this chip with a kernel that only moves the bytes (read x,
+// read y, write y; 352 814 rows of 8192 bf16, one barrier per step): a workgroup whose wavefronts
+// all sit on the same 256-byte column slice of 64 different rows (RW x CW = 4 x 1) sustains 65 % of
+// the 8 TB/s peak however many units it keeps in flight and however many workgroups share a
+// compute unit; 4 x 2 (512 contiguous bytes per row and step) 73-74 %, 2 x 2 and 4 x 4 77-78 %,
+// 8 x 1 60 %.  The memory system wants each row's bytes requested side by side, not 16 KB apart.
+//
+// With CW = 1 a wavefront walks all columns of its own rows and z never leaves its registers;
+// with CW > 1 the CW partial sums of a row block meet in LDS after the sweep (every wavefront adds
+// them in the same order, so all hold the same z).  Activations take the same path as in
+// mfma_tile_kernel: 4 rows x 256 bytes per instruction, turned through a wavefront-private LDS
+// buffer.  One barrier per step publishes the next factor units.  MFMA operand layouts as in
+// mfma_tile_kernel, except that MFMA e of the expand takes the columns 2m + e of a 32-column
+// step (lane (row, g) then owns outputs 8g + 2v + e), which makes the LDS reads of the B unit
+// conflict-free.
 //
 // SLICES > 1 (LoRA only): packed projections, as in mfma_tile_kernel.  The outputs share x: every
 // unit of x is loaded and turned once and then multiplied with the unit of each output's own A
-// (one factor unit and one barrier per output and unit of x, through the same two LDS buffers),
+// (one factor step and one barrier per output and unit of x, through the same two LDS buffers),
 // which leaves SLICES * NB accumulator blocks; one expand sweep per output follows.
 #pragma once
 #include "common.hpp"
@@ -28,30 +37,38 @@
 
 namespace preft {
 
-constexpr int wide_lds_bytes(int NB, int MB, int WAVES)
+constexpr int wide_fac_bytes(int NB, int CW)                   // one buffer of CW factor units
 {
-    const int turn = WAVES * MB * 16 * MFMA_TRS * 16;
-    const int fa = 2 * NB * 16 * MFMA_TRS * 16;               // A units: NB*16 ranks x 272 B, two buffers
-    const int fb = 2 * 128 * (32 * NB + 8);                   // B units: 128 columns x (2r + 8) B, two buffers
-    return turn + (fa > fb ? fa : fb);
+    const int fa = NB * 16 * MFMA_TRS * 16;                   // A unit: NB*16 ranks x 272 B
+    const int fb = 128 * (32 * NB + 8);                       // B unit: 128 columns x (2r + 8) B
+    return CW * (fa > fb ? fa : fb);
+}
+constexpr int wide_lds_bytes(int NB, int MB, int RW, int CW)
+{
+    return RW * CW * MB * 16 * MFMA_TRS * 16 + 2 * wide_fac_bytes(NB, CW);
 }
 
-template <int NB, int MB, int WAVES, bool DIREFT, int SLICES = 1>
+template <int NB, int MB, int RW, int CW, bool DIREFT, int SLICES = 1>
 __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
 {
     static_assert(SLICES == 1 || !DIREFT, "packed projections are a LoRA feature");
+    constexpr int WAVES = RW * CW;
     constexpr int NBT = NB * SLICES;                          // accumulator blocks of the shrink sweep
-    constexpr int R = 16 * MB * WAVES;
+    constexpr int R = 16 * MB * RW;
     constexpr int TPC = CHUNK_ROWS / R;
     constexpr int NT = WAVES * 64;
-    constexpr int A_PIECES = NB * 16 * 16;                    // 16-byte pieces of an A unit (padded ranks included)
+    constexpr int A_UNIT = NB * 16 * MFMA_TRS;                // 16-byte vectors of an A unit in LDS
+    constexpr int A_PIECES = NB * 16 * 16 * CW;               // 16-byte pieces of a step's A units (padded ranks included)
     constexpr int A_ITERS = (A_PIECES + NT - 1) / NT;
-    constexpr int B_ITERS = (NB * 16 * 16 + NT - 1) / NT;     // upper bound: 16 r pieces, r <= 16 NB
+    constexpr int B_UNIT = 128 * (32 * NB + 8);               // bytes reserved for a B unit in LDS
+    constexpr int B_ITERS = (NB * 16 * 16 * CW + NT - 1) / NT;   // upper bound: 16 r CW pieces, r <= 16 NB
+    constexpr int FAC = wide_fac_bytes(NB, CW);
     static_assert(CHUNK_ROWS % R == 0, "tile height must divide the chunk height");
+    static_assert(CW == 1 || WAVES * NB * MB * 4 * 64 * 4 <= 2 * FAC, "the partial sums of one output must fit the factor area");
 
-    __shared__ __attribute__((aligned(16))) char lds_raw[wide_lds_bytes(NB, MB, WAVES)];
+    __shared__ __attribute__((aligned(16))) char lds_raw[wide_lds_bytes(NB, MB, RW, CW)];
     u32x4_t *turn_all = reinterpret_cast<u32x4_t *>(lds_raw);
-    char *fac = lds_raw + WAVES * MB * 16 * MFMA_TRS * 16;    // factor area (A units, later B units)
+    char *fac = lds_raw + WAVES * MB * 16 * MFMA_TRS * 16;    // factor area (A units, later B units): two buffers of FAC bytes
 
     if (!schedule_matches(p)) return;
     const int unit_id = xcd_unit(p.header[HDR_CHUNKS] * TPC);
@@ -63,6 +80,7 @@ __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
     const int n_rows = min(R, ch.z - tile_row0);
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int rb = wave / CW, cg = wave % CW;                 // row block, column group
     const int rl = lane & 15, g = lane >> 4;                  // MFMA order
     const int q = lane >> 4, c16 = lane & 15;                 // unit load order
     const int r = p.rank;
@@ -82,10 +100,10 @@ __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int t = wave * 16 * MB + mb * 16 + 4 * i + q;
+            const int t = rb * 16 * MB + mb * 16 + 4 * i + q;
             row_ok[mb][i] = t < n_rows;
             row_u[mb][i] = (int64_t)ch.y + tile_row0 + min(t, n_rows - 1);
-            xu[mb][i] = as_global(p.x) + row_u[mb][i] * ldx_b + c16 * 16;
+            xu[mb][i] = as_global(p.x) + row_u[mb][i] * ldx_b + (cg * 16 + c16) * 16;
         }
 
     auto unit_to_mfma = [&](const u32x4_t (&raw)[MB][4], u32x4_t (&op)[MB][4]) {
@@ -106,34 +124,37 @@ __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) acc[b][mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    const int k_units = p.d_in >> 7;                          // d_in % 128 == 0 (host-checked)
+    // a step covers CW adjacent units: this wavefront's unit of step u is u * CW + cg
+    const int k_steps = p.d_in / (128 * CW);                  // d_in % (128 CW) == 0 (host-checked)
     auto load_x = [&](u32x4_t (&raw)[MB][4], int u) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) raw[mb][i] = ld16_first<DIREFT>(xu[mb][i] + (int64_t)u * 256);
+            for (int i = 0; i < 4; ++i) raw[mb][i] = ld16_first<DIREFT>(xu[mb][i] + (int64_t)u * (256 * CW));
     };
-    // this thread's pieces of the A unit: piece t + i NT = rank (piece >> 4), 16-byte chunk (piece & 15)
+    // this thread's pieces of the step's A units: piece = (rank, 16-byte chunk of the 256 CW bytes of the step)
     auto load_a = [&](u32x4_t (&areg)[A_ITERS], gcptr_t Asl, int u) {
 #pragma unroll
         for (int i = 0; i < A_ITERS; ++i) {
             const int piece = tid + i * NT;
-            const int rank = min(piece >> 4, r - 1);          // padding ranks alias rank r-1 (their z is zeroed)
+            const int rank = min(piece / (16 * CW), r - 1);   // padding ranks alias rank r-1 (their z is zeroed)
             if (A_PIECES % NT == 0 || piece < A_PIECES)
-                areg[i] = ld16(Asl + ((int64_t)rank * p.d_in) * 2 + (int64_t)u * 256 + (piece & 15) * 16);
+                areg[i] = ld16(Asl + ((int64_t)rank * p.d_in) * 2 + (int64_t)u * (256 * CW) + (piece % (16 * CW)) * 16);
         }
     };
     auto publish_a = [&](const u32x4_t (&areg)[A_ITERS], int buf) {
-        u32x4_t *fa = reinterpret_cast<u32x4_t *>(fac) + buf * (NB * 16 * MFMA_TRS);
+        u32x4_t *fa = reinterpret_cast<u32x4_t *>(fac + buf * FAC);
 #pragma unroll
         for (int i = 0; i < A_ITERS; ++i) {
             const int piece = tid + i * NT;
-            if (A_PIECES % NT == 0 || piece < A_PIECES) fa[(piece >> 4) * MFMA_TRS + (piece & 15)] = areg[i];
+            const int chunk = piece % (16 * CW);
+            if (A_PIECES % NT == 0 || piece < A_PIECES)
+                fa[(chunk >> 4) * A_UNIT + (piece / (16 * CW)) * MFMA_TRS + (chunk & 15)] = areg[i];
         }
     };
     auto mfma_a = [&](const u32x4_t (&op)[MB][4], int buf, auto sl_tag) {
         constexpr int SL = decltype(sl_tag)::value;
-        const u32x4_t *fa = reinterpret_cast<const u32x4_t *>(fac) + buf * (NB * 16 * MFMA_TRS);
+        const u32x4_t *fa = reinterpret_cast<const u32x4_t *>(fac + buf * FAC) + cg * A_UNIT;
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
@@ -148,60 +169,97 @@ __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
             }
     };
     {
-        // One trip of `unit` handles a unit of x: SLICES steps, one per output's factor unit.  Step
-        // number t = u * SLICES + sl multiplies from LDS buffer (t & 1) while the factor unit of step
-        // t + 1 is published into the other buffer; one barrier per step.  With one output the factor
-        // unit of step t + 1 is requested at the start of step t (before x is turned, so its latency
-        // overlaps the wait for x); with several outputs a step is only a handful of MFMAs long, so
-        // the requests run two steps ahead, through two register sets.  P0 is the buffer of the trip's
-        // first step: the trips come in pairs (the register buffers of x swap without copies) and a
-        // pair takes an even number of steps, so P0 is known at compile time.  No conditional loads
-        // in the steady state: the prefetches stay in flight across the MFMAs.
-        constexpr int DEPTH = SLICES > 1 ? 2 : 1;
-        u32x4_t x0[MB][4], x1[MB][4], op[MB][4], areg[DEPTH][A_ITERS];
-        auto unit = [&](const u32x4_t (&xc)[MB][4], u32x4_t (&xn)[MB][4], int u, auto next_tag, auto p0_tag) {
-            constexpr bool HAS_NEXT = decltype(next_tag)::value;
-            constexpr int P0 = decltype(p0_tag)::value;
-            if constexpr (HAS_NEXT) load_x(xn, u + 1);
-            if constexpr (SLICES == 1 && HAS_NEXT) load_a(areg[0], A[0], u + 1);
-            unit_to_mfma(xc, op);
+        // Pipeline.  A wavefront keeps two units of x on their way (three register buffers in
+        // rotation) while it multiplies a third.  One trip handles a unit of x in SLICES steps, one
+        // per output's factor units: step t = u * SLICES + sl multiplies from LDS buffer (t & 1)
+        // while the factor units of step t + 1 are published into the other buffer; one barrier per
+        // step.  With one output the factor units of step t + 1 are requested at the start of step
+        // t; with several outputs a step is only a handful of MFMAs long, so the requests run two
+        // steps ahead, the units of output sl always through register set sl.  Requests are issued
+        // factor first, activations second: the memory counter retires in order, and the publish at
+        // the end of a step must not wait for the activations requested in the same step.  Trips
+        // come in threes with compile-time buffer numbers; GUARD = false (steady state) has no
+        // conditional load, so that the compiler's wait counts stay exact; the last trips of a sweep
+        // check which requests still exist.
+        u32x4_t X[3][MB][4], op[MB][4], areg[SLICES][A_ITERS];
+        int par = 0;                                          // LDS buffer of the current step
+        auto trip = [&](auto xi_tag, int u, auto guard_tag) {
+            constexpr int XI = decltype(xi_tag)::value;
+            constexpr bool GUARD = decltype(guard_tag)::value;
+            const bool has1 = !GUARD || u + 1 < k_steps, has2 = !GUARD || u + 2 < k_steps;
             auto step = [&](auto sl_tag) {
                 constexpr int SL = decltype(sl_tag)::value;
-                constexpr int BUF = (P0 + SL) & 1;
-                constexpr bool PUBLISH = SL + 1 < SLICES || HAS_NEXT;       // step t + 1 exists
-                if constexpr (SLICES > 1) {
-                    constexpr int S2 = SL + 2;                               // step t + 2: (u, S2) or (u + 1, S2 - SLICES)
-                    if constexpr (S2 < SLICES) load_a(areg[BUF], A[S2 % SLICES], u);
-                    else if constexpr (HAS_NEXT) load_a(areg[BUF], A[(S2 - SLICES) % SLICES], u + 1);
+                if constexpr (SLICES == 1) {
+                    if (has1) load_a(areg[0], A[0], u + 1);
+                } else {                                      // step t + 2 is (u, SL + 2) or (u + 1, SL + 2 - SLICES)
+                    constexpr int S2 = (SL + 2) % SLICES, DU = (SL + 2) / SLICES;
+                    if (DU == 0 || has1) load_a(areg[S2], A[S2], u + DU);
                 }
-                mfma_a(op, BUF, sl_tag);
-                if constexpr (PUBLISH) publish_a(areg[SLICES > 1 ? (BUF ^ 1) : 0], BUF ^ 1);
-                __syncthreads();                              // the last one: the factor area is reused by the expand
+                if constexpr (SL == 0) {
+                    if (has2) load_x(X[(XI + 2) % 3], u + 2);
+                    unit_to_mfma(X[XI], op);
+                }
+                mfma_a(op, par, sl_tag);
+                if (SL + 1 < SLICES || has1) publish_a(areg[(SL + 1) % SLICES], par ^ 1);   // step t + 1 exists
+                __syncthreads();                              // the last one: the factor area is reused below
+                par ^= 1;
             };
             step(std::integral_constant<int, 0>{});
             if constexpr (SLICES > 1) step(std::integral_constant<int, 1>{});
             if constexpr (SLICES > 2) step(std::integral_constant<int, 2>{});
         };
-        constexpr std::integral_constant<bool, true> more{};
-        constexpr std::integral_constant<bool, false> last{};
-        constexpr std::integral_constant<int, 0> even{};
-        constexpr std::integral_constant<int, SLICES & 1> second{};
-        load_x(x0, 0);
+        constexpr std::integral_constant<bool, false> steady{};
+        constexpr std::integral_constant<bool, true> guarded{};
+        constexpr std::integral_constant<int, 0> b0{};
+        constexpr std::integral_constant<int, 1> b1{};
+        constexpr std::integral_constant<int, 2> b2{};
         load_a(areg[0], A[0], 0);
         if constexpr (SLICES > 1) load_a(areg[1], A[1], 0);
+        load_x(X[0], 0);
+        if (k_steps > 1) load_x(X[1], 1);
         publish_a(areg[0], 0);
         __syncthreads();
         int u = 0;
-        while (u + 2 < k_units) {
-            unit(x0, x1, u, more, even);
-            unit(x1, x0, u + 1, more, second);
-            u += 2;
+        for (; u + 5 <= k_steps; u += 3) {                    // steps u .. u + 4 exist
+            trip(b0, u, steady);
+            trip(b1, u + 1, steady);
+            trip(b2, u + 2, steady);
         }
-        if (k_units - u == 2) {
-            unit(x0, x1, u, more, even);
-            unit(x1, x0, u + 1, last, second);
-        } else {
-            unit(x0, x1, u, last, even);
+        for (; u < k_steps; u += 3) {
+            trip(b0, u, guarded);
+            if (u + 1 < k_steps) trip(b1, u + 1, guarded);
+            if (u + 2 < k_steps) trip(b2, u + 2, guarded);
+        }
+    }
+
+    // ---------------------------------------------------------------- sum over the column groups
+    // the CW partial sums of a row block meet in the factor area (free after the sweep's last
+    // barrier), one output at a time; every wavefront adds them in the same order
+    if constexpr (CW > 1) {
+        float *red = reinterpret_cast<float *>(fac);
+        constexpr int PER = NB * MB * 4;
+#pragma unroll
+        for (int sl = 0; sl < SLICES; ++sl) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        red[(wave * PER + (b * MB + mb) * 4 + v) * 64 + lane] = acc[sl * NB + b][mb][v];
+            __syncthreads();
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        float s = 0.f;
+#pragma unroll
+                        for (int c = 0; c < CW; ++c) s += red[((rb * CW + c) * PER + (b * MB + mb) * 4 + v) * 64 + lane];
+                        acc[sl * NB + b][mb][v] = s;
+                    }
+            __syncthreads();                                  // the area is written again (next output, or B units)
         }
     }
 
@@ -239,28 +297,28 @@ __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
     }
 
     // ---------------------------------------------------------------- expand (once per output)
-    // B unit in LDS: column c of the unit at byte c * CS, its r factors contiguous; CS = 2r + 8.
+    // B units in LDS: column c of the step (0 .. 128 CW - 1) at byte c * CS, its r factors contiguous; CS = 2r + 8.
     const int cs = 2 * r + 8;
-    const int b_halves = 32 * r;                              // 8-byte halves of a B unit (128 columns x r factors)
-    // where this thread's pieces land in LDS (the same for every unit): two 8-byte halves each,
+    const int b_halves = 32 * r * CW;                         // 8-byte halves of a step's B units (128 CW columns x r factors)
+    // where this thread's pieces land in LDS (the same for every step): two 8-byte halves each,
     // a half never straddles a column because r % 4 == 0
     int b_dst[B_ITERS][2];
 #pragma unroll
     for (int i = 0; i < B_ITERS; ++i)
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh) {
-            const int byte = ((tid + i * NT) * 2 + hh) * 8;   // offset in the contiguous unit
+            const int byte = ((tid + i * NT) * 2 + hh) * 8;   // offset in the contiguous units
             const int col = byte / (2 * r);
             b_dst[i][hh] = col * cs + (byte - col * 2 * r);
         }
-    // byte offset of this lane's factors inside a B unit for MFMA e, rank block b, step 0
+    // byte offset of this lane's factors inside the step's B units for MFMA e, rank block b, 32-column step 0
     int w_off[2][NB];
 #pragma unroll
     for (int e = 0; e < 2; ++e)
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             const int rank0 = 16 * b + 4 * g;
-            w_off[e][b] = (2 * rl + e) * cs + (rank0 < r ? rank0 : 0) * 2;
+            w_off[e][b] = (cg * 128 + 2 * rl + e) * cs + (rank0 < r ? rank0 : 0) * 2;
         }
 
     auto expand_slice = [&](auto sl_tag) {
@@ -271,10 +329,10 @@ __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) yu[mb][i] = as_global(slice_y<SL>(p)) + row_u[mb][i] * ldy_b + c16 * 16;
+        for (int i = 0; i < 4; ++i) yu[mb][i] = as_global(slice_y<SL>(p)) + row_u[mb][i] * ldy_b + (cg * 16 + c16) * 16;
 
     auto load_b = [&](u32x4_t (&breg)[B_ITERS], int u) {
-        gcptr_t base = Bt + (int64_t)u * 256 * r;             // 128 columns x r x 2 bytes
+        gcptr_t base = Bt + (int64_t)u * (256 * CW) * r;      // 128 CW columns x r x 2 bytes
 #pragma unroll
         for (int i = 0; i < B_ITERS; ++i) {
             const int piece = tid + i * NT;
@@ -282,7 +340,7 @@ __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
         }
     };
     auto publish_b = [&](const u32x4_t (&breg)[B_ITERS], int buf) {
-        char *fb = fac + buf * (128 * (32 * NB + 8));
+        char *fb = fac + buf * FAC;
 #pragma unroll
         for (int i = 0; i < B_ITERS; ++i) {
             const int piece = tid + i * NT;
@@ -297,10 +355,10 @@ __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) raw[mb][i] = ld16_stream(yu[mb][i] + (int64_t)u * 256);
+            for (int i = 0; i < 4; ++i) raw[mb][i] = ld16_stream(yu[mb][i] + (int64_t)u * (256 * CW));
     };
     auto finish_unit = [&](const u32x4_t (&yop)[MB][4], int buf, int u) {
-        const char *fb = fac + buf * (128 * (32 * NB + 8));
+        const char *fb = fac + buf * FAC;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             f32x4_t d[2][MB];
@@ -335,46 +393,48 @@ __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const u32x4_t o = tr[(mb * 16 + 4 * i + q) * MFMA_TRS + c16];
-                if (row_ok[mb][i]) st16_stream(yu[mb][i] + (int64_t)u * 256, o);
+                if (row_ok[mb][i]) st16_stream(yu[mb][i] + (int64_t)u * (256 * CW), o);
             }
     };
 
-    const int c_units = slice_d_out<SL>(p) >> 7;              // d_out % 128 == 0 (host-checked)
+    const int c_steps = slice_d_out<SL>(p) / (128 * CW);      // d_out % (128 CW) == 0 (host-checked)
     {
-        u32x4_t y0[MB][4], y1[MB][4], yop[MB][4], breg[B_ITERS];
-        load_y(y0, 0);
+        // the same pipeline: two units of y on their way while a third is finished and stored
+        u32x4_t Y[3][MB][4], yop[MB][4], breg[B_ITERS];
+        int par = 0;
+        auto trip = [&](auto yi_tag, int u, auto guard_tag) {
+            constexpr int YI = decltype(yi_tag)::value;
+            constexpr bool GUARD = decltype(guard_tag)::value;
+            const bool has1 = !GUARD || u + 1 < c_steps, has2 = !GUARD || u + 2 < c_steps;
+            if (has1) load_b(breg, u + 1);
+            if (has2) load_y(Y[(YI + 2) % 3], u + 2);
+            unit_to_mfma(Y[YI], yop);
+            finish_unit(yop, par, u);
+            if (has1) publish_b(breg, par ^ 1);
+            __syncthreads();
+            par ^= 1;
+        };
+        constexpr std::integral_constant<bool, false> steady{};
+        constexpr std::integral_constant<bool, true> guarded{};
+        constexpr std::integral_constant<int, 0> b0{};
+        constexpr std::integral_constant<int, 1> b1{};
+        constexpr std::integral_constant<int, 2> b2{};
         load_b(breg, 0);
-        if constexpr (SL > 0) __syncthreads();                // the previous output's last unit is still being read
+        load_y(Y[0], 0);
+        if (c_steps > 1) load_y(Y[1], 1);
+        if constexpr (SL > 0) __syncthreads();                // the previous output's last step is still being read
         publish_b(breg, 0);
         __syncthreads();
         int u = 0;
-        while (u + 2 < c_units) {
-            load_y(y1, u + 1);
-            load_b(breg, u + 1);
-            unit_to_mfma(y0, yop);
-            finish_unit(yop, u & 1, u);
-            publish_b(breg, (u + 1) & 1);
-            __syncthreads();
-            load_y(y0, u + 2);
-            load_b(breg, u + 2);
-            unit_to_mfma(y1, yop);
-            finish_unit(yop, (u + 1) & 1, u + 1);
-            publish_b(breg, u & 1);
-            __syncthreads();
-            u += 2;
+        for (; u + 5 <= c_steps; u += 3) {
+            trip(b0, u, steady);
+            trip(b1, u + 1, steady);
+            trip(b2, u + 2, steady);
         }
-        if (c_units - u == 2) {
-            load_y(y1, u + 1);
-            load_b(breg, u + 1);
-            unit_to_mfma(y0, yop);
-            finish_unit(yop, u & 1, u);
-            publish_b(breg, (u + 1) & 1);
-            __syncthreads();
-            unit_to_mfma(y1, yop);
-            finish_unit(yop, (u + 1) & 1, u + 1);
-        } else {
-            unit_to_mfma(y0, yop);
-            finish_unit(yop, u & 1, u);
+        for (; u < c_steps; u += 3) {
+            trip(b0, u, guarded);
+            if (u + 1 < c_steps) trip(b1, u + 1, guarded);
+            if (u + 2 < c_steps) trip(b2, u + 2, guarded);
         }
     }
     };
@@ -383,21 +443,26 @@ __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
     if constexpr (SLICES > 2) expand_slice(std::integral_constant<int, 2>{});
 }
 
-// Packed launches carry SLICES * NB accumulator blocks: the register allocation is held to two
-// wavefronts per SIMD (two workgroups of four wavefronts per compute unit), which the unpacked
-// shapes reach by themselves.
-template <int NB, int MB, int WAVES, bool DIREFT, int SLICES = 1>
-__global__ __launch_bounds__(WAVES * 64, (SLICES > 1 && WAVES == 4) ? 2 : 1) void mfma_wide_kernel(ApplyArgs p)
+// Wavefronts per SIMD the register allocation must leave room for.  Packed launches carry SLICES * NB
+// accumulator blocks: with four wavefronts per workgroup they are held to two workgroups per compute
+// unit, which the unpacked shapes reach by themselves.
+constexpr int wide_min_waves(int RW, int CW, int SLICES)
 {
-    mfma_wide_body<NB, MB, WAVES, DIREFT, SLICES>(p);
+    return (RW * CW == 4 && SLICES > 1) ? 2 : 1;
+}
+
+template <int NB, int MB, int RW, int CW, bool DIREFT, int SLICES = 1>
+__global__ __launch_bounds__(RW * CW * 64, wide_min_waves(RW, CW, SLICES)) void mfma_wide_kernel(ApplyArgs p)
+{
+    mfma_wide_body<NB, MB, RW, CW, DIREFT, SLICES>(p);
 }
 
 // the same for one of several residual streams (in-place calls): blockIdx.y is the layer
-template <int NB, int MB, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void mfma_wide_layers_kernel(ApplyArgs p)
+template <int NB, int MB, int RW, int CW>
+__global__ __launch_bounds__(RW * CW * 64) void mfma_wide_layers_kernel(ApplyArgs p)
 {
     select_layer(p);
-    mfma_wide_body<NB, MB, WAVES, true>(p);
+    mfma_wide_body<NB, MB, RW, CW, true>(p);
 }
 
 }  // namespace preft

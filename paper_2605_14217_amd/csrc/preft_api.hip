@@ -133,7 +133,7 @@ inline unsigned tile_grid(const ApplyArgs &a, int64_t S, int rows)
 // few tiles to occupy the chip, and one workgroup per tile would walk every output column alone.
 inline int choose_col_split(int32_t T, const Knobs &k)
 {
-    if (k.colsplit) return k.colsplit;
+    if (k.colsplit && k.variant != 4) return k.colsplit;      // with variant 4 the knob names the row-split kernel's column groups
     return T <= 1024 ? 4 : 1;
 }
 
@@ -205,33 +205,40 @@ bool launch_mfma_resident(const ApplyArgs &a, int64_t S, hipStream_t stream)
     }
 }
 
-// row-split kernel with the factors shared through LDS (rank >= 32, widths multiples of 128)
-template <int NB, bool DIREFT>
-bool launch_mfma_wide(const ApplyArgs &a, int64_t S, int mb, int waves, const Knobs &k, hipStream_t stream)
+// row-split kernel with the factors shared through LDS (rank >= 32, widths multiples of 128):
+// `rw` row blocks of 16 `mb` rows x `cw` column groups of wavefronts per workgroup
+template <int NB, int MB, int RW, int CW, bool DIREFT>
+void launch_wide_shape(const ApplyArgs &a, int64_t S, hipStream_t stream)
 {
-    {
-        if (NB < 2 && k.variant != 4) return false;           // rank <= 16: only on request
-        if ((a.d_in & 127) || (a.d_out & 127)) return false;
-        void (*kernel)(ApplyArgs);
-        int rows = 128, threads = 512;
-        constexpr bool L = DIREFT;                              // a.h_layers is set on in-place calls only
-        if (mb == 1 && waves != 8) {
-            kernel = mfma_wide_kernel<NB, 1, 4, DIREFT>;
-            if constexpr (L) { if (a.h_layers) kernel = mfma_wide_layers_kernel<NB, 1, 4>; }
-            rows = 64; threads = 256;
-        } else if (mb != 1 && NB <= 4) {
-            if constexpr (NB <= 4) {
-                kernel = mfma_wide_kernel<NB, 2, 4, DIREFT>;
-                if constexpr (L) { if (a.h_layers) kernel = mfma_wide_layers_kernel<NB, 2, 4>; }
-            }
-            threads = 256;
-        } else {
-            kernel = mfma_wide_kernel<NB, 1, 8, DIREFT>;
-            if constexpr (L) { if (a.h_layers) kernel = mfma_wide_layers_kernel<NB, 1, 8>; }
-        }
-        hipLaunchKernelGGL(kernel, dim3(chunk_grid(a, S, rows), a.n_layers), dim3(threads), 0, stream, a);
+    void (*kernel)(ApplyArgs) = mfma_wide_kernel<NB, MB, RW, CW, DIREFT>;
+    if constexpr (DIREFT) { if (a.h_layers) kernel = mfma_wide_layers_kernel<NB, MB, RW, CW>; }   // set on in-place calls only
+    hipLaunchKernelGGL(kernel, dim3(chunk_grid(a, S, 16 * MB * RW), a.n_layers), dim3(RW * CW * 64), 0, stream, a);
+}
+
+// widths the shape with `cw` column groups takes
+inline bool wide_widths_ok(const ApplyArgs &a, int cw)
+{
+    const int m = 128 * cw;
+    return (a.d_in % m) == 0 && (a.d_out % m) == 0;
+}
+
+template <int NB, bool DIREFT>
+bool launch_mfma_wide(const ApplyArgs &a, int64_t S, int mb, int waves, int cw, const Knobs &k, hipStream_t stream)
+{
+    if (NB < 2 && k.variant != 4) return false;               // rank <= 16: only on request
+    if (!wide_widths_ok(a, 1)) return false;
+    if (!wide_widths_ok(a, cw)) cw = 1;
+    if (mb != 1 && NB <= 4) {                                  // 4 wavefronts x 32 rows
+        if constexpr (NB <= 4) launch_wide_shape<NB, 2, 4, 1, DIREFT>(a, S, stream);
         return true;
     }
+    if (cw >= 2 && NB <= 4) {                                  // 2 column groups: 8 wavefronts on 64 rows
+        if constexpr (NB <= 4) launch_wide_shape<NB, 1, 4, 2, DIREFT>(a, S, stream);
+        return true;
+    }
+    if (waves == 8) launch_wide_shape<NB, 1, 8, 1, DIREFT>(a, S, stream);
+    else            launch_wide_shape<NB, 1, 4, 1, DIREFT>(a, S, stream);
+    return true;
 }
 
 template <int NB, bool DIREFT>
@@ -243,6 +250,11 @@ void launch_mfma_nb(const ApplyArgs &a, int64_t S, const Knobs &k, hipStream_t s
     // the 8B- and 70B-sized batches); above, 8 wavefronts (4 would leave one workgroup per unit)
     const int wide_mb = k.rowblocks ? k.rowblocks : 1;
     const int wide_waves = k.waves ? (k.waves == 8 ? 8 : 4) : (NB <= 4 ? 4 : 8);
+    // Column groups (with test variant 4 the column-split knob names them: 1 or 2).  Two of them at
+    // rank 32 (measured: 70B q,k,v,o 64 -> 70-76 % of peak, skewed batch 64-75 -> 78 %); at rank 48-64
+    // the two factor units per step leave one workgroup per compute unit and that costs more than the
+    // access pattern gains (o 62 -> 64.5 %, but gate+up 69 -> 62.5 %, down 64 -> 59 %).
+    const int wide_cw = (k.variant == 4 && k.colsplit) ? k.colsplit : (NB <= 2 ? 2 : 1);
     // column-split kernel.  rank <= 16: 8 wavefronts per 16-row tile; rank 32 (widths the
     // row-split kernel does not take): 32-row tiles of 4 wavefronts
     const int mb = k.rowblocks ? k.rowblocks : (NB == 2 ? 2 : 1);
@@ -265,7 +277,7 @@ void launch_mfma_nb(const ApplyArgs &a, int64_t S, const Knobs &k, hipStream_t s
             return;
         }
     }
-    if (k.variant != 3 && launch_mfma_wide<NB, DIREFT>(a, S, wide_mb, wide_waves, k, stream)) {
+    if (k.variant != 3 && launch_mfma_wide<NB, DIREFT>(a, S, wide_mb, wide_waves, wide_cw, k, stream)) {
         // the row-split kernel shares one adapter's factors among the 128 rows of a chunk;
         // gathered tiles (16 rows of an adapter) go to the column-split kernel
         ApplyArgs g = a;
@@ -301,8 +313,14 @@ void launch_mfma_packed(const ApplyArgs &a, int64_t S, const Knobs &k, hipStream
 template <int NB>
 void launch_mfma_wide_packed(const ApplyArgs &a, int n_proj, int64_t S, hipStream_t stream)
 {
-    void (*kernel)(ApplyArgs) = n_proj == 2 ? mfma_wide_kernel<NB, 1, 4, false, 2> : mfma_wide_kernel<NB, 1, 4, false, 3>;
-    hipLaunchKernelGGL(kernel, dim3(chunk_grid(a, S, 64)), dim3(256), 0, stream, a);
+    // two column groups at rank 32 where every width allows it (see launch_mfma_nb)
+    bool cw2 = NB <= 2 && (a.d_in % 256) == 0 && (a.d_out % 256) == 0;
+    for (int i = 1; i < n_proj; ++i) cw2 = cw2 && (a.more[i - 1].d_out % 256) == 0;
+    void (*kernel)(ApplyArgs) = n_proj == 2 ? mfma_wide_kernel<NB, 1, 4, 1, false, 2> : mfma_wide_kernel<NB, 1, 4, 1, false, 3>;
+    if constexpr (NB <= 2) {
+        if (cw2) kernel = n_proj == 2 ? mfma_wide_kernel<NB, 1, 4, 2, false, 2> : mfma_wide_kernel<NB, 1, 4, 2, false, 3>;
+    }
+    hipLaunchKernelGGL(kernel, dim3(chunk_grid(a, S, 64)), dim3(cw2 ? 512 : 256), 0, stream, a);
     for (int i = 0; i < n_proj; ++i) {
         ApplyArgs g = a;
         if (i > 0) {
