@@ -94,9 +94,10 @@ enum {
  *                            batches of up to 1024 rows, else 1), or 1..15.  Together with
  *                            variant 4 it names the column groups of the row-split kernel
  *                            instead: 0 = automatic, 1 or 2
- *   PREFT_TEST_RESIDENT(n)   in-place MFMA kernels: how much of a tile stays in registers between
- *                            the two sweeps: 0 = automatic, 1 = nothing, 2 = all of it where a
- *                            shape exists, 3 = half of a 32-row tile
+ *   PREFT_TEST_RESIDENT(n)   in-place MFMA kernel at rank 20..32: 0 = automatic (32-row tiles
+ *                            streamed in both sweeps), 3 = every wavefront keeps 8 of its
+ *                            128-column units in registers between the sweeps (half of a
+ *                            32-row tile of 8192 columns) and streams the rest twice
  */
 #define PREFT_TEST_VARIANT(v)   (((v) & 7) << 16)
 #define PREFT_TEST_WAVES(w)     (((w) & 15) << 19)

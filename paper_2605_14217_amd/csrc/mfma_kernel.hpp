@@ -78,13 +78,21 @@ constexpr int mfma_min_waves(int NB, int MB, int WAVES, int HUNITS)
 // one expand sweep per output.  x is read once instead of SLICES times.
 //
 // COLSPLIT (LoRA only): the small-batch shape, see below.
-template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT, int SLICES = 1, bool COLSPLIT = false>
+//
+// PARTIAL (in place, HUNITS > 0): the wavefront keeps its first HUNITS units and streams the rest in
+// both sweeps -- for tiles too large to hold (32 rows of 8192 elements are the whole register file).
+// Without it a HUNITS > 0 shape expects every unit to fit (the host picks it only then).
+template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT, int SLICES = 1, bool COLSPLIT = false, bool PARTIAL = false>
 __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
 {
+    static_assert(!PARTIAL || HUNITS > 0, "a partially resident tile keeps some units");
+    constexpr bool STREAMS = HUNITS == 0 || PARTIAL;         // some units pass through both sweeps
     static_assert(!COLSPLIT || !DIREFT, "a tile of an in-place call belongs to one workgroup");
     // x is read a second time by this workgroup (in place without a resident tile) or by the
     // workgroups that share the tile (small-batch shape): then its loads stay cacheable
-    constexpr bool X_READ_AGAIN = (DIREFT && HUNITS == 0) || COLSPLIT;
+    // (in place, the units the wavefront does not keep: HUNITS names how many of its units stay in
+    // registers; the others are streamed in both sweeps)
+    constexpr bool X_READ_AGAIN = DIREFT || COLSPLIT;
     constexpr int R = 16 * MB;
     constexpr int NBT = NB * SLICES;                          // rank blocks of the shrink sweep
     constexpr bool PREFETCH_A = (NBT * MB <= 3);              // register budget
@@ -204,13 +212,16 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
     u32x4_t hreg[HUNITS > 0 ? HUNITS : 1][MB][4];             // DiReFT: this wavefront's units, MFMA order
     u32x4_t htail[MB];                                        // DiReFT: its tail step, MFMA order
 
-    auto load_x_unit = [&](u32x4_t (&raw)[MB][4], int u) {
+    auto load_x_unit = [&](u32x4_t (&raw)[MB][4], int u, auto again_tag) {
+        constexpr bool AGAIN = decltype(again_tag)::value;    // these bytes are read a second time: keep them cacheable
         const int64_t off = (int64_t)(wave + u * WAVES) * 256;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) raw[mb][i] = ld16_first<X_READ_AGAIN>(xu[mb][i] + off);
+            for (int i = 0; i < 4; ++i) raw[mb][i] = ld16_first<AGAIN>(xu[mb][i] + off);
     };
+    constexpr std::integral_constant<bool, false> read_once{};
+    constexpr std::integral_constant<bool, X_READ_AGAIN> read_streamed{};
     auto load_a_unit = [&](u32x4_t (&araw)[NBT][4], int u) {
         const int64_t off = (int64_t)(wave + u * WAVES) * 256;
 #pragma unroll
@@ -238,11 +249,12 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
     };
 
     if constexpr (HUNITS > 0) {
-        // DiReFT, tile resident: issue every load of the wavefront's share, then turn and multiply
+        // DiReFT: the wavefront's first HUNITS units stay in registers between the sweeps: issue
+        // every load of them, then turn and multiply
         u32x4_t raw[HUNITS][MB][4];
 #pragma unroll
         for (int u = 0; u < HUNITS; ++u)
-            if (u < my_ku) load_x_unit(raw[u], u);
+            if (u < my_ku) load_x_unit(raw[u], u, read_once);
 #pragma unroll
         for (int u = 0; u < HUNITS; ++u)
             if (u < my_ku) {
@@ -251,34 +263,34 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
                 unit_to_mfma(raw[u], hreg[u]);
                 mfma_unit(hreg[u], araw);
             }
-    } else {
-        if (my_ku > 0) {
-            u32x4_t x0[MB][4], x1[MB][4], a0[NBT][4], a1[NBT][4], op[MB][4];
-            auto stage_load = [&](u32x4_t (&xr)[MB][4], u32x4_t (&ar)[NBT][4], int u) {
-                load_x_unit(xr, u);
-                if constexpr (PREFETCH_A) load_a_unit(ar, u);
-            };
-            auto stage_compute = [&](const u32x4_t (&xr)[MB][4], u32x4_t (&ar)[NBT][4], int u) {
-                if constexpr (!PREFETCH_A) load_a_unit(ar, u);
-                unit_to_mfma(xr, op);
-                mfma_unit(op, ar);
-            };
-            stage_load(x0, a0, 0);
-            int u = 0;
-            while (u + 2 < my_ku) {
-                stage_load(x1, a1, u + 1);
-                stage_compute(x0, a0, u);
-                stage_load(x0, a0, u + 2);
-                stage_compute(x1, a1, u + 1);
-                u += 2;
-            }
-            if (my_ku - u == 2) {
-                stage_load(x1, a1, u + 1);
-                stage_compute(x0, a0, u);
-                stage_compute(x1, a1, u + 1);
-            } else {
-                stage_compute(x0, a0, u);
-            }
+    }
+    // the units that are not kept (all of them unless HUNITS > 0) are streamed, two in flight
+    if (STREAMS && my_ku > HUNITS) {
+        u32x4_t x0[MB][4], x1[MB][4], a0[NBT][4], a1[NBT][4], op[MB][4];
+        auto stage_load = [&](u32x4_t (&xr)[MB][4], u32x4_t (&ar)[NBT][4], int u) {
+            load_x_unit(xr, u, read_streamed);
+            if constexpr (PREFETCH_A) load_a_unit(ar, u);
+        };
+        auto stage_compute = [&](const u32x4_t (&xr)[MB][4], u32x4_t (&ar)[NBT][4], int u) {
+            if constexpr (!PREFETCH_A) load_a_unit(ar, u);
+            unit_to_mfma(xr, op);
+            mfma_unit(op, ar);
+        };
+        int u = HUNITS;
+        stage_load(x0, a0, u);
+        while (u + 2 < my_ku) {
+            stage_load(x1, a1, u + 1);
+            stage_compute(x0, a0, u);
+            stage_load(x0, a0, u + 2);
+            stage_compute(x1, a1, u + 1);
+            u += 2;
+        }
+        if (my_ku - u == 2) {
+            stage_load(x1, a1, u + 1);
+            stage_compute(x0, a0, u);
+            stage_compute(x1, a1, u + 1);
+        } else {
+            stage_compute(x0, a0, u);
         }
     }
     // tail: at most one 32-column step per wavefront (width not a multiple of 128)
@@ -289,7 +301,8 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
         const u32x4_t zero = {0u, 0u, 0u, 0u};
         const int64_t off = (int64_t)k_tail_step * 64;
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) htail[mb] = as_u32x4(step_to_mfma(col_ok ? ld16_first<X_READ_AGAIN>(xs[mb] + off) : zero));
+        for (int mb = 0; mb < MB; ++mb)
+            htail[mb] = as_u32x4(step_to_mfma(col_ok ? ld16_first<(X_READ_AGAIN && HUNITS == 0)>(xs[mb] + off) : zero));
 #pragma unroll
         for (int b = 0; b < NBT; ++b) {
             const bf16x8_t av = step_to_mfma(col_ok ? ld16(abase[b / NB] + off + aoff_s[b % NB]) : zero);
@@ -478,8 +491,49 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
     const int c_steps = cslice == csplit - 1 ? (d_out + 31) >> 5 : 0;
     const int c_tail_step = c_units * 4 + wave;
 
+    // streamed units first (in place these are second reads: the sooner after the first the better),
+    // then the units held in registers (d_in == d_out: the units of the expand are the units of hreg)
+    if (STREAMS && my_cu > HUNITS) {
+        u32x4_t y0[MB][4], y1[MB][4], yop[MB][4];
+        u32x2_t w0[4][2][NB], w1[4][2][NB];
+        auto stage_load = [&](u32x4_t (&yr)[MB][4], u32x2_t (&wr)[4][2][NB], int u) {
+            load_y_unit(yr, u);
+            if constexpr (PREFETCH_A) load_w_unit(wr, u);
+        };
+        auto stage_compute = [&](const u32x4_t (&yr)[MB][4], u32x2_t (&wr)[4][2][NB], int u) {
+            if constexpr (!PREFETCH_A) load_w_unit(wr, u);
+            unit_to_mfma(yr, yop);
+            finish_unit(yop, wr, u);
+        };
+        int u = HUNITS;
+        if constexpr (EARLY_UNIT && SL == 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) y0[0][i] = y_early[0][i];
+            if constexpr (PREFETCH_A) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) w0[s][e][0] = w_early[s][e][0];
+            }
+        } else {
+            stage_load(y0, w0, u);
+        }
+        while (u + 2 < my_cu) {
+            stage_load(y1, w1, u + 1);
+            stage_compute(y0, w0, u);
+            stage_load(y0, w0, u + 2);
+            stage_compute(y1, w1, u + 1);
+            u += 2;
+        }
+        if (my_cu - u == 2) {
+            stage_load(y1, w1, u + 1);
+            stage_compute(y0, w0, u);
+            stage_compute(y1, w1, u + 1);
+        } else {
+            stage_compute(y0, w0, u);
+        }
+    }
     if constexpr (HUNITS > 0) {
-        // d_in == d_out: the units of the expand are the units held in hreg
 #pragma unroll
         for (int u = 0; u < HUNITS; ++u)
             if (u < my_cu) {
@@ -487,47 +541,6 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
                 load_w_unit(wv, u);
                 finish_unit(hreg[u], wv, u);
             }
-    } else {
-        if (my_cu > 0) {
-            u32x4_t y0[MB][4], y1[MB][4], yop[MB][4];
-            u32x2_t w0[4][2][NB], w1[4][2][NB];
-            auto stage_load = [&](u32x4_t (&yr)[MB][4], u32x2_t (&wr)[4][2][NB], int u) {
-                load_y_unit(yr, u);
-                if constexpr (PREFETCH_A) load_w_unit(wr, u);
-            };
-            auto stage_compute = [&](const u32x4_t (&yr)[MB][4], u32x2_t (&wr)[4][2][NB], int u) {
-                if constexpr (!PREFETCH_A) load_w_unit(wr, u);
-                unit_to_mfma(yr, yop);
-                finish_unit(yop, wr, u);
-            };
-            if constexpr (EARLY_UNIT && SL == 0) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) y0[0][i] = y_early[0][i];
-                if constexpr (PREFETCH_A) {
-#pragma unroll
-                    for (int s = 0; s < 4; ++s)
-#pragma unroll
-                        for (int e = 0; e < 2; ++e) w0[s][e][0] = w_early[s][e][0];
-                }
-            } else {
-                stage_load(y0, w0, 0);
-            }
-            int u = 0;
-            while (u + 2 < my_cu) {
-                stage_load(y1, w1, u + 1);
-                stage_compute(y0, w0, u);
-                stage_load(y0, w0, u + 2);
-                stage_compute(y1, w1, u + 1);
-                u += 2;
-            }
-            if (my_cu - u == 2) {
-                stage_load(y1, w1, u + 1);
-                stage_compute(y0, w0, u);
-                stage_compute(y1, w1, u + 1);
-            } else {
-                stage_compute(y0, w0, u);
-            }
-        }
     }
     // tail step of this wavefront (DiReFT: it still holds those activations in htail)
     if (c_tail_step < c_steps) {
@@ -563,18 +576,18 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
     if constexpr (SLICES > 2) expand_slice(std::integral_constant<int, 2>{});
 }
 
-template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT, int SLICES = 1, bool COLSPLIT = false>
+template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT, int SLICES = 1, bool COLSPLIT = false, bool PARTIAL = false>
 __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) void mfma_tile_kernel(ApplyArgs p)
 {
-    mfma_tile_body<NB, MB, WAVES, HUNITS, DIREFT, SLICES, COLSPLIT>(p);
+    mfma_tile_body<NB, MB, WAVES, HUNITS, DIREFT, SLICES, COLSPLIT, PARTIAL>(p);
 }
 
 // the same for one of several residual streams (in-place calls): blockIdx.y is the layer
-template <int NB, int MB, int WAVES, int HUNITS>
+template <int NB, int MB, int WAVES, int HUNITS, bool PARTIAL = false>
 __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) void mfma_tile_layers_kernel(ApplyArgs p)
 {
     select_layer(p);
-    mfma_tile_body<NB, MB, WAVES, HUNITS, true, 1, false>(p);
+    mfma_tile_body<NB, MB, WAVES, HUNITS, true, 1, false, PARTIAL>(p);
 }
 
 }  // namespace preft

@@ -152,6 +152,15 @@ inline unsigned chunk_grid(const ApplyArgs &a, int64_t S, int rows)
     return (unsigned)(((units + 7) / 8) * 8);
 }
 
+// in place, part of the tile held in registers (HUNITS units of each wavefront), the rest streamed twice
+template <int NB, int MB, int WAVES, int HUNITS>
+void launch_mfma_partial(const ApplyArgs &a, int64_t S, hipStream_t stream)
+{
+    void (*kernel)(ApplyArgs) = mfma_tile_kernel<NB, MB, WAVES, HUNITS, true, 1, false, true>;
+    if (a.h_layers) kernel = mfma_tile_layers_kernel<NB, MB, WAVES, HUNITS, true>;
+    hipLaunchKernelGGL(kernel, dim3(tile_grid(a, S, 16 * MB), a.n_layers), dim3(WAVES * 64), 0, stream, a);
+}
+
 template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT>
 void launch_mfma(const ApplyArgs &a, int64_t S, hipStream_t stream)
 {
@@ -266,7 +275,13 @@ void launch_mfma_nb(const ApplyArgs &a, int64_t S, const Knobs &k, hipStream_t s
         // measured ahead of the resident and row-split shapes at d = 4096 and d = 8192
         if constexpr (NB == 2) {
             if (k.waves == 0 && k.variant == 0 && k.rowblocks == 0) {
-                launch_mfma<2, 2, 4, 0, true>(a, S, stream);
+                // resident == 3 (tests): each wavefront keeps 8 of its units in registers and streams the
+                // rest twice.  Measured on the skewed batch (d = 8192): traffic through the fabric falls
+                // by a sixth (half of the tile is read once), the time by 4 % (5985 against 6216 us): the
+                // 256 + 248 registers leave one workgroup of four wavefronts per compute unit, and what
+                // binds is the latency of the factor sweeps, not the bytes.  Not the default.
+                if (k.resident == 3) launch_mfma_partial<2, 2, 4, 8>(a, S, stream);
+                else                 launch_mfma<2, 2, 4, 0, true>(a, S, stream);
                 return;
             }
         }

@@ -147,6 +147,23 @@ def test_bf16_direft_variants(variant, rank, d, waves, rowblocks):
         print(f"  all_tokens={all_tokens} bias={bias} worst rel err {worst:.2e} counts {counts}")
 
 
+@pytest.mark.parametrize("resident", [3])
+@pytest.mark.parametrize("rank,d", [(32, 8192), (32, 4096), (32, 1160), (20, 8192), (24, 2048), (32, 16384), (28, 520)])
+def test_partially_resident_in_place_tiles(resident, rank, d):
+    """In place at rank 32..64: a wavefront keeps some of its units in registers between the sweeps and
+    streams the others twice (or keeps all of them when the row is narrow enough); ragged widths
+    put the 32-column tail steps on top."""
+    from parity_util import run_direft_case
+    N = 5
+    tab = _mixed_table(rank * 31 + d + resident, N, max_len=40 if d > 4200 else 150, n_prompts=3 if d > 4200 else 6)
+    pool = wl.direft_pool(N, rank, d, "bf16", device="cuda", seed=rank + 1)
+    h = wl.activations(tab.T, d, "bf16", device="cuda", seed=14)
+    for all_tokens, scale, bias in ((False, 1.0, True), (True, 1.0 / np.sqrt(rank), False)):
+        _set(0, 0, 0, resident=resident)
+        worst, counts = run_direft_case(tab, pool, h, "bf16", scale, all_tokens, pad_cols=8, bias=bias)
+        print(f"  resident={resident} r={rank} d={d} all_tokens={all_tokens} worst rel err {worst:.2e} counts {counts}")
+
+
 @pytest.mark.parametrize("rank,d", [(3, 132), (8, 64), (17, 260)])
 def test_fp32_generic_path(rank, d):
     from parity_util import run_direft_case, run_lora_case
