@@ -3,8 +3,15 @@ the CPU oracle on the very same tensors, compare.
 
 Bar (stated here once, used by every parity test):
   * rows outside the position set: bit-identical to the input (compared on the raw bits);
-  * active rows: row-wise max-norm relative error  max_t |g_t - o_t|_inf / |o_t|_inf
+  * active rows, primary figure: row-wise max-norm relative error  max_t |g_t - o_t|_inf / |o_t|_inf
     <= 1e-2 for bf16 storage with fp32 accumulation, <= 1e-5 for fp32;
+  * active rows, secondary figure: elementwise  |g - o| / max(|o|, 1e-3 |o_t|_inf)  (a plain
+    elementwise relative error is ill-posed where y + delta cancels to about zero, hence the floor
+    at a thousandth of the row's largest element).  Computed and printed by every comparison; for
+    bf16 it is asserted <= 1e-2 as well: an element's error is one rounding of the result (<= 2^-9
+    of itself) plus fp32 accumulation error of the order 1e-6 of the row scale, i.e. at most about
+    1e-3 of the floor.  For fp32 the primary bound implies <= 1e-5 / 1e-3 = 1e-2, which is what is
+    asserted;
   * padding beyond the row width (ld > width) and guard rows around the buffer: untouched.
 """
 from __future__ import annotations
@@ -17,7 +24,10 @@ from oracle import preft_oracle as ora
 from paper_2605_14217_amd import workloads as wl
 
 TOL = {"bf16": 1e-2, "f32": 1e-5}
+TOL_ELEMENTWISE = {"bf16": 1e-2, "f32": 1e-2}     # secondary figure, see above
+FLOOR = 1e-3
 GUARD_ROWS = 3
+last_secondary = 0.0                               # secondary figure of the latest compare() call
 
 
 def dev_tables(tab: wl.SegmentTable, device="cuda"):
@@ -49,7 +59,7 @@ def check_guards(buf: torch.Tensor, T: int, d: int, sentinel: float):
 
 
 def compare(got: torch.Tensor, before: torch.Tensor, want64: np.ndarray, row_adapter: np.ndarray,
-            dtype: str, rows=None):
+            dtype: str, rows=None, assert_elementwise=True):
     """got/before: device tensors [T,d] (after / before the call); want64: oracle output for
     `rows` (all rows if None).  Checks every inactive row bitwise (on the device) and the
     selected active rows against the oracle; returns the worst row-wise relative error."""
@@ -65,11 +75,23 @@ def compare(got: torch.Tensor, before: torch.Tensor, want64: np.ndarray, row_ada
     sel_active = active[rows]
     if not sel_active.any():
         return 0.0
-    g = got[torch.from_numpy(rows[sel_active]).to(got.device)].double().cpu().numpy()
-    o = want64[sel_active]
-    err = np.max(np.abs(g - o), axis=1) / np.maximum(np.max(np.abs(o), axis=1), 1e-30)
-    worst = float(err.max())
+    global last_secondary
+    worst, second = 0.0, 0.0
+    act_rows = rows[sel_active]
+    o_all = want64[sel_active]
+    step = max(1, (1 << 27) // max(1, got.shape[1]))          # bounded host memory for large full-size cases
+    for lo in range(0, len(act_rows), step):
+        g = got[torch.from_numpy(act_rows[lo:lo + step]).to(got.device)].double().cpu().numpy()
+        o = o_all[lo:lo + step]
+        diff = np.abs(g - o)
+        row_max = np.maximum(np.max(np.abs(o), axis=1), 1e-30)
+        worst = max(worst, float((np.max(diff, axis=1) / row_max).max()))
+        second = max(second, float((diff / np.maximum(np.abs(o), FLOOR * row_max[:, None])).max()))
+    last_secondary = second
+    print(f"    [parity] rows {len(act_rows)}: row-wise {worst:.2e} (bar {TOL[dtype]:.0e}), "
+          f"elementwise with floor {second:.2e} (bar {TOL_ELEMENTWISE[dtype]:.0e})", flush=True)
     assert worst <= TOL[dtype], f"row-wise relative error {worst:.3e} exceeds {TOL[dtype]:.0e}"
+    assert not assert_elementwise or second <= TOL_ELEMENTWISE[dtype], f"elementwise relative error (floored) {second:.3e} exceeds {TOL_ELEMENTWISE[dtype]:.0e}"
     return worst
 
 
@@ -242,4 +264,7 @@ def run_loreft_case(tab: wl.SegmentTable, W, R, b, h0: torch.Tensor, dtype: str,
     row_adapter = ora.positions(T, tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, N, pos)
     want = ora.loreft(h0.cpu(), tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, [w.cpu() for w in W],
                       [q.cpu() for q in R], None if b is None else [v.cpu() for v in b], r, scale, pos)
-    return compare(h, h0, want, row_adapter, dtype)
+    # secondary figure reported only: the derived factor D = W - R is itself rounded to the storage type,
+    # an error of 2^-9 of each element of D, which reaches an output element scaled by the row, not by
+    # that element
+    return compare(h, h0, want, row_adapter, dtype, assert_elementwise=False)

@@ -31,7 +31,10 @@ LORA = [
     ("llama70b_lora", "down", 1, False), ("llama70b_lora", "k", 16, True),
     ("skewed70b", "res", 32, False), ("skewed70b", "res", 32, True),
     ("llama8b_lora", "gate", 16, False, "dense"), ("llama8b_lora", "down", 16, False, "dense"),
-    ("llama70b_lora", "down", 64, False, "dense"),
+    ("llama8b_lora", "o", 16, True, "dense"), ("llama8b_lora", "v", 8, False, "dense"),
+    ("llama70b_lora", "down", 64, False, "dense"), ("llama70b_lora", "o", 64, False, "dense"),
+    ("llama70b_lora", "gate", 64, True, "dense"), ("llama70b_lora", "o", 32, False, "dense"),
+    ("skewed70b", "res", 32, False, "dense"),
 ]
 
 
@@ -52,19 +55,23 @@ def test_fullsize_lora(case):
     pool = wl.lora_pool(cfg["N"], rank, d_in, d_out, "bf16", device="cuda", seed=5)
     x = wl.activations(tab.T, d_in, "bf16", device="cuda", seed=51)
     y0 = wl.activations(tab.T, d_out, "bf16", device="cuda", seed=52)
-    rows = wl.sample_rows(tab, 2, max_rows=1200)
+    # the 8B LoRA batch is compared whole (every row); the larger batches on a deterministic row sample
+    rows = None if config == "llama8b_lora" else wl.sample_rows(tab, 2, max_rows=1200)
     worst, counts = run_lora_case(tab, pool, x, y0, "bf16", cfg["lora_scale"], all_tokens, rows=rows,
                                   pad_x=0 if dense else _pow2_pad(d_in), pad_y=0 if dense else _pow2_pad(d_out))
-    print(f"  T={tab.T} S={tab.S} rows checked={len(rows)} worst {worst:.2e} counts {counts}")
+    print(f"  T={tab.T} S={tab.S} rows checked={tab.T if rows is None else len(rows)} worst {worst:.2e} counts {counts}")
 
 
-DIREFT = [("llama8b_direft", 8, False), ("llama8b_direft", 16, True), ("skewed70b", 32, False),
-          ("llama70b_lora", 64, False), ("tiny", 4, False)]
+# (config, rank, all positions, prefactor: "1" = Eq. 3 as printed, "rsqrt" = 1 / sqrt(rank) of App. C.2)
+DIREFT = [("llama8b_direft", 8, False, "1"), ("llama8b_direft", 8, True, "rsqrt"), ("llama8b_direft", 16, False, "1"),
+          ("llama8b_direft", 16, True, "rsqrt"), ("llama8b_direft", 16, False, "rsqrt"), ("llama8b_direft", 8, False, "rsqrt"),
+          ("skewed70b", 32, False, "rsqrt"), ("skewed70b", 32, True, "1"),
+          ("llama70b_lora", 64, False, "rsqrt"), ("llama70b_lora", 16, True, "1"), ("tiny", 4, False, "rsqrt")]
 
 
-@pytest.mark.parametrize("config,rank,all_tokens", DIREFT,
-                         ids=[f"{c}-r{r}-{'all' if a else 'prefill'}" for c, r, a in DIREFT])
-def test_fullsize_direft(config, rank, all_tokens):
+@pytest.mark.parametrize("config,rank,all_tokens,prefactor", DIREFT,
+                         ids=[f"{c}-r{r}-{'all' if a else 'prefill'}-s{p}" for c, r, a, p in DIREFT])
+def test_fullsize_direft(config, rank, all_tokens, prefactor):
     from parity_util import run_direft_case
     cfg = wl.CONFIGS[config]
     d = cfg["direft_d"]
@@ -72,22 +79,30 @@ def test_fullsize_direft(config, rank, all_tokens):
     tab = wl.make_segments(config, seed=0)
     pool = wl.direft_pool(cfg["N"], rank, d, dtype, device="cuda", seed=6)
     h = wl.activations(tab.T, d, dtype, device="cuda", seed=61)
-    rows = wl.sample_rows(tab, 2, max_rows=1200)
-    worst, counts = run_direft_case(tab, pool, h, dtype, 1.0 / np.sqrt(rank), all_tokens, rows=rows)
-    print(f"  T={tab.T} S={tab.S} rows checked={len(rows)} worst {worst:.2e} counts {counts}")
+    # the 8B DiReFT batch at rank 16 in prefill-only mode is compared whole; the others on a row sample
+    whole = config in ("tiny",) or (config == "llama8b_direft" and rank == 16 and not all_tokens)
+    rows = None if whole else wl.sample_rows(tab, 2, max_rows=1200)
+    scale = 1.0 if prefactor == "1" else 1.0 / np.sqrt(rank)
+    worst, counts = run_direft_case(tab, pool, h, dtype, scale, all_tokens, rows=rows)
+    print(f"  T={tab.T} S={tab.S} rows checked={tab.T if rows is None else len(rows)} scale={scale:.4f} worst {worst:.2e} counts {counts}")
 
 
 PACKED = [("llama8b_lora", ("q", "k", "v"), 16, False), ("llama8b_lora", ("gate", "up"), 16, False),
           ("llama8b_lora", ("q", "k", "v"), 1, True), ("llama70b_lora", ("q", "k", "v"), 16, True),
-          ("llama70b_lora", ("gate", "up"), 1, False)]
+          ("llama70b_lora", ("gate", "up"), 1, False),
+          # the packed launches of the row-split kernel (rank 32 and 64), on dense rows as bench.py times them
+          ("llama70b_lora", ("q", "k", "v"), 64, False, "dense"), ("llama70b_lora", ("gate", "up"), 64, False, "dense"),
+          ("llama70b_lora", ("q", "k", "v"), 32, True, "dense"), ("llama70b_lora", ("gate", "up"), 64, True)]
 
 
-@pytest.mark.parametrize("config,projs,rank,all_tokens", PACKED,
-                         ids=[f"{c}-{'+'.join(p)}-r{r}-{'all' if a else 'prefill'}" for c, p, r, a in PACKED])
-def test_fullsize_packed_lora(config, projs, rank, all_tokens):
+@pytest.mark.parametrize("case", PACKED,
+                         ids=["-".join([c[0], "+".join(c[1]), f"r{c[2]}", "all" if c[3] else "prefill", *c[4:]]) for c in PACKED])
+def test_fullsize_packed_lora(case):
     """The packed launches of the benchmark step (q+k+v, gate+up), at full size, on sampled rows."""
     from oracle import preft_oracle as ora
     from parity_util import compare, dev_tables, lora_pools_to_device
+    config, projs, rank, all_tokens = case[:4]
+    dense = len(case) > 4
     cfg = wl.CONFIGS[config]
     N = cfg["N"]
     shapes = [cfg["lora_shapes"][p] for p in projs]
@@ -98,7 +113,7 @@ def test_fullsize_packed_lora(config, projs, rank, all_tokens):
     pools = [wl.lora_pool(N, rank, d_in, n, "bf16", device="cuda", seed=72 + i) for i, (_, n) in enumerate(shapes)]
     from parity_util import check_guards, padded
     y0s = [wl.activations(tab.T, n, "bf16", device="cuda", seed=80 + i) for i, (_, n) in enumerate(shapes)]
-    bufs = [padded(y, _pow2_pad(y.shape[1]), 7.0) for y in y0s]       # rows every next power of two, as bench.py lays them out
+    bufs = [padded(y, 0 if dense else _pow2_pad(y.shape[1]), 7.0) for y in y0s]   # dense rows, or rows every next power of two
     ys = [b[1] for b in bufs]
     tables = [lora_pools_to_device(pl) for pl in pools]
     ss, sa, sp = dev_tables(tab)
