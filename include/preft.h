@@ -335,8 +335,11 @@ int preft_loreft_apply(void *h, int64_t ldh, int32_t T, int32_t d,
  *                       without memory that only does the residency bookkeeping.
  * preft_slots_store     copies part `part` of adapter `adapter` from host memory `src`
  *                       (part_bytes[part] bytes) into the store; if the adapter is resident
- *                       its slot is refreshed in place on `stream` (the call first waits
- *                       for `stream`, so a pending copy never reads a half-written record).
+ *                       its slot is refreshed in place on `stream`.  The call first waits for
+ *                       the latest copy that reads this adapter's record (queued by an
+ *                       acquire or an earlier store, on whatever stream, whether or not the
+ *                       adapter is still resident), so no copy ever reads a half-written
+ *                       record.
  * preft_slots_acquire   adapter_ids[n] (host) -> slot_ids[n] (host); ids outside
  *                       [0, n_adapters) map to -1 ("no adapter").  PREFT_ECAPACITY if the call
  *                       names more distinct adapters than there are slots (the manager stays

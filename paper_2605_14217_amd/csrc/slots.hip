@@ -25,12 +25,24 @@ struct preft_slots {
     std::vector<int32_t> adapter_in;               // per slot: adapter or -1
     std::vector<int64_t> last_use;                 // per slot: tick of the last acquire that named it
     std::vector<int64_t> stored;                   // per adapter: bit p set once part p was stored (PREFT_MAX_PARTS <= 64)
+    std::vector<hipEvent_t> read_done;             // per adapter: recorded after the latest copy that reads its pinned
+                                                   // record (created on first use; null: no copy ever read it)
     int64_t tick = 0, hits = 0, misses = 0, evictions = 0, bytes_copied = 0;
 };
 
 namespace {
 
 constexpr size_t PART_ALIGN = 256;
+
+// Marks the point on `st` after which the adapter's pinned record is no longer being read by a copy.
+// preft_slots_store waits for it before it overwrites the record, whichever stream the copy ran on
+// and whether or not the adapter is still resident.
+int mark_record_read(preft_slots *m, int32_t adapter, hipStream_t st)
+{
+    hipEvent_t &ev = m->read_done[(size_t)adapter];
+    if (!ev && hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) { ev = nullptr; return PREFT_EHIP; }
+    return hipEventRecord(ev, st) == hipSuccess ? PREFT_OK : PREFT_EHIP;
+}
 
 int copy_record(preft_slots *m, int32_t adapter, int32_t slot, hipStream_t st)
 {
@@ -39,7 +51,7 @@ int copy_record(preft_slots *m, int32_t adapter, int32_t slot, hipStream_t st)
     char *dst = m->device_slab + (size_t)slot * m->record_bytes;
     if (hipMemcpyAsync(dst, src, m->record_bytes, hipMemcpyHostToDevice, st) != hipSuccess) return PREFT_EHIP;
     m->bytes_copied += (int64_t)m->record_bytes;
-    return PREFT_OK;
+    return mark_record_read(m, adapter, st);
 }
 
 }  // namespace
@@ -66,6 +78,7 @@ int preft_slots_create(preft_slots_t **out, int32_t n_adapters, int32_t n_slots,
     m->adapter_in.assign((size_t)m->n_slots, -1);
     m->last_use.assign((size_t)m->n_slots, 0);
     m->stored.assign((size_t)n_adapters, 0);
+    m->read_done.assign((size_t)n_adapters, nullptr);
     if (n_parts > 0) {
         // pinned host memory is allocated as such (registering existing memory is not used)
         if (hipHostMalloc(reinterpret_cast<void **>(&m->host_store), (size_t)n_adapters * m->record_bytes,
@@ -95,6 +108,8 @@ int preft_slots_destroy(preft_slots_t *m)
 {
     if (!m) return PREFT_OK;
     int rc = PREFT_OK;
+    for (hipEvent_t ev : m->read_done)
+        if (ev && hipEventDestroy(ev) != hipSuccess) rc = PREFT_EHIP;
     if (m->device_tables && hipFree(m->device_tables) != hipSuccess) rc = PREFT_EHIP;
     if (m->device_slab && hipFree(m->device_slab) != hipSuccess) rc = PREFT_EHIP;
     if (m->host_store && hipHostFree(m->host_store) != hipSuccess) rc = PREFT_EHIP;
@@ -108,16 +123,17 @@ int preft_slots_store(preft_slots_t *m, int32_t adapter, int32_t part, const voi
     char *rec = m->host_store + (size_t)adapter * m->record_bytes + m->part_offset[part];
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const int32_t slot = m->slot_of[adapter];
-    if (slot >= 0) {
-        // the pinned record may still be the source of a copy enqueued earlier on this stream
-        if (hipStreamSynchronize(st) != hipSuccess) return PREFT_EHIP;
-    }
+    // The pinned record may still be the source of a copy enqueued earlier -- by an acquire that brought
+    // the adapter in (it may have been evicted since) or by an earlier refresh, on any stream: wait for
+    // the latest such copy, resident or not, before the record is overwritten.
+    if (m->read_done[(size_t)adapter] && hipEventSynchronize(m->read_done[(size_t)adapter]) != hipSuccess) return PREFT_EHIP;
     std::memcpy(rec, src, m->part_bytes[part]);
     m->stored[adapter] |= (int64_t)1 << part;
     if (slot >= 0) {                                   // resident: refresh in place, same address
         char *dst = m->device_slab + (size_t)slot * m->record_bytes + m->part_offset[part];
         if (hipMemcpyAsync(dst, rec, m->part_bytes[part], hipMemcpyHostToDevice, st) != hipSuccess) return PREFT_EHIP;
         m->bytes_copied += (int64_t)m->part_bytes[part];
+        return mark_record_read(m, adapter, st);
     }
     return PREFT_OK;
 }

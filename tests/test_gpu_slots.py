@@ -111,3 +111,39 @@ def test_graph_replay_sees_refreshed_weights():
     finally:
         torch.cuda.synchronize()
         preft.preft_slots_destroy(h)
+
+
+def test_store_right_after_an_eviction_is_ordered_after_the_copy_that_reads_the_record():
+    """An adapter is brought in (asynchronous copy from its pinned record), evicted by the next acquire and
+    updated at once, with no synchronisation by the caller: the store must wait for the copy that may
+    still be reading the record (the adapter is no longer resident, so there is no slot to refresh), and
+    the next acquire must deliver the new weights."""
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+    D2H, D2D = 2, 3
+    N, M, n = 6, 2, 8 << 20                        # 16 MB records: the copies take a while
+    h = preft.preft_slots_create(N, M, [n * 2])
+    try:
+        for i in range(N):
+            preft.preft_slots_store(h, i, 0, torch.full((n,), float(i + 1), dtype=torch.bfloat16))
+        pool = preft.preft_slots_pool(h, 0)
+        ptrs = (ctypes.c_int64 * M)()
+        torch.cuda.synchronize()
+        assert hip.hipMemcpy(ctypes.addressof(ptrs), pool.data_ptr(), 8 * M, D2H) == 0     # the slots' device addresses
+        seen = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+        for rounds in range(3):
+            preft.preft_slots_acquire(h, [0, 1])
+            preft.preft_slots_acquire(h, [2, 3])                         # evicts 0 and 1 while their copies may be in flight
+            assert preft.preft_slots_resident(h, 0) == -1
+            new0 = torch.full((n,), 100.0 + rounds, dtype=torch.bfloat16)
+            preft.preft_slots_store(h, 0, 0, new0)                       # no synchronisation by the caller
+            s0 = preft.preft_slots_acquire(h, [0])[0]
+            torch.cuda.synchronize()
+            assert hip.hipMemcpy(seen.data_ptr(), ptrs[s0], n * 2, D2D) == 0
+            torch.cuda.synchronize()
+            assert torch.equal(seen.cpu(), new0), "the slot does not hold the updated weights"
+        assert preft.preft_slots_stats(h)["evictions"] >= 5
+    finally:
+        torch.cuda.synchronize()
+        preft.preft_slots_destroy(h)
