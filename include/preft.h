@@ -172,10 +172,11 @@ int preft_schedule(void *workspace, size_t workspace_bytes,
  * 14336-wide bf16 buffer with rows every 16384 elements: 64 -> 71 % of peak bandwidth): a caller
  * that owns the layout of its activations should pad wide rows to the next power of two.
  * rank in 1..PREFT_MAX_RANK.  scale is the paper's alpha (or alpha/r), already evaluated.
- * Every rank is computed as given (rank 1 is not padded to 8 in memory).  bf16 ranks 1-3 and the
- * multiples of 4 run at the library's full speed (vector-ALU and matrix-core kernels); the other
- * ranks (5-7, 9-11, ...) take slower kernels: an adapter of such a rank is served faster when its
- * factors are zero-padded to the next multiple of 4.  fp32 takes the per-row kernels.
+ * Every rank is computed as given (rank 1 is not padded to 8 in memory).  bf16 ranks 1-16 and the
+ * multiples of 4 above run at the library's full speed (vector-ALU and matrix-core kernels; ranks
+ * 5-7, 9-11 and 13-15 a few points below their neighbours); the other ranks (17-19, 21-23, ...)
+ * take slower kernels: an adapter of such a rank is served faster when its factors are zero-padded
+ * to the next multiple of 4.  fp32 takes the per-row kernels.
  * Unless mode carries PREFT_SCHEDULE_READY the call first runs the scheduler into
  * `workspace` (>= preft_workspace_bytes(T, S) bytes).
  * T == 0 or S == 0 returns PREFT_OK without launching.

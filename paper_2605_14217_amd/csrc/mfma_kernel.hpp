@@ -82,10 +82,22 @@ constexpr int mfma_min_waves(int NB, int MB, int WAVES, int HUNITS)
 // PARTIAL (in place, HUNITS > 0): the wavefront keeps its first HUNITS units and streams the rest in
 // both sweeps -- for tiles too large to hold (32 rows of 8192 elements are the whole register file).
 // Without it a HUNITS > 0 shape expects every unit to fit (the host picks it only then).
-template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT, int SLICES = 1, bool COLSPLIT = false, bool PARTIAL = false>
+//
+// ODD (rank <= 16): ranks that are not multiples of 4 (5, 6, 7, 9, ...).  Nothing is padded in memory:
+// the shrink's rank rows past r alias row r-1 and their z is zeroed; in the expand a column's r
+// factors no longer start on an 8-byte boundary, so a wavefront fetches its unit's [128 columns][r]
+// block of B -- contiguous in the [d_out, r] layout -- with coalesced 16-byte loads, parks it in its
+// private LDS buffer (the shrink's factor buffer, idle by then) and picks its operands from there,
+// two bytes at a time, zero for the ranks past r.  ODD is the number of 16-byte pieces of that block a
+// lane carries: 2 up to rank 8, 4 up to rank 16.  In place with the tile in registers, the blocks of the
+// first two units are requested before the reduction of z and the next ones while a unit is finished.
+template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT, int SLICES = 1, bool COLSPLIT = false, bool PARTIAL = false,
+          int ODD = 0>
 __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
 {
     static_assert(!PARTIAL || HUNITS > 0, "a partially resident tile keeps some units");
+    static_assert(!ODD || (NB == 1 && SLICES == 1 && !PARTIAL), "the any-rank shape covers rank <= 16, one output");
+    static_assert(ODD == 0 || ODD == 2 || ODD == 4, "pieces per lane of a unit's factor block");
     constexpr bool STREAMS = HUNITS == 0 || PARTIAL;         // some units pass through both sweeps
     static_assert(!COLSPLIT || !DIREFT, "a tile of an in-place call belongs to one workgroup");
     // x is read a second time by this workgroup (in place without a resident tile) or by the
@@ -317,7 +329,7 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
     // first output's y and factor is requested before the reduction of z, so that the sweep over
     // the output starts without a gap.  The addresses are those of the sweep.  (Measured: +1 to +3
     // points of bandwidth with one output, nothing with two, a loss with three.)
-    constexpr bool EARLY_UNIT = SLICES <= 2 && HUNITS == 0 && NB == 1 && MB == 1;
+    constexpr bool EARLY_UNIT = SLICES <= 2 && HUNITS == 0 && NB == 1 && MB == 1 && !ODD;
     u32x4_t y_early[MB][4];
     u32x2_t w_early[4][2][NB];
     if constexpr (EARLY_UNIT) {
@@ -342,6 +354,27 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
                         w_early[s][e][0] = ld8(w0p + (int64_t)4 * e * r * 2 + ((ubase + wave) * 4 + s) * w_step);
             }
         }
+    }
+
+    // what a wavefront holds of a unit's factors between request and use: its MFMA operands
+    // (8-byte pieces straight from memory), or, for ranks that are not multiples of 4, its share
+    // of the unit's contiguous [128 columns][r] block (16 r pieces of 16 bytes, ODD per lane)
+    using wbuf_t = std::conditional_t<(ODD > 0), u32x4_t[ODD > 0 ? ODD : 1], u32x2_t[4][2][NB]>;
+    auto load_w_block = [&](wbuf_t &wb, gcptr_t Bt, int unit_index) {     // any-rank shape only
+        if constexpr (ODD > 0) {
+            gcptr_t base = Bt + (int64_t)unit_index * 256 * r;
+#pragma unroll
+            for (int i = 0; i < ODD; ++i)
+                if (lane + 64 * i < 16 * r) wb[i] = ld16(base + (lane + 64 * i) * 16);
+        }
+    };
+    // in place, tile in registers: the blocks of two units are in flight
+    constexpr int W_AHEAD = (ODD > 0 && HUNITS > 0) ? 2 : 1;
+    wbuf_t w_ahead[W_AHEAD];
+    if constexpr (ODD > 0 && HUNITS > 0) {
+#pragma unroll
+        for (int u = 0; u < W_AHEAD; ++u)
+            if (u < my_ku) load_w_block(w_ahead[u], as_global(p.Bt_pool[adapter]), wave + u * WAVES);
     }
 
     // ---------------------------------------------------------------- reduce over wavefronts
@@ -375,13 +408,14 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
 #pragma unroll
     for (int b = 0; b < NBT; ++b) {
         const int rank0 = 16 * (b % NB) + 4 * g;              // rank within the block's own slice
-        const bool rank_ok = rank0 < r;                       // r % 4 == 0: all four or none
+        const bool rank_ok = rank0 < r;                       // r % 4 == 0: all four or none; else see v_ok
         float bias[4] = {0.f, 0.f, 0.f, 0.f};
         if (DIREFT && rank_ok) {
             gcptr_t bias_p = bias_of(p, adapter);
             if (bias_p) {
 #pragma unroll
-                for (int v = 0; v < 4; ++v) bias[v] = Elem<bf16_tag>::load1(bias_p, rank0 + v);
+                for (int v = 0; v < 4; ++v)
+                    if (!ODD || rank0 + v < r) bias[v] = Elem<bf16_tag>::load1(bias_p, rank0 + v);
             }
         }
 #pragma unroll
@@ -389,7 +423,8 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
             float head_f[4], rem_f[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const float zv = rank_ok ? (acc[b][mb][v] + bias[v]) * p.scale : 0.f;
+                const bool v_ok = ODD ? rank0 + v < r : rank_ok;
+                const float zv = v_ok ? (acc[b][mb][v] + bias[v]) * p.scale : 0.f;
                 const uint32_t hb = pack_bf16(zv, 0.f) & 0xffffu;
                 head_f[v] = zv;
                 rem_f[v] = zv - __uint_as_float(hb << 16);
@@ -404,6 +439,23 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
     }
 
     // ---------------------------------------------------------------- expand (once per output)
+    // any-rank shape: where this lane's factors of step 0, column 8(rl/4) + rl%4 start in the parked block
+    // (steps and the second MFMA of a step move on by an even number of elements), and which of its
+    // four ranks 4g .. 4g+3 exist
+    const int odd_at = (8 * (rl >> 2) + (rl & 3)) * r + 4 * g;
+    const uint32_t *odd_words = reinterpret_cast<const uint32_t *>(tra) + (odd_at >> 1);
+    const uint32_t odd_shift = (odd_at & 1) * 16;
+    const int odd_n = r - 4 * g;
+    const uint32_t odd_mask01 = odd_n >= 2 ? 0xffffffffu : odd_n == 1 ? 0xffffu : 0u;
+    const uint32_t odd_mask23 = odd_n >= 4 ? 0xffffffffu : odd_n == 3 ? 0xffffu : 0u;
+    auto take_early_w = [&](wbuf_t &w) {                      // the factors requested before the reduction of z
+        if constexpr (EARLY_UNIT && PREFETCH_A) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int e = 0; e < 2; ++e) w[s][e][0] = w_early[s][e][0];
+        }
+    };
     auto expand_slice = [&](auto sl_tag) {
     constexpr int SL = decltype(sl_tag)::value;
     gcptr_t Bt = as_global(slice_Bt<SL>(p)[adapter]);
@@ -455,14 +507,38 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
         }
         return Elem<bf16_tag>::pack(out);
     };
-    auto load_w_unit = [&](u32x2_t (&wv)[4][2][NB], int u) {
-        const int cs0 = (ubase + wave + u * WAVES) * 4;
+    auto load_w_unit = [&](wbuf_t &wb, int u) {
+        if constexpr (ODD > 0) {
+            load_w_block(wb, Bt, ubase + wave + u * WAVES);
+        } else {
+            const int cs0 = (ubase + wave + u * WAVES) * 4;
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int e = 0; e < 2; ++e)
+#pragma unroll
+                    for (int b = 0; b < NB; ++b) wb[s][e][b] = ld8(bp[e][b] + (cs0 + s) * w_step);
+        }
+    };
+    // the MFMA operands of step s of a unit from what load_w_unit fetched (any-rank shape: from the
+    // block parked in LDS)
+    auto w_operands = [&](const wbuf_t &wb, int s, u32x2_t (&wv)[2][NB]) {
+        if constexpr (ODD > 0) {
+            // this lane's four factors of a column are two or three consecutive 32-bit words of the
+            // block (three when they start on an odd element): shift them into place, mask the ranks past r
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const uint32_t *w3 = odd_words + (16 * s + 2 * e) * r;
+                const uint32_t d0 = w3[0], d1 = w3[1], d2 = w3[2];
+                wv[e][0] = u32x2_t{__builtin_amdgcn_alignbit(d1, d0, odd_shift) & odd_mask01,
+                                   __builtin_amdgcn_alignbit(d2, d1, odd_shift) & odd_mask23};
+            }
+        } else {
 #pragma unroll
             for (int e = 0; e < 2; ++e)
 #pragma unroll
-                for (int b = 0; b < NB; ++b) wv[s][e][b] = ld8(bp[e][b] + (cs0 + s) * w_step);
+                for (int b = 0; b < NB; ++b) wv[e][b] = wb[s][e][b];
+        }
     };
     auto load_y_unit = [&](u32x4_t (&raw)[MB][4], int u) {
         const int64_t off = (int64_t)(ubase + wave + u * WAVES) * 256;
@@ -472,14 +548,22 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
             for (int i = 0; i < 4; ++i) raw[mb][i] = ld16_stream(yu[mb][i] + off);
     };
     // a whole unit: y (MFMA order) -> out, turned back to load order through LDS and stored
-    auto finish_unit = [&](const u32x4_t (&yop)[MB][4], const u32x2_t (&wv)[4][2][NB], int u) {
+    auto finish_unit = [&](const u32x4_t (&yop)[MB][4], const wbuf_t &wb, int u) {
+        if constexpr (ODD > 0) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+            for (int i = 0; i < ODD; ++i)
+                if (lane + 64 * i < 16 * r) tra[lane + 64 * i] = wb[i];
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            u32x2_t wv[2][NB];
+            w_operands(wb, s, wv);
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
                 const u32x4_t yv = yop[mb][s];
-                tr[(mb * 16 + rl) * MFMA_TRS + 4 * s + g] = expand_step(yv, wv[s], mb);
+                tr[(mb * 16 + rl) * MFMA_TRS + 4 * s + g] = expand_step(yv, wv, mb);
             }
+        }
         const int64_t off = (int64_t)(ubase + wave + u * WAVES) * 256;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
@@ -495,12 +579,12 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
     // then the units held in registers (d_in == d_out: the units of the expand are the units of hreg)
     if (STREAMS && my_cu > HUNITS) {
         u32x4_t y0[MB][4], y1[MB][4], yop[MB][4];
-        u32x2_t w0[4][2][NB], w1[4][2][NB];
-        auto stage_load = [&](u32x4_t (&yr)[MB][4], u32x2_t (&wr)[4][2][NB], int u) {
+        wbuf_t w0, w1;
+        auto stage_load = [&](u32x4_t (&yr)[MB][4], wbuf_t &wr, int u) {
             load_y_unit(yr, u);
             if constexpr (PREFETCH_A) load_w_unit(wr, u);
         };
-        auto stage_compute = [&](const u32x4_t (&yr)[MB][4], u32x2_t (&wr)[4][2][NB], int u) {
+        auto stage_compute = [&](const u32x4_t (&yr)[MB][4], wbuf_t &wr, int u) {
             if constexpr (!PREFETCH_A) load_w_unit(wr, u);
             unit_to_mfma(yr, yop);
             finish_unit(yop, wr, u);
@@ -509,12 +593,7 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
         if constexpr (EARLY_UNIT && SL == 0) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) y0[0][i] = y_early[0][i];
-            if constexpr (PREFETCH_A) {
-#pragma unroll
-                for (int s = 0; s < 4; ++s)
-#pragma unroll
-                    for (int e = 0; e < 2; ++e) w0[s][e][0] = w_early[s][e][0];
-            }
+            take_early_w(w0);
         } else {
             stage_load(y0, w0, u);
         }
@@ -537,9 +616,14 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
 #pragma unroll
         for (int u = 0; u < HUNITS; ++u)
             if (u < my_cu) {
-                u32x2_t wv[4][2][NB];
-                load_w_unit(wv, u);
-                finish_unit(hreg[u], wv, u);
+                if constexpr (ODD > 0) {
+                    finish_unit(hreg[u], w_ahead[u % W_AHEAD], u);
+                    if (u + W_AHEAD < HUNITS && u + W_AHEAD < my_cu) load_w_unit(w_ahead[u % W_AHEAD], u + W_AHEAD);
+                } else {
+                    wbuf_t wb;
+                    load_w_unit(wb, u);
+                    finish_unit(hreg[u], wb, u);
+                }
             }
     }
     // tail step of this wavefront (DiReFT: it still holds those activations in htail)
@@ -555,7 +639,18 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
             const int col = c0 + 8 * (rl >> 2) + 4 * e + (rl & 3);
             const int64_t back = col < d_out ? 0 : (int64_t)(col - (d_out - 1)) * r * 2;
 #pragma unroll
-            for (int b = 0; b < NB; ++b) wv[e][b] = ld8(bp[e][b] + c_tail_step * w_step - back);
+            for (int b = 0; b < NB; ++b) {
+                gcptr_t wp = bp[e][b] + c_tail_step * w_step - back;
+                if constexpr (ODD > 0) {                      // two bytes at a time, zero past rank r
+                    uint32_t f[4];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        f[v] = 4 * g + v < r ? (uint32_t) reinterpret_cast<const PREFT_GLOBAL uint16_t *>(wp)[v] : 0u;
+                    wv[e][b] = u32x2_t{f[0] | (f[1] << 16), f[2] | (f[3] << 16)};
+                } else {
+                    wv[e][b] = ld8(wp);
+                }
+            }
         }
         // every load before the first store: row slots of different blocks may alias one row
         u32x4_t yv[MB];
@@ -576,18 +671,19 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
     if constexpr (SLICES > 2) expand_slice(std::integral_constant<int, 2>{});
 }
 
-template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT, int SLICES = 1, bool COLSPLIT = false, bool PARTIAL = false>
+template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT, int SLICES = 1, bool COLSPLIT = false, bool PARTIAL = false,
+          int ODD = 0>
 __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) void mfma_tile_kernel(ApplyArgs p)
 {
-    mfma_tile_body<NB, MB, WAVES, HUNITS, DIREFT, SLICES, COLSPLIT, PARTIAL>(p);
+    mfma_tile_body<NB, MB, WAVES, HUNITS, DIREFT, SLICES, COLSPLIT, PARTIAL, ODD>(p);
 }
 
 // the same for one of several residual streams (in-place calls): blockIdx.y is the layer
-template <int NB, int MB, int WAVES, int HUNITS, bool PARTIAL = false>
+template <int NB, int MB, int WAVES, int HUNITS, bool PARTIAL = false, int ODD = 0>
 __global__ __launch_bounds__(WAVES * 64, mfma_min_waves(NB, MB, WAVES, HUNITS)) void mfma_tile_layers_kernel(ApplyArgs p)
 {
     select_layer(p);
-    mfma_tile_body<NB, MB, WAVES, HUNITS, true, 1, false, PARTIAL>(p);
+    mfma_tile_body<NB, MB, WAVES, HUNITS, true, 1, false, PARTIAL, ODD>(p);
 }
 
 }  // namespace preft

@@ -347,10 +347,48 @@ void launch_mfma_wide_packed(const ApplyArgs &a, int n_proj, int64_t S, hipStrea
     }
 }
 
+// bf16 ranks up to 16 that are not multiples of 4 (5, 6, 7, 9, ...): the column-split kernel's any-rank
+// shape, 8 wavefronts per 16-row tile; in place with the tile held in registers where it fits
+template <bool DIREFT, int PIECES>
+void launch_mfma_odd_pieces(const ApplyArgs &a, int64_t S, hipStream_t stream)
+{
+    void (*kernel)(ApplyArgs);
+    int waves = 8;
+    if constexpr (DIREFT) {
+        // In place the tile stays in registers where it fits.  Up to 4096 columns: 4 wavefronts of 8
+        // units each (the 8-wavefront shape of the other ranks has no registers left for the factor
+        // block and spills; measured 58 against 55 % of peak at d = 4096), up to 8192: 8 wavefronts of 8
+        const int units = (a.d_in >> 7) + ((a.d_in & 127) ? 1 : 0);
+        const bool L = a.h_layers != nullptr;
+        if (units <= 32) {
+            kernel = L ? mfma_tile_layers_kernel<1, 1, 4, 8, false, PIECES> : mfma_tile_kernel<1, 1, 4, 8, true, 1, false, false, PIECES>;
+            waves = 4;
+        } else if (units <= 64) {
+            kernel = L ? mfma_tile_layers_kernel<1, 1, 8, 8, false, PIECES> : mfma_tile_kernel<1, 1, 8, 8, true, 1, false, false, PIECES>;
+        } else {
+            kernel = L ? mfma_tile_layers_kernel<1, 1, 8, 0, false, PIECES> : mfma_tile_kernel<1, 1, 8, 0, true, 1, false, false, PIECES>;
+        }
+    } else {
+        kernel = a.col_split > 1 ? mfma_tile_kernel<1, 1, 8, 0, false, 1, true, false, PIECES>
+                                 : mfma_tile_kernel<1, 1, 8, 0, false, 1, false, false, PIECES>;
+    }
+    hipLaunchKernelGGL(kernel, dim3(tile_grid(a, S, 16), a.n_layers), dim3(waves * 64), 0, stream, a);
+}
+
+template <bool DIREFT>
+void launch_mfma_odd(const ApplyArgs &a, int64_t S, hipStream_t stream)
+{
+    // a unit's [128 columns][rank] block of the expand factor is 16 * rank pieces of 16 bytes: 2 per lane
+    // up to rank 8, 4 up to rank 16
+    if (a.rank <= 8) launch_mfma_odd_pieces<DIREFT, 2>(a, S, stream);
+    else             launch_mfma_odd_pieces<DIREFT, 4>(a, S, stream);
+}
+
 template <bool DIREFT>
 void launch_mfma_rank(const ApplyArgs &a, int64_t S, const Knobs &k, hipStream_t stream)
 {
     const int nb = (a.rank + 15) / 16;
+    if (a.rank % 4) { launch_mfma_odd<DIREFT>(a, S, stream); return; }      // rank <= 16 (choose_path)
     if (nb <= 1)      launch_mfma_nb<1, DIREFT>(a, S, k, stream);
     else if (nb <= 2) launch_mfma_nb<2, DIREFT>(a, S, k, stream);
     else if (nb <= 4) launch_mfma_nb<4, DIREFT>(a, S, k, stream);
@@ -442,11 +480,13 @@ enum class Path { Rows, Valu, Mfma };
 Path choose_path(int dtype, int rank, const Knobs &k)
 {
     if (dtype != PREFT_BF16 || k.variant == 1) return Path::Rows;
-    const bool valu_ok = rank <= 8, mfma_ok = (rank % 4) == 0;
+    // matrix-core kernels: multiples of 4, and every rank from 5 to 16 (the any-rank shape of the
+    // column-split kernel); ranks 1..3 are a vector-ALU matter
+    const bool valu_ok = rank <= 8, mfma_ok = (rank % 4) == 0 || (rank > 4 && rank < 16);
     if (k.variant == 2 && valu_ok) return Path::Valu;
     if ((k.variant == 3 || k.variant == 4) && mfma_ok) return Path::Mfma;
+    if (rank <= 3) return Path::Valu;
     if (mfma_ok) return Path::Mfma;
-    if (valu_ok) return Path::Valu;
     return Path::Rows;
 }
 

@@ -147,6 +147,34 @@ def test_bf16_direft_variants(variant, rank, d, waves, rowblocks):
         print(f"  all_tokens={all_tokens} bias={bias} worst rel err {worst:.2e} counts {counts}")
 
 
+@pytest.mark.parametrize("rank", [5, 6, 7, 9, 10, 11, 13, 14, 15])
+def test_ranks_that_are_not_multiples_of_four_on_the_matrix_core_kernel(rank):
+    """bf16 ranks 5..15 other than 8 and 12 take the column-split MFMA kernel's any-rank shape (nothing
+    padded in memory): LoRA on ragged widths, DiReFT with the tile held in registers (d <= 8192) and
+    streamed (d > 8192), with and without bias, both modes, small-batch shape included."""
+    from parity_util import run_direft_case, run_lora_case
+    N = 5
+    shapes = [(512, 1024), (1000, 264), (136, 4096)][rank % 3:][:2]
+    for d_in, d_out in shapes:
+        for n_prompts, max_len in ((6, 300), (2, 60)):            # a large batch and one of the small-batch shape
+            tab = _mixed_table(rank * 13 + d_in + n_prompts, N, n_prompts=n_prompts, max_len=max_len)
+            pool = wl.lora_pool(N, rank, d_in, d_out, "bf16", device="cuda", seed=rank)
+            x = wl.activations(tab.T, d_in, "bf16", device="cuda", seed=11)
+            y0 = wl.activations(tab.T, d_out, "bf16", device="cuda", seed=12)
+            for all_tokens in (False, True):
+                _set()
+                worst, counts = run_lora_case(tab, pool, x, y0, "bf16", 2.0, all_tokens, pad_cols=8, perm=[2, 4, 0, 3, 1])
+                print(f"  lora r={rank} {d_in}->{d_out} T={tab.T} all_tokens={all_tokens} worst {worst:.2e}")
+    for d in ((4096, 520) if rank % 2 else (8192, 264)) + ((16384 + 8,) if rank in (7, 10) else ()):
+        tab = _mixed_table(rank * 17 + d, N, max_len=40 if d > 4200 else 200, n_prompts=3 if d > 4200 else 6)
+        pool = wl.direft_pool(N, rank, d, "bf16", device="cuda", seed=rank + 2)
+        h = wl.activations(tab.T, d, "bf16", device="cuda", seed=13)
+        for all_tokens, scale, bias in ((False, 1.0, True), (True, 1.0 / np.sqrt(rank), False)):
+            _set()
+            worst, counts = run_direft_case(tab, pool, h, "bf16", scale, all_tokens, pad_cols=8, bias=bias)
+            print(f"  direft r={rank} d={d} all_tokens={all_tokens} bias={bias} worst {worst:.2e}")
+
+
 @pytest.mark.parametrize("resident", [3])
 @pytest.mark.parametrize("rank,d", [(32, 8192), (32, 4096), (32, 1160), (20, 8192), (24, 2048), (32, 16384), (28, 520)])
 def test_partially_resident_in_place_tiles(resident, rank, d):
@@ -858,6 +886,7 @@ LAYER_CASES = [
     (0, "bf16", 16, 1000, 3, 0, 0), (0, "bf16", 32, 1024, 2, 0, 0), (0, "bf16", 64, 512, 3, 0, 0),   # streamed, row-split
     (0, "bf16", 2, 520, 4, 0, 0), (0, "bf16", 7, 256, 2, 0, 0), (VARIANT_VALU, "bf16", 4, 512, 2, 2, 0),
     (VARIANT_ROW, "bf16", 12, 264, 3, 0, 0), (0, "f32", 4, 132, 5, 0, 0), (0, "bf16", 24, 264, 2, 0, 0),
+    (0, "bf16", 5, 4096, 2, 0, 0), (0, "bf16", 11, 8192 + 32, 2, 0, 0), (0, "bf16", 13, 8192 + 264, 2, 0, 0),   # any-rank shapes
 ]
 
 
@@ -919,6 +948,8 @@ EXACT_CASES = [
     # (dtype, variant, rank, d_in, d_out): one case per kernel family
     ("bf16", VARIANT_AUTO, 16, 256, 384), ("bf16", VARIANT_AUTO, 8, 200, 72), ("bf16", VARIANT_VALU, 2, 136, 264),
     ("bf16", VARIANT_AUTO, 32, 256, 256), ("bf16", VARIANT_AUTO, 64, 128, 384), ("bf16", VARIANT_ROW, 5, 64, 40),
+    ("bf16", VARIANT_AUTO, 5, 256, 384), ("bf16", VARIANT_AUTO, 7, 200, 136), ("bf16", VARIANT_AUTO, 11, 128, 264),
+    ("bf16", VARIANT_AUTO, 14, 264, 128),
     ("f32", VARIANT_AUTO, 4, 132, 68), ("f32", VARIANT_AUTO, 9, 64, 64),
 ]
 
