@@ -96,7 +96,7 @@ template <int NB, int MB, int WAVES, int HUNITS, bool DIREFT, int SLICES = 1, bo
 __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
 {
     static_assert(!PARTIAL || HUNITS > 0, "a partially resident tile keeps some units");
-    static_assert(!ODD || (NB == 1 && SLICES == 1 && !PARTIAL), "the any-rank shape covers rank <= 16, one output");
+    static_assert(!ODD || (NB == 1 && !PARTIAL), "the any-rank shape covers rank <= 16");
     static_assert(ODD == 0 || ODD == 2 || ODD == 4, "pieces per lane of a unit's factor block");
     constexpr bool STREAMS = HUNITS == 0 || PARTIAL;         // some units pass through both sweeps
     static_assert(!COLSPLIT || !DIREFT, "a tile of an in-place call belongs to one workgroup");

@@ -138,11 +138,11 @@ inline int choose_col_split(int32_t T, const Knobs &k)
 }
 
 // the small-batch shape of the column-split kernel (col_split > 1): one shape per rank class
-template <int NB, int SLICES>
+template <int NB, int SLICES, int PIECES = 0>
 void launch_mfma_colsplit(const ApplyArgs &a, int64_t S, hipStream_t stream)
 {
     constexpr int WAVES = NB >= 4 ? 4 : 8;                 // register budget
-    hipLaunchKernelGGL((mfma_tile_kernel<NB, 1, WAVES, 0, false, SLICES, true>), dim3(tile_grid(a, S, 16)),
+    hipLaunchKernelGGL((mfma_tile_kernel<NB, 1, WAVES, 0, false, SLICES, true, false, PIECES>), dim3(tile_grid(a, S, 16)),
                        dim3(WAVES * 64), 0, stream, a);
 }
 // the row-split kernel takes whole chunks only
@@ -303,23 +303,24 @@ void launch_mfma_nb(const ApplyArgs &a, int64_t S, const Knobs &k, hipStream_t s
     launch_mfma_stream<NB, DIREFT>(a, S, mb, waves, stream);
 }
 
-// packed projections (LoRA, rank <= 16): one shrink sweep over x, one expand sweep per output
-template <int SLICES>
+// packed projections (LoRA, rank <= 16): one shrink sweep over x, one expand sweep per output.
+// PIECES > 0: the any-rank shape (ranks that are not multiples of 4)
+template <int SLICES, int PIECES = 0>
 void launch_mfma_packed(const ApplyArgs &a, int64_t S, const Knobs &k, hipStream_t stream)
 {
     if (a.col_split > 1) {
-        launch_mfma_colsplit<1, SLICES>(a, S, stream);
+        launch_mfma_colsplit<1, SLICES, PIECES>(a, S, stream);
         return;
     }
     // three outputs: 4 wavefronts per tile leave room for two workgroups per compute unit (measured
     // better on small and large batches); two outputs: as for a single projection
     const int waves = k.waves ? (k.waves == 8 ? 8 : 4) : (SLICES == 2 ? 8 : 4);
     if (waves == 8)
-        hipLaunchKernelGGL((mfma_tile_kernel<1, 1, 8, 0, false, SLICES>), dim3(tile_grid(a, S, 16)), dim3(512), 0,
-                           stream, a);
+        hipLaunchKernelGGL((mfma_tile_kernel<1, 1, 8, 0, false, SLICES, false, false, PIECES>), dim3(tile_grid(a, S, 16)),
+                           dim3(512), 0, stream, a);
     else
-        hipLaunchKernelGGL((mfma_tile_kernel<1, 1, 4, 0, false, SLICES>), dim3(tile_grid(a, S, 16)), dim3(256), 0,
-                           stream, a);
+        hipLaunchKernelGGL((mfma_tile_kernel<1, 1, 4, 0, false, SLICES, false, false, PIECES>), dim3(tile_grid(a, S, 16)),
+                           dim3(256), 0, stream, a);
 }
 
 // packed projections at rank 32..64 (widths multiples of 128): the row-split kernel with one sweep
@@ -651,7 +652,7 @@ int preft_lora_apply_packed(int32_t n_proj, void *const *y, const int64_t *ldy, 
     }
     const int ready = mode | PREFT_SCHEDULE_READY;
     const Knobs k = knobs_of(mode);
-    const bool fused_mfma = n_proj > 1 && dtype == PREFT_BF16 && rank <= 16 && (rank % 4) == 0 &&
+    const bool fused_mfma = n_proj > 1 && dtype == PREFT_BF16 && rank >= 4 && rank <= 16 &&
                             (k.variant == 0 || k.variant == 3);
     const bool fused_valu = n_proj > 1 && dtype == PREFT_BF16 && rank <= 3 && (k.variant == 0 || k.variant == 2) &&
                             (k.waves == 0 || k.waves == 4);
@@ -681,8 +682,16 @@ int preft_lora_apply_packed(int32_t n_proj, void *const *y, const int64_t *ldy, 
         else            launch_mfma_wide_packed<4>(a, n_proj, S, st);
     } else if (fused_mfma) {
         a.col_split = choose_col_split(T, k);
-        if (n_proj == 2) launch_mfma_packed<2>(a, S, k, st);
-        else             launch_mfma_packed<3>(a, S, k, st);
+        const int pieces = (rank % 4) == 0 ? 0 : rank < 8 ? 2 : 4;      // the any-rank shape's block pieces per lane
+        if (n_proj == 2) {
+            if (pieces == 0)      launch_mfma_packed<2>(a, S, k, st);
+            else if (pieces == 2) launch_mfma_packed<2, 2>(a, S, k, st);
+            else                  launch_mfma_packed<2, 4>(a, S, k, st);
+        } else {
+            if (pieces == 0)      launch_mfma_packed<3>(a, S, k, st);
+            else if (pieces == 2) launch_mfma_packed<3, 2>(a, S, k, st);
+            else                  launch_mfma_packed<3, 4>(a, S, k, st);
+        }
     } else {
         if (n_proj == 2) launch_valu_packed<2>(a, S, st);
         else             launch_valu_packed<3>(a, S, st);

@@ -755,7 +755,11 @@ def _packed_case(dtype, r, d_in, d_outs, fused_buffer, seed, all_tokens, S=30, m
     ("bf16", 3, 512, (512, 128, 128), False),        # ranks 1..3: fused by the vector-ALU kernel
     ("bf16", 1, 4096, (4096, 1024, 1024), True),
     ("bf16", 2, 520, (1408, 264), False),
-    ("bf16", 5, 512, (512, 128), True),              # a rank neither kernel fuses: one launch each
+    ("bf16", 5, 512, (512, 128), True),              # ranks 5..15 that are not multiples of 4: the any-rank shape
+    ("bf16", 7, 1000, (264, 520, 136), False),
+    ("bf16", 11, 4096, (4096, 1024, 1024), True),
+    ("bf16", 13, 512, (1408, 1408), True),
+    ("bf16", 17, 256, (256, 128), False),            # a rank no kernel fuses: one launch each
     ("f32", 4, 256, (256, 64), True),
     ("bf16", 16, 512, (384,), False),                # a single projection is an ordinary apply
 ])
@@ -779,10 +783,12 @@ def test_packed_projections_in_the_row_split_kernel(r, d_in, d_outs, fused_buffe
         print(f"  packed r={r} {d_in}->{d_outs} fused_buffer={fused_buffer} all_tokens={all_tokens} worst {worst:.2e}")
 
 
-@pytest.mark.parametrize("rank,d_in,d_outs", [(32, 256, (256, 128, 128)), (64, 128, (384, 128)), (64, 384, (128, 128, 256))])
+@pytest.mark.parametrize("rank,d_in,d_outs", [(32, 256, (256, 128, 128)), (64, 128, (384, 128)), (64, 384, (128, 128, 256)),
+                                              (7, 264, (256, 136, 128)), (13, 128, (392, 128))])
 def test_packed_row_split_kernel_gives_the_exactly_rounded_result(rank, d_in, d_outs):
     """Small-integer data (every product and sum exact on both sides): the packed launch must equal
-    the oracle's result rounded once to bf16, bit for bit, on every output."""
+    the oracle's result rounded once to bf16, bit for bit, on every output.  (Rank 32 and 64: the
+    row-split kernel; rank 7 and 13: the column-split kernel's any-rank shape.)"""
     from oracle import preft_oracle as ora
     from parity_util import dev_tables
     N = 4
@@ -868,8 +874,9 @@ def test_column_split_with_packed_projections_and_in_place_calls(colsplit):
     _set()
     _set_colsplit(colsplit)
     for all_tokens in (False, True):
-        worst = _packed_case("bf16", 16, 512, [512, 128, 264], True, 800 + colsplit, all_tokens, S=12, max_len=60)
-        print(f"  colsplit={colsplit} packed all_tokens={all_tokens} worst {worst:.2e}")
+        for r, d_outs in ((16, [512, 128, 264]), (6, [512, 128, 264]), (15, [264, 512])):
+            worst = _packed_case("bf16", r, 512, d_outs, True, 800 + colsplit + r, all_tokens, S=12, max_len=60)
+            print(f"  colsplit={colsplit} packed r={r} all_tokens={all_tokens} worst {worst:.2e}")
     N, r, d = 4, 16, 1000
     tab = _mixed_table(810, N, n_prompts=3, max_len=90, n_decode=12)
     pool = wl.direft_pool(N, r, d, "bf16", device="cuda", seed=81)
