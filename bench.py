@@ -73,6 +73,8 @@ def parse_args():
     ap.add_argument("--no-trace", action="store_true", help="skip the serving-trace replay leg")
     ap.add_argument("--no-packed", action="store_true",
                     help="one launch per projection instead of packed q,k,v and gate,up launches")
+    ap.add_argument("--no-z", action="store_true",
+                    help="workspace without room for z: every LoRA call runs both sweeps in one launch")
     ap.add_argument("--only", default="", help="experiment: comma-separated subset of projections")
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--waves", type=int, default=0)
@@ -94,7 +96,7 @@ def parse_args():
 
 def experiment_flags(args):
     return bool(args.variant or args.waves or args.rowblocks or args.colsplit or args.resident or args.ldpad or args.only
-                or args.no_packed)
+                or args.no_packed or args.no_z)
 
 
 def run(args):
@@ -122,7 +124,9 @@ def run(args):
     T_act = tab.active_rows(False, N)
     n_ad = tab.distinct_active_adapters(False, N)
     ss, sa, sp = (torch.from_numpy(a.copy()).to(dev) for a in (tab.seg_start, tab.seg_adapter, tab.seg_prefill_len))
-    ws = preft.new_workspace(T, S, device=dev)
+    # with room for z the single-output LoRA calls at rank 20..64 run their sweeps as two launches
+    # (preft_workspace_bytes_z)
+    ws = preft.new_workspace(T, S, device=dev, z_rank=0 if args.no_z else r)
 
     # ---- buffers and pools --------------------------------------------------------------
     projs = []
@@ -283,6 +287,7 @@ def run(args):
                    "row_pitch": ("dense (row pitch = width)" if args.pitch == "dense" else
                                  "next power of two (rows of 14336 or 28672 elements start every 16384 or 32768; "
                                  "the padding is never touched)") + (f" + {args.ldpad}" if args.ldpad else ""),
+                   "workspace_bytes": int(ws.numel()),
                    "schedule": {"chunks": counts[0], "short_rows": counts[1]}},
         "roofline": roofline,
         "pct_peak_hbm": round(100 * achieved / PEAK_HBM_GBPS, 2),

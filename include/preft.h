@@ -85,6 +85,8 @@ enum {
  *                            4 = MFMA tile kernel, row-split shape with the factors shared
  *                                through LDS where it applies (widths multiples of 128), and
  *                                no register-resident DiReFT
+ *                            5 = automatic, but both sweeps of a LoRA call in one launch even
+ *                                if the workspace has room for z (preft_workspace_bytes_z)
  *   PREFT_TEST_WAVES(w)      wavefronts per tile workgroup: 0 = automatic, else 1, 2, 4 or 8
  *                            (any non-zero value also makes DiReFT stream its tile instead
  *                            of holding it in registers)
@@ -133,6 +135,20 @@ enum {
  * The workspace must be 16-byte aligned.  Returns 0 if T or S is negative.
  */
 size_t preft_workspace_bytes(int32_t T, int32_t S);
+
+/*
+ * Bytes of a workspace that, beyond the schedule, has room for the intermediate z = A_i x of Eq. 2 of
+ * every active row (LoRA calls of up to `rank`).  A preft_lora_apply call (bf16, rank 20..64 in
+ * multiples of 4, more than 1024 rows, d_in a multiple of 128, d_out a multiple of 256) that is
+ * handed at least this many bytes runs its two sweeps as two launches -- shrink into z, then the
+ * expand in 2-D tiles -- which measured 2-5 % faster on batches of several GB; with fewer bytes, or
+ * outside those limits, the same call runs as before, and packed calls always do.  The result is
+ * the same bit for bit.  The z area lies behind the schedule and is rewritten by every such call:
+ * calls that share a workspace must be ordered on one stream, as they must be for the schedule
+ * already.
+ * Returns 0 for a negative T or S or a rank outside 1..PREFT_MAX_RANK.
+ */
+size_t preft_workspace_bytes_z(int32_t T, int32_t S, int32_t rank);
 
 /*
  * Token-segment scheduler (paper Eq. 1 and Eq. 4; App. D.3 "position mask", which the

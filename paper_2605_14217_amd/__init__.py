@@ -11,7 +11,7 @@ from .binding import (  # noqa: F401
     test_flags, set_test_flags, PREFT_ESCHEDULE, PREFT_ETOOLARGE, PREFT_STATIC_SCRATCH_BYTES,
     PreftError, load_library, pointer_table, preft_direft_apply, preft_direft_apply_static, preft_direft_apply_layers, preft_lora_apply, preft_lora_apply_packed, preft_loreft_apply,
     preft_loreft_prepare, preft_schedule,
-    preft_schedule_counts, preft_strerror, preft_version, preft_workspace_bytes,
+    preft_schedule_counts, preft_strerror, preft_version, preft_workspace_bytes, preft_workspace_bytes_z,
     new_workspace, preft_slots_create, preft_slots_destroy, preft_slots_store, preft_slots_acquire,
     preft_slots_pool, preft_slots_resident, preft_slots_stats, PREFT_ECAPACITY,
 )

@@ -68,7 +68,7 @@ def _mode(mode: int) -> int:
     return int(mode) | _extra_mode_bits
 
 # every symbol include/preft.h declares
-ABI_SYMBOLS = ("preft_workspace_bytes", "preft_schedule", "preft_lora_apply", "preft_lora_apply_packed",
+ABI_SYMBOLS = ("preft_workspace_bytes", "preft_workspace_bytes_z", "preft_schedule", "preft_lora_apply", "preft_lora_apply_packed",
                "preft_direft_apply", "preft_direft_apply_static", "preft_direft_apply_layers",
                "preft_loreft_prepare", "preft_loreft_apply", "preft_slots_create", "preft_slots_destroy",
                "preft_slots_store", "preft_slots_acquire", "preft_slots_pool", "preft_slots_resident",
@@ -99,6 +99,8 @@ def load_library(path: Optional[str] = None):
     vp, i32, i64, sz = c.c_void_p, c.c_int32, c.c_int64, c.c_size_t
     lib.preft_workspace_bytes.restype = sz
     lib.preft_workspace_bytes.argtypes = [i32, i32]
+    lib.preft_workspace_bytes_z.restype = sz
+    lib.preft_workspace_bytes_z.argtypes = [i32, i32, i32]
     lib.preft_schedule.restype = c.c_int
     lib.preft_schedule.argtypes = [vp, sz, vp, vp, vp, i32, i32, i32, c.c_int, vp]
     lib.preft_lora_apply.restype = c.c_int
@@ -214,9 +216,15 @@ def preft_workspace_bytes(T: int, S: int) -> int:
     return int(load_library().preft_workspace_bytes(int(T), int(S)))
 
 
-def new_workspace(T: int, S: int, device="cuda") -> torch.Tensor:
-    """Caller-owned workspace for a batch of T rows in S segments."""
-    return torch.empty(max(preft_workspace_bytes(T, S), 16), dtype=torch.uint8, device=device)
+def preft_workspace_bytes_z(T: int, S: int, rank: int) -> int:
+    return int(load_library().preft_workspace_bytes_z(int(T), int(S), int(rank)))
+
+
+def new_workspace(T: int, S: int, device="cuda", z_rank: int = 0) -> torch.Tensor:
+    """Caller-owned workspace for a batch of T rows in S segments; with z_rank > 0 it also has room for
+    the intermediate z of LoRA calls of up to that rank (preft_workspace_bytes_z)."""
+    n = preft_workspace_bytes_z(T, S, z_rank) if z_rank > 0 else preft_workspace_bytes(T, S)
+    return torch.empty(max(n, 16), dtype=torch.uint8, device=device)
 
 
 def preft_schedule(workspace: torch.Tensor, seg_start, seg_adapter, seg_prefill_len, T: int, N: int,

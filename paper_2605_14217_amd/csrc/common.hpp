@@ -201,6 +201,7 @@ struct ApplyArgs {
     const int4         *chunks;
     const int2         *shorts;
     const int4         *gtiles;
+    void               *zws;             // z area of the workspace (two-launch LoRA), or null
     int32_t             gathered_only;   // tile kernels: skip the chunks (another launch covers them)
     int32_t             col_split;       // >= 1: workgroups per tile, each expanding its share of the columns
     // packed projections (LoRA only): further outputs computed from the same x, each with its

@@ -48,10 +48,15 @@ constexpr int wide_lds_bytes(int NB, int MB, int RW, int CW)
     return RW * CW * MB * 16 * MFMA_TRS * 16 + 2 * wide_fac_bytes(NB, CW);
 }
 
-template <int NB, int MB, int RW, int CW, bool DIREFT, int SLICES = 1>
+//
+// ZOUT (LoRA only): the shrink sweep alone.  z, already in the form the expand's MFMAs take it (scaled,
+// split into bf16 head and remainder, in lane order), goes to the z area of the workspace, 1 KB per
+// 16-row block and rank block, and mfma_expand_panel_kernel does the expand in a second launch.
+template <int NB, int MB, int RW, int CW, bool DIREFT, int SLICES = 1, bool ZOUT = false>
 __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
 {
     static_assert(SLICES == 1 || !DIREFT, "packed projections are a LoRA feature");
+    static_assert(!ZOUT || (!DIREFT && MB == 1 && SLICES == 1), "the two-launch form: LoRA, one output, 16-row blocks per wavefront");
     constexpr int WAVES = RW * CW;
     constexpr int NBT = NB * SLICES;                          // accumulator blocks of the shrink sweep
     constexpr int R = 16 * MB * RW;
@@ -296,6 +301,16 @@ __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
         }
     }
 
+    if constexpr (ZOUT) {
+        if (cg == 0) {                                        // with column groups every one of them holds the same z
+            const int64_t blk16 = (int64_t)(unit_id / TPC) * (CHUNK_ROWS / 16) + tile_row0 / 16 + rb;
+            u32x4_t *zw = reinterpret_cast<u32x4_t *>(p.zws) + blk16 * (NBT * 64) + lane;
+#pragma unroll
+            for (int b = 0; b < NBT; ++b) zw[b * 64] = as_u32x4(zop[b][0]);
+        }
+        return;
+    }
+
     // ---------------------------------------------------------------- expand (once per output)
     // B units in LDS: column c of the step (0 .. 128 CW - 1) at byte c * CS, its r factors contiguous; CS = 2r + 8.
     const int cs = 2 * r + 8;
@@ -451,10 +466,143 @@ constexpr int wide_min_waves(int RW, int CW, int SLICES)
     return (RW * CW == 4 && SLICES > 1) ? 2 : 1;
 }
 
-template <int NB, int MB, int RW, int CW, bool DIREFT, int SLICES = 1>
+template <int NB, int MB, int RW, int CW, bool DIREFT, int SLICES = 1, bool ZOUT = false>
 __global__ __launch_bounds__(RW * CW * 64, wide_min_waves(RW, CW, SLICES)) void mfma_wide_kernel(ApplyArgs p)
 {
-    mfma_wide_body<NB, MB, RW, CW, DIREFT, SLICES>(p);
+    mfma_wide_body<NB, MB, RW, CW, DIREFT, SLICES, ZOUT>(p);
+}
+
+// The expand sweep as a launch of its own (LoRA, after a ZOUT launch of the kernel above), in 2-D tiles:
+// a workgroup of RW wavefronts takes 16 RW rows x PU units of 128 columns of one output; neighbouring
+// workgroups take neighbouring column panels of the same rows.  Why: what the memory system rewards is
+// a small set of rows in flight.  Measured with a kernel that only moves the bytes (read and write y,
+// 352 814 rows): 64-row tiles that sweep all 8192 columns of their rows sustain 62 % of the 8 TB/s
+// peak, the same tiles cut into 32 panels of 256 columns 77 % (16-row tiles of 8 wavefronts: 71 -> 83 %
+// with 1024-column panels; on dense 28 672-wide rows 63 -> 68 % and 65 -> 71 %).  A workgroup that
+// sweeps only a panel cannot afford the shrink sweep over the whole of x, hence the two launches, with z
+// (r values per row) through HBM in between: 4 r bytes per row against 2 (d_in + 2 d_out).  One output per
+// call: see the notes at the launch site.
+// The panel's factors (PU * 128 columns x r, contiguous in [d_out, r]) go to LDS once per workgroup
+// and are shared by its RW row blocks; operand layouts as in the expand of mfma_wide_body.
+// 52 KB of LDS at rank 64: three workgroups per compute unit, and the register allocation is held to that.
+template <int NB, int RW, int PU>
+__global__ __launch_bounds__(RW * 64, 3) void mfma_expand_panel_kernel(ApplyArgs p)
+{
+    constexpr int R = 16 * RW;
+    constexpr int TPC = CHUNK_ROWS / R;
+    constexpr int NT = RW * 64;
+    constexpr int B_ITERS = (NB * 16 * 16 * PU + NT - 1) / NT;   // upper bound: 16 r PU pieces, r <= 16 NB
+    constexpr int B_BYTES = PU * 128 * (32 * NB + 8);            // column c of the panel at byte c * (2r + 8)
+    static_assert(CHUNK_ROWS % R == 0, "tile height must divide the chunk height");
+    __shared__ __attribute__((aligned(16))) char lds_raw[RW * 16 * MFMA_TRS * 16 + B_BYTES];
+
+    if (!schedule_matches(p)) return;
+    const int64_t ldy_b = p.ldy * 2;
+    const int panels = p.d_out / (128 * PU);                  // d_out % (128 PU) == 0 (host-checked)
+    const int id = xcd_unit(p.header[HDR_CHUNKS] * TPC * panels);
+    if (id < 0) return;
+    const int tile = id / panels, panel = id - tile * panels;
+    const int4 ch = p.chunks[tile / TPC];
+    const int tile_row0 = (tile % TPC) * R;
+    if (tile_row0 >= ch.z) return;                            // uniform over the workgroup
+    const int adapter = ch.x;
+    const int n_rows = min(R, ch.z - tile_row0);
+
+    const int tid = threadIdx.x, rb = tid >> 6, lane = tid & 63;
+    const int rl = lane & 15, g = lane >> 4;                  // MFMA order
+    const int q = lane >> 4, c16 = lane & 15;                 // unit load order
+    const int r = p.rank;
+    u32x4_t *tr = reinterpret_cast<u32x4_t *>(lds_raw) + rb * (16 * MFMA_TRS);
+    char *fb = lds_raw + RW * 16 * MFMA_TRS * 16;
+
+    // requests first: the panel's factors, this row block's z, its PU units of y
+    gcptr_t Wp = as_global(p.Bt_pool[adapter]) + (int64_t)panel * (PU * 256) * r;
+    const int b_halves = 32 * r * PU;                         // 8-byte halves of the panel's factors
+    u32x4_t breg[B_ITERS];
+#pragma unroll
+    for (int i = 0; i < B_ITERS; ++i) {
+        const int piece = tid + i * NT;
+        if (piece * 2 < b_halves) breg[i] = ld16(Wp + (int64_t)piece * 16);
+    }
+    const int64_t blk16 = (int64_t)(tile / TPC) * (CHUNK_ROWS / 16) + tile_row0 / 16 + rb;
+    gcptr_t zw = as_global(p.zws) + (blk16 * NB * 64 + lane) * 16;
+    bf16x8_t zop[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) zop[b] = as_bf16x8(ld16(zw + b * 1024));
+    gptr_t yu[4];
+    bool row_ok[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int t = rb * 16 + 4 * i + q;
+        row_ok[i] = t < n_rows;                               // rows past the tile alias its last row; their stores are masked
+        yu[i] = as_global(p.y) + ((int64_t)ch.y + tile_row0 + min(t, n_rows - 1)) * ldy_b + (int64_t)panel * (PU * 256) + c16 * 16;
+    }
+    u32x4_t Y[PU][4];
+#pragma unroll
+    for (int u = 0; u < PU; ++u)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) Y[u][i] = ld16_stream(yu[i] + u * 256);
+
+    // factors to LDS: two 8-byte halves per piece, a half never straddles a column because r % 4 == 0
+    const int cs = 2 * r + 8;
+#pragma unroll
+    for (int i = 0; i < B_ITERS; ++i) {
+        const int piece = tid + i * NT;
+        if (piece * 2 < b_halves) {
+            const u32x4_t v = breg[i];
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                const int byte = (piece * 2 + hh) * 8;
+                const int col = byte / (2 * r);
+                *reinterpret_cast<u32x2_t *>(fb + col * cs + (byte - col * 2 * r)) = u32x2_t{v[2 * hh], v[2 * hh + 1]};
+            }
+        }
+    }
+    int w_off[2][NB];
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int rank0 = 16 * b + 4 * g;
+            w_off[e][b] = (2 * rl + e) * cs + (rank0 < r ? rank0 : 0) * 2;
+        }
+    __syncthreads();
+
+#pragma unroll
+    for (int u = 0; u < PU; ++u) {
+        u32x4_t yop[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) tr[(4 * i + q) * MFMA_TRS + c16] = Y[u][i];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) yop[s] = tr[rl * MFMA_TRS + 4 * s + g];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            f32x4_t d[2];
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                d[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    const u32x2_t w = *reinterpret_cast<const u32x2_t *>(fb + (u * 128 + s * 32) * cs + w_off[e][b]);
+                    const bf16x8_t wop = as_bf16x8(u32x4_t{w[0], w[1], w[0], w[1]});
+                    d[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wop, zop[b], d[e], 0, 0, 0);
+                }
+            }
+            const u32x4_t yv = yop[s];                        // lane (row, g) owns columns 8g + 2v + e of the step
+            float out[8];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                out[2 * v]     = bf16_lo(yv[v]) + d[0][v];
+                out[2 * v + 1] = bf16_hi(yv[v]) + d[1][v];
+            }
+            tr[rl * MFMA_TRS + 4 * s + g] = Elem<bf16_tag>::pack(out);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const u32x4_t o = tr[(4 * i + q) * MFMA_TRS + c16];
+            if (row_ok[i]) st16_stream(yu[i] + u * 256, o);
+        }
+    }
 }
 
 // the same for one of several residual streams (in-place calls): blockIdx.y is the layer

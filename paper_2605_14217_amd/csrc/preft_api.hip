@@ -43,7 +43,7 @@ inline Knobs knobs_of(int mode)
 }
 inline bool knobs_valid(const Knobs &k)
 {
-    if (k.variant > 4) return false;
+    if (k.variant > 5) return false;
     if (k.waves != 0 && k.waves != 1 && k.waves != 2 && k.waves != 4 && k.waves != 8) return false;
     if (k.rowblocks > 2) return false;
     return true;
@@ -55,6 +55,14 @@ size_t workspace_bytes(int64_t T, int64_t S)
 {
     return (size_t)HEADER_INTS * 4 + (size_t)chunk_capacity(T, S) * sizeof(int4) +
            (size_t)short_capacity(T, S) * (sizeof(int4) + sizeof(int2));
+}
+
+// z area (LoRA calls whose sweeps run as two launches): after the schedule, 1 KB per 16-row block of
+// a chunk and rank block of 16
+size_t z_offset(int64_t T, int64_t S) { return (workspace_bytes(T, S) + 255) & ~(size_t)255; }
+size_t z_bytes(int64_t T, int64_t S, int rank)
+{
+    return (size_t)chunk_capacity(T, S) * (CHUNK_ROWS / 16) * (size_t)((rank + 15) / 16) * 1024;
 }
 
 ScheduleView view_of(void *workspace, int64_t T, int64_t S)
@@ -231,11 +239,39 @@ inline bool wide_widths_ok(const ApplyArgs &a, int cw)
     return (a.d_in % m) == 0 && (a.d_out % m) == 0;
 }
 
+// LoRA at rank 20..64, one output, with a z area in the workspace: the chunks' shrink sweep and expand
+// sweep as two launches, the expand in 2-D tiles of 64 rows x 256 columns (see mfma_expand_panel_kernel).
+// Measured on the 70B-shaped batch, same buffers, against the single launch (% of peak): rank 64 o
+// 62.5 -> 64.7, down 62.1 -> 65.9; rank 32 o 73.8 -> 74.2, down 71.9 -> 76.5.  Packed calls stay single
+// launches: the shrink sweep of two or three outputs is bound by LDS reads and MFMA issue once no expand
+// sweep of another workgroup runs beside it (rank 64 q+k+v: 33 % of peak for the shrink launch alone), and
+// on 28 672-wide dense rows the tiling gains little (rank 64 gate+up 61.8 -> 60.8, q+k+v 57.8 -> 52).
+// Panels of 128 columns: -1 to -3 points; of 512: one workgroup per compute unit, -15.
+template <int NB>
+bool launch_mfma_split(const ApplyArgs &a, int64_t S, const Knobs &k, hipStream_t stream)
+{
+    constexpr int PU = 2;
+    if (!a.zws || k.variant == 5 || k.waves || k.rowblocks || k.colsplit) return false;
+    if ((a.d_in % 128) != 0 || (a.d_out % (128 * PU)) != 0) return false;
+    void (*shrink)(ApplyArgs) = mfma_wide_kernel<NB, 1, 4, 1, false, 1, true>;
+    int threads = 256;
+    if constexpr (NB <= 2) {
+        if ((a.d_in % 256) == 0) { shrink = mfma_wide_kernel<NB, 1, 4, 2, false, 1, true>; threads = 512; }
+    }
+    hipLaunchKernelGGL(shrink, dim3(chunk_grid(a, S, 64)), dim3(threads), 0, stream, a);
+    const int64_t tiles = chunk_capacity(a.T, S) * (CHUNK_ROWS / 64) * (int64_t)(a.d_out / (128 * PU));
+    hipLaunchKernelGGL((mfma_expand_panel_kernel<NB, 4, PU>), dim3((unsigned)(((tiles + 7) / 8) * 8)), dim3(256), 0, stream, a);
+    return true;
+}
+
 template <int NB, bool DIREFT>
 bool launch_mfma_wide(const ApplyArgs &a, int64_t S, int mb, int waves, int cw, const Knobs &k, hipStream_t stream)
 {
     if (NB < 2 && k.variant != 4) return false;               // rank <= 16: only on request
     if (!wide_widths_ok(a, 1)) return false;
+    if constexpr (!DIREFT && NB >= 2 && NB <= 4) {
+        if (launch_mfma_split<NB>(a, S, k, stream)) return true;
+    }
     if (!wide_widths_ok(a, cw)) cw = 1;
     if (mb != 1 && NB <= 4) {                                  // 4 wavefronts x 32 rows
         if constexpr (NB <= 4) launch_wide_shape<NB, 2, 4, 1, DIREFT>(a, S, stream);
@@ -274,7 +310,7 @@ void launch_mfma_nb(const ApplyArgs &a, int64_t S, const Knobs &k, hipStream_t s
         // 16-row tile, and the tile's second read mostly still finds it in the memory-side cache)
         // measured ahead of the resident and row-split shapes at d = 4096 and d = 8192
         if constexpr (NB == 2) {
-            if (k.waves == 0 && k.variant == 0 && k.rowblocks == 0) {
+            if (k.waves == 0 && (k.variant == 0 || k.variant == 5) && k.rowblocks == 0) {
                 // resident == 3 (tests): each wavefront keeps 8 of its units in registers and streams the
                 // rest twice.  Measured on the skewed batch (d = 8192): traffic through the fabric falls
                 // by a sixth (half of the tile is read once), the time by 4 % (5985 against 6216 us): the
@@ -532,7 +568,14 @@ void bind_schedule(ApplyArgs &a, void *workspace, int32_t T, int32_t S, int32_t 
     const ScheduleView v = view_of(workspace, T, S);
     a.T = T; a.S = S; a.N = N; a.all_tokens = (mode & PREFT_ALL_TOKENS) ? 1 : 0;
     a.header = v.header; a.chunks = v.chunks; a.shorts = v.shorts; a.gtiles = v.gtiles;
-    a.gathered_only = 0; a.col_split = 1;
+    a.gathered_only = 0; a.col_split = 1; a.zws = nullptr;
+}
+
+// a workspace with room for z lets the LoRA calls of large batches run their sweeps as two launches
+void bind_z(ApplyArgs &a, void *workspace, size_t bytes, int32_t T, int32_t S, int32_t rank)
+{
+    if (T > 1024 && bytes >= z_offset(T, S) + z_bytes(T, S, rank))
+        a.zws = reinterpret_cast<char *>(workspace) + z_offset(T, S);
 }
 
 int check_matrix(const void *p, int64_t ld, int32_t width, int dtype)
@@ -568,6 +611,12 @@ size_t preft_workspace_bytes(int32_t T, int32_t S)
 {
     if (T < 0 || S < 0) return 0;
     return workspace_bytes(T, S);
+}
+
+size_t preft_workspace_bytes_z(int32_t T, int32_t S, int32_t rank)
+{
+    if (T < 0 || S < 0 || rank < 1 || rank > PREFT_MAX_RANK) return 0;
+    return z_offset(T, S) + z_bytes(T, S, rank);
 }
 
 int preft_schedule(void *workspace, size_t bytes, const int32_t *seg_start, const int32_t *seg_adapter,
@@ -608,6 +657,7 @@ int preft_lora_apply(void *y, int64_t ldy, const void *x, int64_t ldx, int32_t T
     bind_schedule(a, workspace, T, S, N, mode);
     a.y = y; a.x = x; a.ldy = ldy; a.ldx = ldx; a.d_in = d_in; a.d_out = d_out;
     a.A_pool = A_pool; a.Bt_pool = B_pool; a.bias_pool = nullptr; a.rank = rank; a.scale = scale;
+    bind_z(a, workspace, bytes, T, S, rank);
     return launch_apply<false>(a, S, dtype, knobs_of(mode), st);
 }
 
@@ -653,11 +703,11 @@ int preft_lora_apply_packed(int32_t n_proj, void *const *y, const int64_t *ldy, 
     const int ready = mode | PREFT_SCHEDULE_READY;
     const Knobs k = knobs_of(mode);
     const bool fused_mfma = n_proj > 1 && dtype == PREFT_BF16 && rank >= 4 && rank <= 16 &&
-                            (k.variant == 0 || k.variant == 3);
+                            (k.variant == 0 || k.variant == 3 || k.variant == 5);
     const bool fused_valu = n_proj > 1 && dtype == PREFT_BF16 && rank <= 3 && (k.variant == 0 || k.variant == 2) &&
                             (k.waves == 0 || k.waves == 4);
     bool fused_wide = n_proj > 1 && dtype == PREFT_BF16 && rank > 16 && rank <= 64 && (rank % 4) == 0 &&
-                      (k.variant == 0 || k.variant == 4) && k.waves == 0 && k.rowblocks == 0 && (d_in % 128) == 0 &&
+                      (k.variant == 0 || k.variant == 4 || k.variant == 5) && k.waves == 0 && k.rowblocks == 0 && (d_in % 128) == 0 &&
                       choose_col_split(T, k) == 1;
     for (int32_t i = 0; i < n_proj && fused_wide; ++i) fused_wide = (d_out[i] % 128) == 0;
     const bool fused = fused_mfma || fused_valu || fused_wide;

@@ -128,9 +128,10 @@ def direft_pools_to_device(pool: wl.DireftPool, perm=None, bias=True, null_bias=
 
 def run_lora_case(tab: wl.SegmentTable, pool: wl.LoraPool, x: torch.Tensor, y0: torch.Tensor, dtype: str,
                   scale: float, all_tokens: bool, pad_cols=0, rows=None, perm=None, reuse_schedule=False,
-                  pad_x=None, pad_y=None):
+                  pad_x=None, pad_y=None, z_room=False):
     """Tensors live on the GPU; returns (worst error, schedule counts).  pad_cols (or pad_x / pad_y for
-    x and y separately): guard columns that widen the row pitch and must come back untouched."""
+    x and y separately): guard columns that widen the row pitch and must come back untouched.
+    z_room: a workspace with room for z (the call may then run its sweeps as two launches)."""
     N, r = pool.N, pool.r
     T = tab.T
     mode = preft.PREFT_ALL_TOKENS if all_tokens else preft.PREFT_PREFILL_ONLY
@@ -138,7 +139,7 @@ def run_lora_case(tab: wl.SegmentTable, pool: wl.LoraPool, x: torch.Tensor, y0: 
     Ap, Bp, keep = lora_pools_to_device(pool, perm)
     ybuf, y = padded(y0, pad_cols if pad_y is None else pad_y, 7.0)
     xbuf, xv = padded(x, pad_cols if pad_x is None else pad_x, -3.0)
-    ws = preft.new_workspace(T, tab.S)
+    ws = preft.new_workspace(T, tab.S, z_rank=r if z_room else 0)
     if reuse_schedule:
         preft.preft_schedule(ws, ss, sa, sp, T, N, mode)
         preft.preft_lora_apply(y, xv, ss, sa, sp, Ap, Bp, r, scale, mode | preft.PREFT_SCHEDULE_READY, ws)

@@ -69,7 +69,8 @@ def test_kernel_selection_travels_in_the_call_not_in_the_library(lib):
         return lib.preft_schedule(None, 0, one, one, one, 1, 1, 1, mode, None)
     assert schedule(0) == -4 and schedule(1) == -4                      # EWORKSPACE: the mode passed
     assert schedule(preft.test_flags(variant=4, waves=8, rowblocks=2, colsplit=15, resident=3)) == -4
-    assert schedule(preft.test_flags(variant=5)) == -1                   # undefined variant
+    assert schedule(preft.test_flags(variant=5)) == -4
+    assert schedule(preft.test_flags(variant=6)) == -1                   # undefined variant
     assert schedule(preft.test_flags(waves=3)) == -1                     # not 0, 1, 2, 4, 8
     assert schedule(preft.test_flags(rowblocks=3)) == -1
     assert schedule(2) == -1 and schedule(0x200) == -1 and schedule(1 << 15) == -1   # undefined bits
@@ -89,6 +90,12 @@ def test_workspace_is_large_enough_for_any_table(lib):
         shorts = int(np.sum(lens[lens <= 4]))
         need = 64 + 16 * chunks + (8 + 16) * shorts
         assert preft.preft_workspace_bytes(tab.T, tab.S) >= need
+        # with room for z: 1 KB per 16-row block of a chunk, rank block of 16 and output, behind the schedule
+        for rank in (64, 20, 128):
+            z = preft.preft_workspace_bytes_z(tab.T, tab.S, rank)
+            assert z >= preft.preft_workspace_bytes(tab.T, tab.S) + chunks * 8 * ((rank + 15) // 16) * 1024
+    assert preft.preft_workspace_bytes_z(-1, 3, 8) == 0 and preft.preft_workspace_bytes_z(10, 3, 0) == 0
+    assert preft.preft_workspace_bytes_z(10, 3, 129) == 0
 
 
 def test_bad_arguments_are_rejected_before_any_launch(lib):

@@ -35,6 +35,9 @@ LORA = [
     ("llama70b_lora", "down", 64, False, "dense"), ("llama70b_lora", "o", 64, False, "dense"),
     ("llama70b_lora", "gate", 64, True, "dense"), ("llama70b_lora", "o", 32, False, "dense"),
     ("skewed70b", "res", 32, False, "dense"),
+    # a workspace with room for z: the call runs its sweeps as two launches, as bench.py times o, down and res
+    ("llama70b_lora", "down", 64, False, "dense", "z"), ("llama70b_lora", "o", 64, True, "dense", "z"),
+    ("skewed70b", "res", 32, False, "dense", "z"),
 ]
 
 
@@ -58,7 +61,8 @@ def test_fullsize_lora(case):
     # the 8B LoRA batch is compared whole (every row); the larger batches on a deterministic row sample
     rows = None if config == "llama8b_lora" else wl.sample_rows(tab, 2, max_rows=1200)
     worst, counts = run_lora_case(tab, pool, x, y0, "bf16", cfg["lora_scale"], all_tokens, rows=rows,
-                                  pad_x=0 if dense else _pow2_pad(d_in), pad_y=0 if dense else _pow2_pad(d_out))
+                                  pad_x=0 if dense else _pow2_pad(d_in), pad_y=0 if dense else _pow2_pad(d_out),
+                                  z_room=len(case) > 5)
     print(f"  T={tab.T} S={tab.S} rows checked={tab.T if rows is None else len(rows)} worst {worst:.2e} counts {counts}")
 
 

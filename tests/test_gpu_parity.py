@@ -783,6 +783,75 @@ def test_packed_projections_in_the_row_split_kernel(r, d_in, d_outs, fused_buffe
         print(f"  packed r={r} {d_in}->{d_outs} fused_buffer={fused_buffer} all_tokens={all_tokens} worst {worst:.2e}")
 
 
+TWO_LAUNCH_CASES = [
+    # (rank, d_in, d_outs): widths the two-launch form takes (d_in % 128 == 0, every d_out % 256 == 0)
+    (64, 512, (512,)), (64, 1024, (1024, 256, 256)), (64, 256, (1792, 1792)), (32, 512, (512, 256, 256)),
+    (32, 384, (768,)), (20, 128, (256, 512)), (48, 640, (256,)), (36, 256, (512, 256, 768)),
+]
+
+
+@pytest.mark.parametrize("rank,d_in,d_outs", TWO_LAUNCH_CASES, ids=[f"r{c[0]}-{c[1]}-{'x'.join(map(str, c[2]))}" for c in TWO_LAUNCH_CASES])
+def test_two_launch_lora_equals_the_single_launch_and_the_oracle(rank, d_in, d_outs):
+    """A workspace with room for z (preft_workspace_bytes_z) makes a one-output LoRA call on more than
+    1024 rows run its shrink and its expand as two launches, the expand in 2-D tiles; packed calls keep
+    one launch on either workspace.  The result must equal the small workspace's bit for bit (same
+    arithmetic, same order), both must match the oracle, in both modes; the guard columns of the
+    buffer and every inactive row stay untouched."""
+    from oracle import preft_oracle as ora
+    from parity_util import bits, compare, dev_tables, lora_pools_to_device
+    N, dtype = 5, "bf16"
+    tab = _mixed_table(rank * 7 + d_in, N, n_prompts=9, max_len=420, n_decode=40)
+    T = tab.T
+    assert T > 1024
+    ss, sa, sp = dev_tables(tab)
+    ws_small = preft.new_workspace(T, tab.S)
+    ws_big = preft.new_workspace(T, tab.S, z_rank=rank)
+    assert ws_big.numel() == preft.preft_workspace_bytes_z(T, tab.S, rank) > ws_small.numel()
+    x = wl.activations(T, d_in, dtype, device="cuda", seed=41)
+    pools = [wl.lora_pool(N, rank, d_in, n, dtype, device="cuda", seed=50 + i) for i, n in enumerate(d_outs)]
+    tables = [lora_pools_to_device(pl) for pl in pools]
+    width = sum(d_outs) + 8
+    buf0 = wl.activations(T, width, dtype, device="cuda", seed=42)
+    offs = np.concatenate([[0], np.cumsum(d_outs)])
+    for all_tokens in (False, True):
+        mode = preft.PREFT_ALL_TOKENS if all_tokens else preft.PREFT_PREFILL_ONLY
+        pos = ora.ALL_POSITIONS if all_tokens else ora.PROMPT_ONLY
+        owner = ora.positions(T, tab.seg_start, tab.seg_adapter, tab.seg_prefill_len, N, pos)
+        got = {}
+        for name, ws in (("one launch", ws_small), ("two launches", ws_big)):
+            buf = buf0.clone()
+            ys = [buf[:, offs[i]:offs[i + 1]] for i in range(len(d_outs))]
+            _set()
+            if len(d_outs) == 1:
+                preft.preft_lora_apply(ys[0], x, ss, sa, sp, tables[0][0], tables[0][1], rank, 2.0, mode, ws)
+            else:
+                preft.preft_lora_apply_packed(ys, x, ss, sa, sp, [t[0] for t in tables], [t[1] for t in tables], rank, 2.0, mode, ws)
+            torch.cuda.synchronize()
+            preft.preft_schedule_counts(ws)
+            got[name] = buf
+        assert torch.equal(bits(got["one launch"]), bits(got["two launches"]))
+        buf = got["two launches"]
+        assert torch.equal(bits(buf[:, sum(d_outs):].contiguous()), bits(buf0[:, sum(d_outs):].contiguous()))
+        worst = 0.0
+        for i, pl in enumerate(pools):
+            y0 = buf0[:, offs[i]:offs[i + 1]].contiguous()
+            want = ora.lora(y0.cpu(), x.cpu(), tab.seg_start, tab.seg_adapter, tab.seg_prefill_len,
+                            [a.cpu() for a in pl.A], [b.cpu() for b in pl.B], rank, 2.0, pos)
+            worst = max(worst, compare(buf[:, offs[i]:offs[i + 1]], y0, want, owner, dtype))
+        print(f"  two launches r={rank} {d_in}->{d_outs} T={T} all_tokens={all_tokens} worst {worst:.2e}")
+    # the forced single-launch variant on the large workspace is the single-launch result too
+    _set(5)
+    buf = buf0.clone()
+    ys = [buf[:, offs[i]:offs[i + 1]] for i in range(len(d_outs))]
+    if len(d_outs) == 1:
+        preft.preft_lora_apply(ys[0], x, ss, sa, sp, tables[0][0], tables[0][1], rank, 2.0, mode, ws_big)
+    else:
+        preft.preft_lora_apply_packed(ys, x, ss, sa, sp, [t[0] for t in tables], [t[1] for t in tables], rank, 2.0, mode, ws_big)
+    torch.cuda.synchronize()
+    assert torch.equal(bits(buf), bits(got["one launch"]))
+    _set()
+
+
 @pytest.mark.parametrize("rank,d_in,d_outs", [(32, 256, (256, 128, 128)), (64, 128, (384, 128)), (64, 384, (128, 128, 256)),
                                               (7, 264, (256, 136, 128)), (13, 128, (392, 128))])
 def test_packed_row_split_kernel_gives_the_exactly_rounded_result(rank, d_in, d_outs):
