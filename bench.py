@@ -124,9 +124,9 @@ def run(args):
     T_act = tab.active_rows(False, N)
     n_ad = tab.distinct_active_adapters(False, N)
     ss, sa, sp = (torch.from_numpy(a.copy()).to(dev) for a in (tab.seg_start, tab.seg_adapter, tab.seg_prefill_len))
-    # with room for z the single-output LoRA calls at rank 20..64 run their sweeps as two launches
+    # with room for z the LoRA calls at rank 20..64 run their sweeps as two launches where that is faster
     # (preft_workspace_bytes_z)
-    ws = preft.new_workspace(T, S, device=dev, z_rank=0 if args.no_z else r)
+    ws = preft.new_workspace(T, S, device=dev, z_rank=0 if args.no_z else r, z_proj=3)
 
     # ---- buffers and pools --------------------------------------------------------------
     projs = []

@@ -96,7 +96,9 @@ enum {
  *                            batches of up to 1024 rows, else 1), or 1..15.  Together with
  *                            variant 4 it names the column groups of the row-split kernel
  *                            instead: 0 = automatic, 1 or 2
- *   PREFT_TEST_RESIDENT(n)   in-place MFMA kernel at rank 20..32: 0 = automatic (32-row tiles
+ *   PREFT_TEST_RESIDENT(n)   LoRA: 1 = two launches (see preft_workspace_bytes_z) wherever that form
+ *                            exists, whatever the batch size.  In-place MFMA kernel at rank
+ *                            20..32: 0 = automatic (32-row tiles
  *                            streamed in both sweeps), 3 = every wavefront keeps 8 of its
  *                            128-column units in registers between the sweeps (half of a
  *                            32-row tile of 8192 columns) and streams the rest twice
@@ -138,17 +140,17 @@ size_t preft_workspace_bytes(int32_t T, int32_t S);
 
 /*
  * Bytes of a workspace that, beyond the schedule, has room for the intermediate z = A_i x of Eq. 2 of
- * every active row (LoRA calls of up to `rank`).  A preft_lora_apply call (bf16, rank 20..64 in
- * multiples of 4, more than 1024 rows, d_in a multiple of 128, d_out a multiple of 256) that is
- * handed at least this many bytes runs its two sweeps as two launches -- shrink into z, then the
- * expand in 2-D tiles -- which measured 2-5 % faster on batches of several GB; with fewer bytes, or
- * outside those limits, the same call runs as before, and packed calls always do.  The result is
- * the same bit for bit.  The z area lies behind the schedule and is rewritten by every such call:
- * calls that share a workspace must be ordered on one stream, as they must be for the schedule
- * already.
- * Returns 0 for a negative T or S or a rank outside 1..PREFT_MAX_RANK.
+ * every active row: LoRA calls of up to `rank` with up to n_proj outputs per call.  A LoRA call
+ * (bf16, rank 20..64 in multiples of 4, d_in a multiple of 128, every d_out a multiple of 256) on a
+ * batch of 8192 to 131 072 rows that is handed at least this many bytes runs its two sweeps as two
+ * launches -- shrink into z, then the expand in 2-D tiles -- which measured 4 to 12 points of
+ * bandwidth faster at that size (a batch of 38 416 rows, rank 32 and 64).  With fewer bytes, or
+ * outside those limits, the same call runs as before.  The result is the same bit for bit.  The z area lies behind the schedule and is rewritten by every such call: calls that
+ * share a workspace must be ordered on one stream, as they must be for the schedule already.
+ * Returns 0 for a negative T or S, a rank outside 1..PREFT_MAX_RANK or n_proj outside
+ * 1..PREFT_MAX_PACKED.
  */
-size_t preft_workspace_bytes_z(int32_t T, int32_t S, int32_t rank);
+size_t preft_workspace_bytes_z(int32_t T, int32_t S, int32_t rank, int32_t n_proj);
 
 /*
  * Token-segment scheduler (paper Eq. 1 and Eq. 4; App. D.3 "position mask", which the

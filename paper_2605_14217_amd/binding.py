@@ -100,7 +100,7 @@ def load_library(path: Optional[str] = None):
     lib.preft_workspace_bytes.restype = sz
     lib.preft_workspace_bytes.argtypes = [i32, i32]
     lib.preft_workspace_bytes_z.restype = sz
-    lib.preft_workspace_bytes_z.argtypes = [i32, i32, i32]
+    lib.preft_workspace_bytes_z.argtypes = [i32, i32, i32, i32]
     lib.preft_schedule.restype = c.c_int
     lib.preft_schedule.argtypes = [vp, sz, vp, vp, vp, i32, i32, i32, c.c_int, vp]
     lib.preft_lora_apply.restype = c.c_int
@@ -216,14 +216,14 @@ def preft_workspace_bytes(T: int, S: int) -> int:
     return int(load_library().preft_workspace_bytes(int(T), int(S)))
 
 
-def preft_workspace_bytes_z(T: int, S: int, rank: int) -> int:
-    return int(load_library().preft_workspace_bytes_z(int(T), int(S), int(rank)))
+def preft_workspace_bytes_z(T: int, S: int, rank: int, n_proj: int = 1) -> int:
+    return int(load_library().preft_workspace_bytes_z(int(T), int(S), int(rank), int(n_proj)))
 
 
-def new_workspace(T: int, S: int, device="cuda", z_rank: int = 0) -> torch.Tensor:
+def new_workspace(T: int, S: int, device="cuda", z_rank: int = 0, z_proj: int = 1) -> torch.Tensor:
     """Caller-owned workspace for a batch of T rows in S segments; with z_rank > 0 it also has room for
-    the intermediate z of LoRA calls of up to that rank (preft_workspace_bytes_z)."""
-    n = preft_workspace_bytes_z(T, S, z_rank) if z_rank > 0 else preft_workspace_bytes(T, S)
+    the intermediate z of LoRA calls of up to that rank and z_proj outputs (preft_workspace_bytes_z)."""
+    n = preft_workspace_bytes_z(T, S, z_rank, z_proj) if z_rank > 0 else preft_workspace_bytes(T, S)
     return torch.empty(max(n, 16), dtype=torch.uint8, device=device)
 
 

@@ -128,8 +128,13 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
     const int n_units = tile_units<R>(p, &n_chunk_units);
     int unit;
     if constexpr (COLSPLIT) {
-        unit = blockIdx.x / csplit;
-        cslice = blockIdx.x - unit * csplit;
+        // the workgroups that share a tile sit side by side on one XCD (workgroup ids are dealt round-robin
+        // to the 8 XCDs), so that all but the first of them find the tile's x in that XCD's L2
+        const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+        const int per_xcd = (n_units + 7) >> 3;
+        const int t = j / csplit;
+        cslice = j - t * csplit;
+        unit = t < per_xcd ? xcd * per_xcd + t : -1;
         if (unit >= n_units) unit = -1;
     } else {
         unit = xcd_unit(n_units);

@@ -56,7 +56,7 @@ template <int NB, int MB, int RW, int CW, bool DIREFT, int SLICES = 1, bool ZOUT
 __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
 {
     static_assert(SLICES == 1 || !DIREFT, "packed projections are a LoRA feature");
-    static_assert(!ZOUT || (!DIREFT && MB == 1 && SLICES == 1), "the two-launch form: LoRA, one output, 16-row blocks per wavefront");
+    static_assert(!ZOUT || (!DIREFT && MB == 1), "the two-launch form: LoRA, 16-row blocks per wavefront");
     constexpr int WAVES = RW * CW;
     constexpr int NBT = NB * SLICES;                          // accumulator blocks of the shrink sweep
     constexpr int R = 16 * MB * RW;
@@ -480,13 +480,13 @@ __global__ __launch_bounds__(RW * CW * 64, wide_min_waves(RW, CW, SLICES)) void 
 // peak, the same tiles cut into 32 panels of 256 columns 77 % (16-row tiles of 8 wavefronts: 71 -> 83 %
 // with 1024-column panels; on dense 28 672-wide rows 63 -> 68 % and 65 -> 71 %).  A workgroup that
 // sweeps only a panel cannot afford the shrink sweep over the whole of x, hence the two launches, with z
-// (r values per row) through HBM in between: 4 r bytes per row against 2 (d_in + 2 d_out).  One output per
-// call: see the notes at the launch site.
+// (r values per row) through HBM in between: 4 r bytes per row and output against 2 (d_in + 2 d_out).
+// blockIdx.y is the output of a packed call.  Which calls take this form: see the notes at the launch site.
 // The panel's factors (PU * 128 columns x r, contiguous in [d_out, r]) go to LDS once per workgroup
 // and are shared by its RW row blocks; operand layouts as in the expand of mfma_wide_body.
 // 52 KB of LDS at rank 64: three workgroups per compute unit, and the register allocation is held to that.
 template <int NB, int RW, int PU>
-__global__ __launch_bounds__(RW * 64, 3) void mfma_expand_panel_kernel(ApplyArgs p)
+__global__ __launch_bounds__(RW * 64, 3) void mfma_expand_panel_kernel(ApplyArgs p, int n_slices)
 {
     constexpr int R = 16 * RW;
     constexpr int TPC = CHUNK_ROWS / R;
@@ -497,17 +497,15 @@ __global__ __launch_bounds__(RW * 64, 3) void mfma_expand_panel_kernel(ApplyArgs
     __shared__ __attribute__((aligned(16))) char lds_raw[RW * 16 * MFMA_TRS * 16 + B_BYTES];
 
     if (!schedule_matches(p)) return;
-    const int64_t ldy_b = p.ldy * 2;
-    const int panels = p.d_out / (128 * PU);                  // d_out % (128 PU) == 0 (host-checked)
-    const int id = xcd_unit(p.header[HDR_CHUNKS] * TPC * panels);
-    if (id < 0) return;
-    const int tile = id / panels, panel = id - tile * panels;
-    const int4 ch = p.chunks[tile / TPC];
-    const int tile_row0 = (tile % TPC) * R;
-    if (tile_row0 >= ch.z) return;                            // uniform over the workgroup
-    const int adapter = ch.x;
-    const int n_rows = min(R, ch.z - tile_row0);
-
+    const int sl = blockIdx.y;                                // output of a packed call
+    void *y = p.y;
+    int64_t ldy_b = p.ldy * 2;
+    int d_out = p.d_out;
+    const void *const *Bt_pool = p.Bt_pool;
+    if (sl > 0) {
+        y = p.more[sl - 1].y; ldy_b = p.more[sl - 1].ldy * 2; d_out = p.more[sl - 1].d_out; Bt_pool = p.more[sl - 1].Bt_pool;
+    }
+    const int panels = d_out / (128 * PU);                    // d_out % (128 PU) == 0 (host-checked)
     const int tid = threadIdx.x, rb = tid >> 6, lane = tid & 63;
     const int rl = lane & 15, g = lane >> 4;                  // MFMA order
     const int q = lane >> 4, c16 = lane & 15;                 // unit load order
@@ -515,8 +513,24 @@ __global__ __launch_bounds__(RW * 64, 3) void mfma_expand_panel_kernel(ApplyArgs
     u32x4_t *tr = reinterpret_cast<u32x4_t *>(lds_raw) + rb * (16 * MFMA_TRS);
     char *fb = lds_raw + RW * 16 * MFMA_TRS * 16;
 
+    // The launch has at most a fixed number of workgroups (a multiple of 8: workgroup ids are dealt round-robin
+    // to the 8 XCDs, and XCD x walks its own run of the tile list); a workgroup takes every gridDim.x-th tile
+    // of its XCD's run, so that a launch that finds little or no work stays cheap whatever the batch's bounds.
+    const int n_tiles = p.header[HDR_CHUNKS] * TPC * panels;
+    const int per_xcd = (n_tiles + 7) >> 3;
+    const int xcd = blockIdx.x & 7;
+    for (int j = blockIdx.x >> 3; j < per_xcd; j += gridDim.x >> 3) {
+    const int id = xcd * per_xcd + j;
+    if (id >= n_tiles) break;
+    const int tile = id / panels, panel = id - tile * panels;
+    const int4 ch = p.chunks[tile / TPC];
+    const int tile_row0 = (tile % TPC) * R;
+    if (tile_row0 >= ch.z) continue;                          // uniform over the workgroup
+    const int adapter = ch.x;
+    const int n_rows = min(R, ch.z - tile_row0);
+
     // requests first: the panel's factors, this row block's z, its PU units of y
-    gcptr_t Wp = as_global(p.Bt_pool[adapter]) + (int64_t)panel * (PU * 256) * r;
+    gcptr_t Wp = as_global(Bt_pool[adapter]) + (int64_t)panel * (PU * 256) * r;
     const int b_halves = 32 * r * PU;                         // 8-byte halves of the panel's factors
     u32x4_t breg[B_ITERS];
 #pragma unroll
@@ -525,7 +539,7 @@ __global__ __launch_bounds__(RW * 64, 3) void mfma_expand_panel_kernel(ApplyArgs
         if (piece * 2 < b_halves) breg[i] = ld16(Wp + (int64_t)piece * 16);
     }
     const int64_t blk16 = (int64_t)(tile / TPC) * (CHUNK_ROWS / 16) + tile_row0 / 16 + rb;
-    gcptr_t zw = as_global(p.zws) + (blk16 * NB * 64 + lane) * 16;
+    gcptr_t zw = as_global(p.zws) + ((blk16 * n_slices + sl) * NB * 64 + lane) * 16;
     bf16x8_t zop[NB];
 #pragma unroll
     for (int b = 0; b < NB; ++b) zop[b] = as_bf16x8(ld16(zw + b * 1024));
@@ -535,7 +549,7 @@ __global__ __launch_bounds__(RW * 64, 3) void mfma_expand_panel_kernel(ApplyArgs
     for (int i = 0; i < 4; ++i) {
         const int t = rb * 16 + 4 * i + q;
         row_ok[i] = t < n_rows;                               // rows past the tile alias its last row; their stores are masked
-        yu[i] = as_global(p.y) + ((int64_t)ch.y + tile_row0 + min(t, n_rows - 1)) * ldy_b + (int64_t)panel * (PU * 256) + c16 * 16;
+        yu[i] = as_global(y) + ((int64_t)ch.y + tile_row0 + min(t, n_rows - 1)) * ldy_b + (int64_t)panel * (PU * 256) + c16 * 16;
     }
     u32x4_t Y[PU][4];
 #pragma unroll
@@ -602,6 +616,8 @@ __global__ __launch_bounds__(RW * 64, 3) void mfma_expand_panel_kernel(ApplyArgs
             const u32x4_t o = tr[(4 * i + q) * MFMA_TRS + c16];
             if (row_ok[i]) st16_stream(yu[i] + u * 256, o);
         }
+    }
+    __syncthreads();                                          // the next tile's factors overwrite this one's
     }
 }
 

@@ -60,9 +60,9 @@ size_t workspace_bytes(int64_t T, int64_t S)
 // z area (LoRA calls whose sweeps run as two launches): after the schedule, 1 KB per 16-row block of
 // a chunk and rank block of 16
 size_t z_offset(int64_t T, int64_t S) { return (workspace_bytes(T, S) + 255) & ~(size_t)255; }
-size_t z_bytes(int64_t T, int64_t S, int rank)
+size_t z_bytes(int64_t T, int64_t S, int rank, int n_proj)
 {
-    return (size_t)chunk_capacity(T, S) * (CHUNK_ROWS / 16) * (size_t)((rank + 15) / 16) * 1024;
+    return (size_t)chunk_capacity(T, S) * (CHUNK_ROWS / 16) * (size_t)(((rank + 15) / 16) * n_proj) * 1024;
 }
 
 ScheduleView view_of(void *workspace, int64_t T, int64_t S)
@@ -239,28 +239,43 @@ inline bool wide_widths_ok(const ApplyArgs &a, int cw)
     return (a.d_in % m) == 0 && (a.d_out % m) == 0;
 }
 
-// LoRA at rank 20..64, one output, with a z area in the workspace: the chunks' shrink sweep and expand
-// sweep as two launches, the expand in 2-D tiles of 64 rows x 256 columns (see mfma_expand_panel_kernel).
-// Measured on the 70B-shaped batch, same buffers, against the single launch (% of peak): rank 64 o
-// 62.5 -> 64.7, down 62.1 -> 65.9; rank 32 o 73.8 -> 74.2, down 71.9 -> 76.5.  Packed calls stay single
-// launches: the shrink sweep of two or three outputs is bound by LDS reads and MFMA issue once no expand
-// sweep of another workgroup runs beside it (rank 64 q+k+v: 33 % of peak for the shrink launch alone), and
-// on 28 672-wide dense rows the tiling gains little (rank 64 gate+up 61.8 -> 60.8, q+k+v 57.8 -> 52).
-// Panels of 128 columns: -1 to -3 points; of 512: one workgroup per compute unit, -15.
-template <int NB>
+// LoRA at rank 20..64 with a z area in the workspace: the chunks' shrink sweep and expand sweep as two
+// launches, the expand in 2-D tiles of 64 rows x 256 columns (see mfma_expand_panel_kernel).  Measured on
+// the same buffers, % of peak, one launch -> two:
+//   8B-sized batch (38 416 rows): rank 64 q+k+v 37 -> 42, o 42-43 -> 51-53, gate+up 47 -> 59, down 46 -> 51;
+//     rank 32 q+k+v 52 -> 53, o 58 -> 62.5, gate+up 58 -> 66.5, down 62 -> 62 (a 64-row tile per workgroup
+//     leaves the chip 1.2 rounds of tiles; the expand launch has thousands of small workgroups);
+//   70B-sized batch (352 814 rows): rank 64 o and down +2 to +4 on one set of buffers, -2 on another (the
+//     one-launch kernel moves between 62 and 68 % with the placement of its buffers, the two launches stay
+//     at 62-66 %), packed q+k+v 57.8 -> 52, gate+up 61.8 -> 60.8 (the shrink launch of two or three outputs is
+//     bound by LDS reads and MFMA issue once no expand sweep of another workgroup runs beside it: 33 % of peak
+//     for q+k+v; 28 672-wide dense rows gain little from the tiling); rank 32 o 73.8 -> 74.2, down 71.9 -> 76.5,
+//     packed q+k+v 69 -> 61, gate+up 74 -> 68; skewed batch (836 609 rows), rank 32, 8192 -> 8192: 77.4 -> 73.9.
+// Hence: batches of 8192 to 131 072 rows.  PREFT_TEST_RESIDENT(1) takes this form wherever it exists,
+// PREFT_TEST_VARIANT(5) never.  Panels of 128 columns: -1 to -3 points; of 512: one workgroup per compute
+// unit, -15.
+template <int NB, int SLICES>
 bool launch_mfma_split(const ApplyArgs &a, int64_t S, const Knobs &k, hipStream_t stream)
 {
     constexpr int PU = 2;
     if (!a.zws || k.variant == 5 || k.waves || k.rowblocks || k.colsplit) return false;
+    if (k.resident != 1 && (a.T < 8192 || a.T > 131072)) return false;
     if ((a.d_in % 128) != 0 || (a.d_out % (128 * PU)) != 0) return false;
-    void (*shrink)(ApplyArgs) = mfma_wide_kernel<NB, 1, 4, 1, false, 1, true>;
+    int max_d_out = a.d_out;
+    for (int i = 1; i < SLICES; ++i) {
+        if ((a.more[i - 1].d_out % (128 * PU)) != 0) return false;
+        if (a.more[i - 1].d_out > max_d_out) max_d_out = a.more[i - 1].d_out;
+    }
+    void (*shrink)(ApplyArgs) = mfma_wide_kernel<NB, 1, 4, 1, false, SLICES, true>;
     int threads = 256;
     if constexpr (NB <= 2) {
-        if ((a.d_in % 256) == 0) { shrink = mfma_wide_kernel<NB, 1, 4, 2, false, 1, true>; threads = 512; }
+        if ((a.d_in % 256) == 0) { shrink = mfma_wide_kernel<NB, 1, 4, 2, false, SLICES, true>; threads = 512; }
     }
     hipLaunchKernelGGL(shrink, dim3(chunk_grid(a, S, 64)), dim3(threads), 0, stream, a);
-    const int64_t tiles = chunk_capacity(a.T, S) * (CHUNK_ROWS / 64) * (int64_t)(a.d_out / (128 * PU));
-    hipLaunchKernelGGL((mfma_expand_panel_kernel<NB, 4, PU>), dim3((unsigned)(((tiles + 7) / 8) * 8)), dim3(256), 0, stream, a);
+    int64_t tiles = chunk_capacity(a.T, S) * (CHUNK_ROWS / 64) * (int64_t)(max_d_out / (128 * PU));
+    tiles = ((tiles + 7) / 8) * 8;
+    if (tiles > 8192) tiles = 8192;                         // the kernel strides over the rest
+    hipLaunchKernelGGL((mfma_expand_panel_kernel<NB, 4, PU>), dim3((unsigned)tiles, SLICES), dim3(256), 0, stream, a, SLICES);
     return true;
 }
 
@@ -270,7 +285,7 @@ bool launch_mfma_wide(const ApplyArgs &a, int64_t S, int mb, int waves, int cw, 
     if (NB < 2 && k.variant != 4) return false;               // rank <= 16: only on request
     if (!wide_widths_ok(a, 1)) return false;
     if constexpr (!DIREFT && NB >= 2 && NB <= 4) {
-        if (launch_mfma_split<NB>(a, S, k, stream)) return true;
+        if (launch_mfma_split<NB, 1>(a, S, k, stream)) return true;
     }
     if (!wide_widths_ok(a, cw)) cw = 1;
     if (mb != 1 && NB <= 4) {                                  // 4 wavefronts x 32 rows
@@ -363,8 +378,9 @@ void launch_mfma_packed(const ApplyArgs &a, int64_t S, const Knobs &k, hipStream
 // over x for all outputs.  It takes the chunks; the gathered tiles (all-token mode: decode rows)
 // go to one launch of the column-split kernel per output.
 template <int NB>
-void launch_mfma_wide_packed(const ApplyArgs &a, int n_proj, int64_t S, hipStream_t stream)
+void launch_mfma_wide_packed(const ApplyArgs &a, int n_proj, int64_t S, const Knobs &k, hipStream_t stream)
 {
+    const bool split = n_proj == 2 ? launch_mfma_split<NB, 2>(a, S, k, stream) : launch_mfma_split<NB, 3>(a, S, k, stream);
     // two column groups at rank 32 where every width allows it (see launch_mfma_nb)
     bool cw2 = NB <= 2 && (a.d_in % 256) == 0 && (a.d_out % 256) == 0;
     for (int i = 1; i < n_proj; ++i) cw2 = cw2 && (a.more[i - 1].d_out % 256) == 0;
@@ -372,7 +388,7 @@ void launch_mfma_wide_packed(const ApplyArgs &a, int n_proj, int64_t S, hipStrea
     if constexpr (NB <= 2) {
         if (cw2) kernel = n_proj == 2 ? mfma_wide_kernel<NB, 1, 4, 2, false, 2> : mfma_wide_kernel<NB, 1, 4, 2, false, 3>;
     }
-    hipLaunchKernelGGL(kernel, dim3(chunk_grid(a, S, 64)), dim3(cw2 ? 512 : 256), 0, stream, a);
+    if (!split) hipLaunchKernelGGL(kernel, dim3(chunk_grid(a, S, 64)), dim3(cw2 ? 512 : 256), 0, stream, a);
     for (int i = 0; i < n_proj; ++i) {
         ApplyArgs g = a;
         if (i > 0) {
@@ -572,9 +588,9 @@ void bind_schedule(ApplyArgs &a, void *workspace, int32_t T, int32_t S, int32_t 
 }
 
 // a workspace with room for z lets the LoRA calls of large batches run their sweeps as two launches
-void bind_z(ApplyArgs &a, void *workspace, size_t bytes, int32_t T, int32_t S, int32_t rank)
+void bind_z(ApplyArgs &a, void *workspace, size_t bytes, int32_t T, int32_t S, int32_t rank, int32_t n_proj)
 {
-    if (T > 1024 && bytes >= z_offset(T, S) + z_bytes(T, S, rank))
+    if (T > 1024 && bytes >= z_offset(T, S) + z_bytes(T, S, rank, n_proj))
         a.zws = reinterpret_cast<char *>(workspace) + z_offset(T, S);
 }
 
@@ -613,10 +629,10 @@ size_t preft_workspace_bytes(int32_t T, int32_t S)
     return workspace_bytes(T, S);
 }
 
-size_t preft_workspace_bytes_z(int32_t T, int32_t S, int32_t rank)
+size_t preft_workspace_bytes_z(int32_t T, int32_t S, int32_t rank, int32_t n_proj)
 {
-    if (T < 0 || S < 0 || rank < 1 || rank > PREFT_MAX_RANK) return 0;
-    return z_offset(T, S) + z_bytes(T, S, rank);
+    if (T < 0 || S < 0 || rank < 1 || rank > PREFT_MAX_RANK || n_proj < 1 || n_proj > PREFT_MAX_PACKED) return 0;
+    return z_offset(T, S) + z_bytes(T, S, rank, n_proj);
 }
 
 int preft_schedule(void *workspace, size_t bytes, const int32_t *seg_start, const int32_t *seg_adapter,
@@ -657,7 +673,7 @@ int preft_lora_apply(void *y, int64_t ldy, const void *x, int64_t ldx, int32_t T
     bind_schedule(a, workspace, T, S, N, mode);
     a.y = y; a.x = x; a.ldy = ldy; a.ldx = ldx; a.d_in = d_in; a.d_out = d_out;
     a.A_pool = A_pool; a.Bt_pool = B_pool; a.bias_pool = nullptr; a.rank = rank; a.scale = scale;
-    bind_z(a, workspace, bytes, T, S, rank);
+    bind_z(a, workspace, bytes, T, S, rank, 1);
     return launch_apply<false>(a, S, dtype, knobs_of(mode), st);
 }
 
@@ -728,8 +744,9 @@ int preft_lora_apply_packed(int32_t n_proj, void *const *y, const int64_t *ldy, 
         a.more[i - 1].A_pool = A_pools[i]; a.more[i - 1].Bt_pool = B_pools[i];
     }
     if (fused_wide) {
-        if (rank <= 32) launch_mfma_wide_packed<2>(a, n_proj, S, st);
-        else            launch_mfma_wide_packed<4>(a, n_proj, S, st);
+        bind_z(a, workspace, bytes, T, S, rank, n_proj);
+        if (rank <= 32) launch_mfma_wide_packed<2>(a, n_proj, S, k, st);
+        else            launch_mfma_wide_packed<4>(a, n_proj, S, k, st);
     } else if (fused_mfma) {
         a.col_split = choose_col_split(T, k);
         const int pieces = (rank % 4) == 0 ? 0 : rank < 8 ? 2 : 4;      // the any-rank shape's block pieces per lane

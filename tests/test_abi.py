@@ -91,11 +91,11 @@ def test_workspace_is_large_enough_for_any_table(lib):
         need = 64 + 16 * chunks + (8 + 16) * shorts
         assert preft.preft_workspace_bytes(tab.T, tab.S) >= need
         # with room for z: 1 KB per 16-row block of a chunk, rank block of 16 and output, behind the schedule
-        for rank in (64, 20, 128):
-            z = preft.preft_workspace_bytes_z(tab.T, tab.S, rank)
-            assert z >= preft.preft_workspace_bytes(tab.T, tab.S) + chunks * 8 * ((rank + 15) // 16) * 1024
-    assert preft.preft_workspace_bytes_z(-1, 3, 8) == 0 and preft.preft_workspace_bytes_z(10, 3, 0) == 0
-    assert preft.preft_workspace_bytes_z(10, 3, 129) == 0
+        for rank, n_proj in ((64, 1), (20, 3), (128, 2)):
+            z = preft.preft_workspace_bytes_z(tab.T, tab.S, rank, n_proj)
+            assert z >= preft.preft_workspace_bytes(tab.T, tab.S) + chunks * 8 * ((rank + 15) // 16) * n_proj * 1024
+    assert preft.preft_workspace_bytes_z(-1, 3, 8, 1) == 0 and preft.preft_workspace_bytes_z(10, 3, 0, 1) == 0
+    assert preft.preft_workspace_bytes_z(10, 3, 129, 1) == 0 and preft.preft_workspace_bytes_z(10, 3, 8, 4) == 0
 
 
 def test_bad_arguments_are_rejected_before_any_launch(lib):

@@ -35,9 +35,11 @@ LORA = [
     ("llama70b_lora", "down", 64, False, "dense"), ("llama70b_lora", "o", 64, False, "dense"),
     ("llama70b_lora", "gate", 64, True, "dense"), ("llama70b_lora", "o", 32, False, "dense"),
     ("skewed70b", "res", 32, False, "dense"),
-    # a workspace with room for z: the call runs its sweeps as two launches, as bench.py times o, down and res
-    ("llama70b_lora", "down", 64, False, "dense", "z"), ("llama70b_lora", "o", 64, True, "dense", "z"),
-    ("skewed70b", "res", 32, False, "dense", "z"),
+    # a workspace with room for z: on a batch of this size the call runs its sweeps as two launches
+    ("llama8b_lora", "gate", 64, False, "dense", "z"), ("llama8b_lora", "o", 32, True, "dense", "z"),
+    ("llama8b_lora", "down", 48, False, "dense", "z"),
+    # ... and on the larger batches as one, whatever the workspace
+    ("llama70b_lora", "down", 64, False, "dense", "z"),
 ]
 
 
@@ -96,7 +98,9 @@ PACKED = [("llama8b_lora", ("q", "k", "v"), 16, False), ("llama8b_lora", ("gate"
           ("llama70b_lora", ("gate", "up"), 1, False),
           # the packed launches of the row-split kernel (rank 32 and 64), on dense rows as bench.py times them
           ("llama70b_lora", ("q", "k", "v"), 64, False, "dense"), ("llama70b_lora", ("gate", "up"), 64, False, "dense"),
-          ("llama70b_lora", ("q", "k", "v"), 32, True, "dense"), ("llama70b_lora", ("gate", "up"), 64, True)]
+          ("llama70b_lora", ("q", "k", "v"), 32, True, "dense"), ("llama70b_lora", ("gate", "up"), 64, True),
+          # a workspace with room for z: two launches on a batch of this size
+          ("llama8b_lora", ("q", "k", "v"), 64, False, "dense", "z"), ("llama8b_lora", ("gate", "up"), 32, True, "dense", "z")]
 
 
 @pytest.mark.parametrize("case", PACKED,
@@ -121,7 +125,7 @@ def test_fullsize_packed_lora(case):
     ys = [b[1] for b in bufs]
     tables = [lora_pools_to_device(pl) for pl in pools]
     ss, sa, sp = dev_tables(tab)
-    ws = preft.new_workspace(tab.T, tab.S)
+    ws = preft.new_workspace(tab.T, tab.S, z_rank=rank if len(case) > 5 else 0, z_proj=len(projs))
     mode = preft.PREFT_ALL_TOKENS if all_tokens else preft.PREFT_PREFILL_ONLY
     preft.preft_lora_apply_packed(ys, x, ss, sa, sp, [t[0] for t in tables], [t[1] for t in tables], rank,
                                   cfg["lora_scale"], mode, ws)
