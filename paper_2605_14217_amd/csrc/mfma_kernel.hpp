@@ -222,7 +222,15 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
         for (int mb = 0; mb < MB; ++mb) acc[b][mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
     const int k_units = p.d_in >> 7;                          // whole 128-column units
-    const int my_ku = k_units > wave ? (k_units - wave + WAVES - 1) / WAVES : 0;
+    // which units a wavefront takes: every WAVES-th one (the workgroup then touches 16 rows x 2 KB side by side
+    // at any moment), or, with a whole tile of more than 4096 columns held in registers, a contiguous range
+    // (in place, d = 8192, rank 8-16: +1.5 to +2.6 points of bandwidth on the 70B-sized and skewed batches; at
+    // d = 4096 the same costs 2-5 points and is not done)
+    constexpr bool CONTIG = HUNITS > 4 && WAVES == 8 && !PARTIAL;
+    const int k_per = (k_units + WAVES - 1) / WAVES;
+    const int my_ku = CONTIG ? max(0, min(k_per, k_units - wave * k_per))
+                             : (k_units > wave ? (k_units - wave + WAVES - 1) / WAVES : 0);
+    auto k_unit = [&](int u) { return CONTIG ? wave * k_per + u : wave + u * WAVES; };
     const int k_steps = (p.d_in + 31) >> 5;                   // 32-column steps, the last may be partial
     const int k_tail_step = k_units * 4 + wave;               // this wavefront's tail step, if < k_steps
 
@@ -231,7 +239,7 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
 
     auto load_x_unit = [&](u32x4_t (&raw)[MB][4], int u, auto again_tag) {
         constexpr bool AGAIN = decltype(again_tag)::value;    // these bytes are read a second time: keep them cacheable
-        const int64_t off = (int64_t)(wave + u * WAVES) * 256;
+        const int64_t off = (int64_t)k_unit(u) * 256;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -240,7 +248,7 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
     constexpr std::integral_constant<bool, false> read_once{};
     constexpr std::integral_constant<bool, X_READ_AGAIN> read_streamed{};
     auto load_a_unit = [&](u32x4_t (&araw)[NBT][4], int u) {
-        const int64_t off = (int64_t)(wave + u * WAVES) * 256;
+        const int64_t off = (int64_t)k_unit(u) * 256;
 #pragma unroll
         for (int b = 0; b < NBT; ++b)
 #pragma unroll
@@ -379,7 +387,7 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
     if constexpr (ODD > 0 && HUNITS > 0) {
 #pragma unroll
         for (int u = 0; u < W_AHEAD; ++u)
-            if (u < my_ku) load_w_block(w_ahead[u], as_global(p.Bt_pool[adapter]), wave + u * WAVES);
+            if (u < my_ku) load_w_block(w_ahead[u], as_global(p.Bt_pool[adapter]), k_unit(u));
     }
 
     // ---------------------------------------------------------------- reduce over wavefronts
@@ -471,6 +479,8 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
     const int c_units = d_out >> 7;
     const int ubase = c_units * cslice / csplit;
     const int n_cu = c_units * (cslice + 1) / csplit - ubase;
+    const int c_per = (n_cu + WAVES - 1) / WAVES;
+    auto c_unit = [&](int u) { return ubase + (CONTIG ? wave * c_per + u : wave + u * WAVES); };
     gptr_t yu[MB][4];             // unit order
     gptr_t ys[MB];                // step order
 #pragma unroll
@@ -514,9 +524,9 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
     };
     auto load_w_unit = [&](wbuf_t &wb, int u) {
         if constexpr (ODD > 0) {
-            load_w_block(wb, Bt, ubase + wave + u * WAVES);
+            load_w_block(wb, Bt, c_unit(u));
         } else {
-            const int cs0 = (ubase + wave + u * WAVES) * 4;
+            const int cs0 = c_unit(u) * 4;
 #pragma unroll
             for (int s = 0; s < 4; ++s)
 #pragma unroll
@@ -546,7 +556,7 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
         }
     };
     auto load_y_unit = [&](u32x4_t (&raw)[MB][4], int u) {
-        const int64_t off = (int64_t)(ubase + wave + u * WAVES) * 256;
+        const int64_t off = (int64_t)c_unit(u) * 256;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -569,14 +579,14 @@ __device__ __forceinline__ void mfma_tile_body(const ApplyArgs &p)
                 tr[(mb * 16 + rl) * MFMA_TRS + 4 * s + g] = expand_step(yv, wv, mb);
             }
         }
-        const int64_t off = (int64_t)(ubase + wave + u * WAVES) * 256;
+        const int64_t off = (int64_t)c_unit(u) * 256;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int i = 0; i < 4; ++i) st16_stream(yu[mb][i] + off, tr[(mb * 16 + 4 * i + q) * MFMA_TRS + c16]);
     };
 
-    const int my_cu = n_cu > wave ? (n_cu - wave + WAVES - 1) / WAVES : 0;
+    const int my_cu = CONTIG ? max(0, min(c_per, n_cu - wave * c_per)) : (n_cu > wave ? (n_cu - wave + WAVES - 1) / WAVES : 0);
     const int c_steps = cslice == csplit - 1 ? (d_out + 31) >> 5 : 0;
     const int c_tail_step = c_units * 4 + wave;
 

@@ -1139,7 +1139,8 @@ def test_segment_permutation_moves_the_rows_and_nothing_else(dtype, rank, d):
         assert not torch.equal(bits(ya), bits(y0))
 
 
-@pytest.mark.parametrize("rank,d,same_bits", [(16, 1024, True), (8, 4096, True), (2, 520, True), (32, 512, False), (64, 256, False)])
+@pytest.mark.parametrize("rank,d,same_bits", [(16, 1024, True), (8, 4096, True), (2, 520, True), (32, 512, False), (64, 256, False),
+                                               (16, 8192, False)])    # 8192 columns in registers: another order of the partial sums
 def test_direft_without_bias_is_the_lora_entry_on_a_copy_of_the_stream(rank, d, same_bits):
     """Eq. 3 with b = 0 is Eq. 2 with A = W1, B = W2, x = h and y0 = h: the in-place entry and the
     out-of-place entry must agree -- bit for bit where both take the same kernel family (one rounding
