@@ -783,6 +783,74 @@ def test_packed_projections_in_the_row_split_kernel(r, d_in, d_outs, fused_buffe
         print(f"  packed r={r} {d_in}->{d_outs} fused_buffer={fused_buffer} all_tokens={all_tokens} worst {worst:.2e}")
 
 
+def test_two_launch_lora_in_a_graph_and_with_a_foreign_schedule():
+    """The two-launch form keeps the boundary's promises: captured into a HIP graph and replayed with the
+    tables rewritten in place it matches the eager run every time (z is rewritten by every replay), and
+    with PREFT_SCHEDULE_READY on a workspace whose schedule belongs to another position set neither of
+    its launches touches y, and preft_schedule_counts reports it."""
+    from parity_util import bits, dev_tables, lora_pools_to_device
+    N, d_in, r = 5, 512, 64
+    d_outs = (512, 256)
+    rng = np.random.Generator(np.random.PCG64(79))
+    lens = np.array([300, 1, 129, 1, 1, 64, 450, 1, 5, 3, 700, 260])
+    tabs = []
+    for k in range(3):
+        ids = rng.integers(-1, N, size=len(lens))
+        pre = np.where(rng.random(len(lens)) < 0.6, lens, (lens * rng.random(len(lens))).astype(np.int64))
+        tabs.append(wl.from_lengths(lens, ids, pre))
+    T, S = tabs[0].T, tabs[0].S
+    assert T > 1024
+    pools = [lora_pools_to_device(wl.lora_pool(N, r, d_in, n, "bf16", device="cuda", seed=90 + i)) for i, n in enumerate(d_outs)]
+    x = wl.activations(T, d_in, "bf16", device="cuda", seed=91)
+    y0 = wl.activations(T, sum(d_outs), "bf16", device="cuda", seed=92)
+    y1 = y0.clone()
+    y2 = wl.activations(T, d_outs[0], "bf16", device="cuda", seed=93)
+    y2_0 = y2.clone()
+    ss, sa, sp = dev_tables(tabs[0])
+    ws = preft.new_workspace(T, S, z_rank=r, z_proj=2)
+    mode = preft.PREFT_PREFILL_ONLY
+    _set(resident=1)
+
+    def body():
+        y1.copy_(y0)
+        y2.copy_(y2_0)
+        preft.preft_schedule(ws, ss, sa, sp, T, N, mode)
+        ready = mode | preft.PREFT_SCHEDULE_READY
+        preft.preft_lora_apply_packed([y1[:, :d_outs[0]], y1[:, d_outs[0]:]], x, ss, sa, sp, [p[0] for p in pools],
+                                      [p[1] for p in pools], r, 2.0, ready, ws)
+        preft.preft_lora_apply(y2, x, ss, sa, sp, pools[0][0], pools[0][1], r, 0.5, ready, ws)
+
+    body()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        body()
+    for k in (1, 2, 0, 1):
+        sa.copy_(torch.from_numpy(tabs[k].seg_adapter.copy()))
+        sp.copy_(torch.from_numpy(tabs[k].seg_prefill_len.copy()))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (y1.clone(), y2.clone())
+        body()
+        torch.cuda.synchronize()
+        assert torch.equal(bits(got[0]), bits(y1)) and torch.equal(bits(got[1]), bits(y2)), f"replay differs (table {k})"
+        assert not torch.equal(bits(y1), bits(y0)) and not torch.equal(bits(y2), bits(y2_0))
+    # a schedule of the other position set in the workspace: both launches of a call must leave y alone
+    preft.preft_schedule(ws, ss, sa, sp, T, N, preft.PREFT_ALL_TOKENS)
+    y1.copy_(y0)
+    y2.copy_(y2_0)
+    ready = mode | preft.PREFT_SCHEDULE_READY
+    preft.preft_lora_apply_packed([y1[:, :d_outs[0]], y1[:, d_outs[0]:]], x, ss, sa, sp, [p[0] for p in pools],
+                                  [p[1] for p in pools], r, 2.0, ready, ws)
+    preft.preft_lora_apply(y2, x, ss, sa, sp, pools[0][0], pools[0][1], r, 0.5, ready, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(bits(y1), bits(y0)) and torch.equal(bits(y2), bits(y2_0))
+    with pytest.raises(preft.PreftError) as e:
+        preft.preft_schedule_counts(ws)
+    assert e.value.code == preft.PREFT_ESCHEDULE
+    _set()
+
+
 TWO_LAUNCH_CASES = [
     # (rank, d_in, d_outs): widths the two-launch form takes (d_in % 128 == 0, every d_out % 256 == 0)
     (64, 512, (512,)), (64, 1024, (1024, 256, 256)), (64, 256, (1792, 1792)), (32, 512, (512, 256, 256)),
