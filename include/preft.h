@@ -190,11 +190,12 @@ int preft_schedule(void *workspace, size_t workspace_bytes,
  * 14336-wide bf16 buffer with rows every 16384 elements: 64 -> 71 % of peak bandwidth): a caller
  * that owns the layout of its activations should pad wide rows to the next power of two.
  * rank in 1..PREFT_MAX_RANK.  scale is the paper's alpha (or alpha/r), already evaluated.
- * Every rank is computed as given (rank 1 is not padded to 8 in memory).  bf16 ranks 1-16 and the
- * multiples of 4 above run at the library's full speed (vector-ALU and matrix-core kernels; ranks
- * 5-7, 9-11 and 13-15 a few points below their neighbours); the other ranks (17-19, 21-23, ...)
- * take slower kernels: an adapter of such a rank is served faster when its factors are zero-padded
- * to the next multiple of 4.  fp32 takes the per-row kernels.
+ * Every rank is computed as given (rank 1 is not padded to 8 in memory).  Every bf16 rank runs on
+ * the library's fast kernels (vector-ALU and matrix-core kernels; ranks that are not multiples of 4
+ * a few points below their neighbours), with one exception: a rank above 16 that is not a multiple
+ * of 4 needs d_in and d_out to be multiples of 128 for that, and takes the slow per-row kernels
+ * otherwise (an adapter of such a rank and such widths is served faster when its factors are
+ * zero-padded to the next multiple of 4).  fp32 takes the per-row kernels.
  * Unless mode carries PREFT_SCHEDULE_READY the call first runs the scheduler into
  * `workspace` (>= preft_workspace_bytes(T, S) bytes).
  * T == 0 or S == 0 returns PREFT_OK without launching.

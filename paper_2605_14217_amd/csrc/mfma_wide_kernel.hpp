@@ -52,9 +52,16 @@ constexpr int wide_lds_bytes(int NB, int MB, int RW, int CW)
 // ZOUT (LoRA only): the shrink sweep alone.  z, already in the form the expand's MFMAs take it (scaled,
 // split into bf16 head and remainder, in lane order), goes to the z area of the workspace, 1 KB per
 // 16-row block and rank block, and mfma_expand_panel_kernel does the expand in a second launch.
-template <int NB, int MB, int RW, int CW, bool DIREFT, int SLICES = 1, bool ZOUT = false>
+//
+// ODD: ranks that are not multiples of 4 (17, 18, 19, 21, ...; nothing is padded in memory).  The shrink
+// needs nothing new (rank rows past r alias row r-1, their z is zeroed, here per element).  The expand's B
+// units go to LDS as they lie in memory, a column's r factors right behind the previous column's, and a
+// lane reads its four factors of a column as the three 32-bit words that hold them, shifts them into place
+// and masks the ranks past r (as the any-rank shape of mfma_tile_kernel does for rank 5..15).
+template <int NB, int MB, int RW, int CW, bool DIREFT, int SLICES = 1, bool ZOUT = false, bool ODD = false>
 __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
 {
+    static_assert(!ODD || (SLICES == 1 && !ZOUT && MB == 1 && CW == 1), "the any-rank form: one output, one launch, the basic shape");
     static_assert(SLICES == 1 || !DIREFT, "packed projections are a LoRA feature");
     static_assert(!ZOUT || (!DIREFT && MB == 1), "the two-launch form: LoRA, 16-row blocks per wavefront");
     constexpr int WAVES = RW * CW;
@@ -279,7 +286,8 @@ __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
             gcptr_t bias_p = bias_of(p, adapter);
             if (bias_p) {
 #pragma unroll
-                for (int v = 0; v < 4; ++v) bias[v] = Elem<bf16_tag>::load1(bias_p, rank0 + v);
+                for (int v = 0; v < 4; ++v)
+                    if (!ODD || rank0 + v < r) bias[v] = Elem<bf16_tag>::load1(bias_p, rank0 + v);
             }
         }
 #pragma unroll
@@ -287,7 +295,8 @@ __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
             float head_f[4], rem_f[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const float zv = rank_ok ? (acc[b][mb][v] + bias[v]) * p.scale : 0.f;
+                const bool v_ok = ODD ? rank0 + v < r : rank_ok;
+                const float zv = v_ok ? (acc[b][mb][v] + bias[v]) * p.scale : 0.f;
                 const uint32_t hb = pack_bf16(zv, 0.f) & 0xffffu;
                 head_f[v] = zv;
                 rem_f[v] = zv - __uint_as_float(hb << 16);
@@ -312,8 +321,9 @@ __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
     }
 
     // ---------------------------------------------------------------- expand (once per output)
-    // B units in LDS: column c of the step (0 .. 128 CW - 1) at byte c * CS, its r factors contiguous; CS = 2r + 8.
-    const int cs = 2 * r + 8;
+    // B units in LDS: column c of the step (0 .. 128 CW - 1) at byte c * CS, its r factors contiguous; CS = 2r + 8
+    // (any-rank form: CS = 2r, the units as they lie in memory)
+    const int cs = ODD ? 2 * r : 2 * r + 8;
     const int b_halves = 32 * r * CW;                         // 8-byte halves of a step's B units (128 CW columns x r factors)
     // where this thread's pieces land in LDS (the same for every step): two 8-byte halves each,
     // a half never straddles a column because r % 4 == 0
@@ -335,6 +345,19 @@ __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
             const int rank0 = 16 * b + 4 * g;
             w_off[e][b] = (cg * 128 + 2 * rl + e) * cs + (rank0 < r ? rank0 : 0) * 2;
         }
+    // any-rank form: element offset of this lane's factors (its four ranks may run past r: masked), the
+    // shift that brings an odd start into place (columns 2m + e: odd only for e = 1 and odd r), the masks
+    int odd_at[2][NB];
+    uint32_t odd_m01[NB], odd_m23[NB];
+    const uint32_t odd_shift[2] = {0u, (uint32_t)((r & 1) * 16)};
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const int n = r - (16 * b + 4 * g);
+        odd_m01[b] = n >= 2 ? 0xffffffffu : n == 1 ? 0xffffu : 0u;
+        odd_m23[b] = n >= 4 ? 0xffffffffu : n == 3 ? 0xffffu : 0u;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) odd_at[e][b] = (cg * 128 + 2 * rl + e) * r + 16 * b + 4 * g;
+    }
 
     auto expand_slice = [&](auto sl_tag) {
     constexpr int SL = decltype(sl_tag)::value;
@@ -383,7 +406,15 @@ __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
                 for (int mb = 0; mb < MB; ++mb) d[e][mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
-                    const u32x2_t w = *reinterpret_cast<const u32x2_t *>(fb + s * 32 * cs + w_off[e][b]);
+                    u32x2_t w;
+                    if constexpr (ODD) {
+                        const uint32_t *w3 = reinterpret_cast<const uint32_t *>(fb) + s * 16 * r + (odd_at[e][b] >> 1);
+                        const uint32_t d0 = w3[0], d1 = w3[1], d2 = w3[2];
+                        w = u32x2_t{__builtin_amdgcn_alignbit(d1, d0, odd_shift[e]) & odd_m01[b],
+                                    __builtin_amdgcn_alignbit(d2, d1, odd_shift[e]) & odd_m23[b]};
+                    } else {
+                        w = *reinterpret_cast<const u32x2_t *>(fb + s * 32 * cs + w_off[e][b]);
+                    }
                     const bf16x8_t wop = as_bf16x8(u32x4_t{w[0], w[1], w[0], w[1]});
 #pragma unroll
                     for (int mb = 0; mb < MB; ++mb)
@@ -466,10 +497,10 @@ constexpr int wide_min_waves(int RW, int CW, int SLICES)
     return (RW * CW == 4 && SLICES > 1) ? 2 : 1;
 }
 
-template <int NB, int MB, int RW, int CW, bool DIREFT, int SLICES = 1, bool ZOUT = false>
+template <int NB, int MB, int RW, int CW, bool DIREFT, int SLICES = 1, bool ZOUT = false, bool ODD = false>
 __global__ __launch_bounds__(RW * CW * 64, wide_min_waves(RW, CW, SLICES)) void mfma_wide_kernel(ApplyArgs p)
 {
-    mfma_wide_body<NB, MB, RW, CW, DIREFT, SLICES, ZOUT>(p);
+    mfma_wide_body<NB, MB, RW, CW, DIREFT, SLICES, ZOUT, ODD>(p);
 }
 
 // The expand sweep as a launch of its own (LoRA, after a ZOUT launch of the kernel above), in 2-D tiles:
@@ -622,11 +653,11 @@ __global__ __launch_bounds__(RW * 64, 3) void mfma_expand_panel_kernel(ApplyArgs
 }
 
 // the same for one of several residual streams (in-place calls): blockIdx.y is the layer
-template <int NB, int MB, int RW, int CW>
+template <int NB, int MB, int RW, int CW, bool ODD = false>
 __global__ __launch_bounds__(RW * CW * 64) void mfma_wide_layers_kernel(ApplyArgs p)
 {
     select_layer(p);
-    mfma_wide_body<NB, MB, RW, CW, true>(p);
+    mfma_wide_body<NB, MB, RW, CW, true, 1, false, ODD>(p);
 }
 
 }  // namespace preft

@@ -224,11 +224,11 @@ bool launch_mfma_resident(const ApplyArgs &a, int64_t S, hipStream_t stream)
 
 // row-split kernel with the factors shared through LDS (rank >= 32, widths multiples of 128):
 // `rw` row blocks of 16 `mb` rows x `cw` column groups of wavefronts per workgroup
-template <int NB, int MB, int RW, int CW, bool DIREFT>
+template <int NB, int MB, int RW, int CW, bool DIREFT, bool ODD = false>
 void launch_wide_shape(const ApplyArgs &a, int64_t S, hipStream_t stream)
 {
-    void (*kernel)(ApplyArgs) = mfma_wide_kernel<NB, MB, RW, CW, DIREFT>;
-    if constexpr (DIREFT) { if (a.h_layers) kernel = mfma_wide_layers_kernel<NB, MB, RW, CW>; }   // set on in-place calls only
+    void (*kernel)(ApplyArgs) = mfma_wide_kernel<NB, MB, RW, CW, DIREFT, 1, false, ODD>;
+    if constexpr (DIREFT) { if (a.h_layers) kernel = mfma_wide_layers_kernel<NB, MB, RW, CW, ODD>; }   // set on in-place calls only
     hipLaunchKernelGGL(kernel, dim3(chunk_grid(a, S, 16 * MB * RW), a.n_layers), dim3(RW * CW * 64), 0, stream, a);
 }
 
@@ -437,10 +437,27 @@ void launch_mfma_odd(const ApplyArgs &a, int64_t S, hipStream_t stream)
     else             launch_mfma_odd_pieces<DIREFT, 4>(a, S, stream);
 }
 
+template <typename E, bool DIREFT>
+void launch_rows(const ApplyArgs &a, int64_t S, bool chunks_too, hipStream_t stream);
+
+// bf16 ranks above 16 that are not multiples of 4, widths multiples of 128: the row-split kernel's any-rank
+// form takes the chunks (its basic shape: 4 wavefronts x 16 rows, above rank 64 8 x 16), the per-row kernel
+// the gathered tiles (all-token mode: decode rows)
+template <bool DIREFT>
+void launch_mfma_odd_wide(const ApplyArgs &a, int64_t S, hipStream_t stream)
+{
+    const int nb = (a.rank + 15) / 16;
+    if (nb <= 2)      launch_wide_shape<2, 1, 4, 1, DIREFT, true>(a, S, stream);
+    else if (nb <= 4) launch_wide_shape<4, 1, 4, 1, DIREFT, true>(a, S, stream);
+    else              launch_wide_shape<8, 1, 8, 1, DIREFT, true>(a, S, stream);
+    launch_rows<bf16_tag, DIREFT>(a, S, false, stream);
+}
+
 template <bool DIREFT>
 void launch_mfma_rank(const ApplyArgs &a, int64_t S, const Knobs &k, hipStream_t stream)
 {
     const int nb = (a.rank + 15) / 16;
+    if ((a.rank % 4) && a.rank > 16) { launch_mfma_odd_wide<DIREFT>(a, S, stream); return; }   // widths: choose_path
     if (a.rank % 4) { launch_mfma_odd<DIREFT>(a, S, stream); return; }      // rank <= 16 (choose_path)
     if (nb <= 1)      launch_mfma_nb<1, DIREFT>(a, S, k, stream);
     else if (nb <= 2) launch_mfma_nb<2, DIREFT>(a, S, k, stream);
@@ -530,12 +547,13 @@ void launch_rows(const ApplyArgs &a, int64_t S, bool chunks_too, hipStream_t str
 
 enum class Path { Rows, Valu, Mfma };
 
-Path choose_path(int dtype, int rank, const Knobs &k)
+Path choose_path(int dtype, int rank, bool widths_128, const Knobs &k)
 {
     if (dtype != PREFT_BF16 || k.variant == 1) return Path::Rows;
-    // matrix-core kernels: multiples of 4, and every rank from 5 to 16 (the any-rank shape of the
-    // column-split kernel); ranks 1..3 are a vector-ALU matter
-    const bool valu_ok = rank <= 8, mfma_ok = (rank % 4) == 0 || (rank > 4 && rank < 16);
+    // matrix-core kernels: multiples of 4, every rank from 5 to 16 (the any-rank shape of the column-split
+    // kernel) and, widths being multiples of 128, every rank above (the any-rank form of the row-split
+    // kernel); ranks 1..3 are a vector-ALU matter
+    const bool valu_ok = rank <= 8, mfma_ok = (rank % 4) == 0 || (rank > 4 && rank < 16) || (rank > 16 && widths_128);
     if (k.variant == 2 && valu_ok) return Path::Valu;
     if ((k.variant == 3 || k.variant == 4) && mfma_ok) return Path::Mfma;
     if (rank <= 3) return Path::Valu;
@@ -546,7 +564,7 @@ Path choose_path(int dtype, int rank, const Knobs &k)
 template <bool DIREFT>
 int launch_apply(const ApplyArgs &a, int64_t S, int dtype, const Knobs &k, hipStream_t stream)
 {
-    switch (choose_path(dtype, a.rank, k)) {
+    switch (choose_path(dtype, a.rank, wide_widths_ok(a, 1), k)) {
     case Path::Mfma: {                     // the tile kernels take chunks and gathered tiles alike
         ApplyArgs b = a;
         if (!DIREFT) b.col_split = choose_col_split(a.T, k);

@@ -175,6 +175,40 @@ def test_ranks_that_are_not_multiples_of_four_on_the_matrix_core_kernel(rank):
             print(f"  direft r={rank} d={d} all_tokens={all_tokens} bias={bias} worst {worst:.2e}")
 
 
+@pytest.mark.parametrize("rank", [17, 18, 19, 21, 23, 30, 37, 50, 63, 65, 100, 127])
+def test_ranks_above_16_that_are_not_multiples_of_four(rank):
+    """bf16 ranks above 16 that are not multiples of 4 take the row-split MFMA kernel's any-rank form when
+    every width is a multiple of 128 (chunks; the gathered tiles of the all-token mode go to the per-row
+    kernel), and the per-row kernels otherwise: LoRA and DiReFT (with and without bias, one call for
+    several layers), both modes, small and large batches."""
+    from parity_util import run_direft_case, run_direft_layers_case, run_lora_case
+    N = 4
+    for (d_in, d_out), (n_prompts, max_len) in (((256, 384), (6, 300)), ((128, 128), (2, 50)), ((384, 264), (4, 200))):
+        tab = _mixed_table(rank * 11 + d_in, N, n_prompts=n_prompts, max_len=max_len)
+        pool = wl.lora_pool(N, rank, d_in, d_out, "bf16", device="cuda", seed=rank)
+        x = wl.activations(tab.T, d_in, "bf16", device="cuda", seed=21)
+        y0 = wl.activations(tab.T, d_out, "bf16", device="cuda", seed=22)
+        for all_tokens in (False, True):
+            _set()
+            worst, counts = run_lora_case(tab, pool, x, y0, "bf16", 2.0, all_tokens, pad_cols=8)
+            print(f"  lora r={rank} {d_in}->{d_out} T={tab.T} all_tokens={all_tokens} worst {worst:.2e}")
+    for d in (512, 136):
+        tab = _mixed_table(rank * 19 + d, N, max_len=260)
+        pool = wl.direft_pool(N, rank, d, "bf16", device="cuda", seed=rank + 3)
+        h = wl.activations(tab.T, d, "bf16", device="cuda", seed=23)
+        for all_tokens, scale, bias in ((False, 1.0, True), (True, 1.0 / np.sqrt(rank), False)):
+            _set()
+            worst, counts = run_direft_case(tab, pool, h, "bf16", scale, all_tokens, pad_cols=8, bias=bias)
+            print(f"  direft r={rank} d={d} all_tokens={all_tokens} bias={bias} worst {worst:.2e}")
+    if rank in (19, 37, 65):
+        tab = _mixed_table(rank * 23, N, max_len=150)
+        pools = [wl.direft_pool(N, rank, 256, "bf16", device="cuda", seed=300 + l) for l in range(3)]
+        h0s = [wl.activations(tab.T, 256, "bf16", device="cuda", seed=310 + l) for l in range(3)]
+        _set()
+        worst = run_direft_layers_case(tab, pools, h0s, "bf16", 0.5, False, [True, False, True], pad_cols=8)
+        print(f"  direft layers r={rank} worst {worst:.2e}")
+
+
 @pytest.mark.parametrize("resident", [3])
 @pytest.mark.parametrize("rank,d", [(32, 8192), (32, 4096), (32, 1160), (20, 8192), (24, 2048), (32, 16384), (28, 520)])
 def test_partially_resident_in_place_tiles(resident, rank, d):
@@ -1095,6 +1129,8 @@ EXACT_CASES = [
     ("bf16", VARIANT_AUTO, 32, 256, 256), ("bf16", VARIANT_AUTO, 64, 128, 384), ("bf16", VARIANT_ROW, 5, 64, 40),
     ("bf16", VARIANT_AUTO, 5, 256, 384), ("bf16", VARIANT_AUTO, 7, 200, 136), ("bf16", VARIANT_AUTO, 11, 128, 264),
     ("bf16", VARIANT_AUTO, 14, 264, 128),
+    ("bf16", VARIANT_AUTO, 17, 128, 256), ("bf16", VARIANT_AUTO, 30, 256, 128), ("bf16", VARIANT_AUTO, 63, 128, 128),
+    ("bf16", VARIANT_AUTO, 101, 128, 256),
     ("f32", VARIANT_AUTO, 4, 132, 68), ("f32", VARIANT_AUTO, 9, 64, 64),
 ]
 
