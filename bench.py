@@ -162,10 +162,10 @@ def run(args):
     direft_scale = 1.0
 
     # launches of a step: projections that read the same x (q,k,v; gate,up) go out as one packed call
-    # (one launch that reads x once for bf16 ranks 1-16 and, widths being multiples of 128, the multiples
-    # of 4 from 20 to 64; other ranks stay one call that issues one launch per projection)
+    # (one launch that reads x once for bf16 ranks 1-16 and, widths being multiples of 128, for ranks 17-64;
+    # above, the call issues one launch per projection)
     packs = {"q": "qkv", "k": "qkv", "v": "qkv", "gate": "gate_up", "up": "gate_up"}
-    packed = not args.no_packed and (r <= 16 or (r % 4 == 0 and r <= 64))
+    packed = not args.no_packed and r <= 64
     groups = []
     for p in projs:
         key = packs.get(p["name"]) if packed else None

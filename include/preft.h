@@ -219,7 +219,7 @@ int preft_lora_apply(void *y, int64_t ldy, const void *x, int64_t ldx,
  * disjoint column ranges of one buffer (a fused qkv or gate-up output: same row stride, every
  * range inside one row); any other overlap, and any overlap with x, is PREFT_EINVAL.
  * The result is that of n_proj preft_lora_apply calls.  For bf16 and rank 1..16,
- * and for rank 20..64 (multiples of 4) when every width is a multiple of 128 and the batch has more
+ * and for rank 17..64 when every width is a multiple of 128 and the batch has more
  * than 1024 rows, they run as one launch that reads x once; otherwise the call issues one launch per
  * projection.
  */

@@ -61,7 +61,7 @@ constexpr int wide_lds_bytes(int NB, int MB, int RW, int CW)
 template <int NB, int MB, int RW, int CW, bool DIREFT, int SLICES = 1, bool ZOUT = false, bool ODD = false>
 __device__ __forceinline__ void mfma_wide_body(const ApplyArgs &p)
 {
-    static_assert(!ODD || (SLICES == 1 && !ZOUT && MB == 1 && CW == 1), "the any-rank form: one output, one launch, the basic shape");
+    static_assert(!ODD || (!ZOUT && MB == 1 && CW == 1), "the any-rank form: one launch, the basic shape");
     static_assert(SLICES == 1 || !DIREFT, "packed projections are a LoRA feature");
     static_assert(!ZOUT || (!DIREFT && MB == 1), "the two-launch form: LoRA, 16-row blocks per wavefront");
     constexpr int WAVES = RW * CW;

@@ -374,12 +374,30 @@ void launch_mfma_packed(const ApplyArgs &a, int64_t S, const Knobs &k, hipStream
                            dim3(256), 0, stream, a);
 }
 
+template <typename E, bool DIREFT>
+void launch_rows(const ApplyArgs &a, int64_t S, bool chunks_too, hipStream_t stream);
+
 // packed projections at rank 32..64 (widths multiples of 128): the row-split kernel with one sweep
 // over x for all outputs.  It takes the chunks; the gathered tiles (all-token mode: decode rows)
 // go to one launch of the column-split kernel per output.
 template <int NB>
 void launch_mfma_wide_packed(const ApplyArgs &a, int n_proj, int64_t S, const Knobs &k, hipStream_t stream)
 {
+    if (a.rank % 4) {
+        // the any-rank form: the basic shape for the chunks, the per-row kernel for the gathered tiles
+        void (*odd)(ApplyArgs) = n_proj == 2 ? mfma_wide_kernel<NB, 1, 4, 1, false, 2, false, true>
+                                             : mfma_wide_kernel<NB, 1, 4, 1, false, 3, false, true>;
+        hipLaunchKernelGGL(odd, dim3(chunk_grid(a, S, 64)), dim3(256), 0, stream, a);
+        for (int i = 0; i < n_proj; ++i) {
+            ApplyArgs g = a;
+            if (i > 0) {
+                g.y = a.more[i - 1].y; g.ldy = a.more[i - 1].ldy; g.d_out = a.more[i - 1].d_out;
+                g.A_pool = a.more[i - 1].A_pool; g.Bt_pool = a.more[i - 1].Bt_pool;
+            }
+            launch_rows<bf16_tag, false>(g, S, false, stream);
+        }
+        return;
+    }
     const bool split = n_proj == 2 ? launch_mfma_split<NB, 2>(a, S, k, stream) : launch_mfma_split<NB, 3>(a, S, k, stream);
     // two column groups at rank 32 where every width allows it (see launch_mfma_nb)
     bool cw2 = NB <= 2 && (a.d_in % 256) == 0 && (a.d_out % 256) == 0;
@@ -436,9 +454,6 @@ void launch_mfma_odd(const ApplyArgs &a, int64_t S, hipStream_t stream)
     if (a.rank <= 8) launch_mfma_odd_pieces<DIREFT, 2>(a, S, stream);
     else             launch_mfma_odd_pieces<DIREFT, 4>(a, S, stream);
 }
-
-template <typename E, bool DIREFT>
-void launch_rows(const ApplyArgs &a, int64_t S, bool chunks_too, hipStream_t stream);
 
 // bf16 ranks above 16 that are not multiples of 4, widths multiples of 128: the row-split kernel's any-rank
 // form takes the chunks (its basic shape: 4 wavefronts x 16 rows, above rank 64 8 x 16), the per-row kernel
@@ -740,7 +755,7 @@ int preft_lora_apply_packed(int32_t n_proj, void *const *y, const int64_t *ldy, 
                             (k.variant == 0 || k.variant == 3 || k.variant == 5);
     const bool fused_valu = n_proj > 1 && dtype == PREFT_BF16 && rank <= 3 && (k.variant == 0 || k.variant == 2) &&
                             (k.waves == 0 || k.waves == 4);
-    bool fused_wide = n_proj > 1 && dtype == PREFT_BF16 && rank > 16 && rank <= 64 && (rank % 4) == 0 &&
+    bool fused_wide = n_proj > 1 && dtype == PREFT_BF16 && rank > 16 && rank <= 64 &&
                       (k.variant == 0 || k.variant == 4 || k.variant == 5) && k.waves == 0 && k.rowblocks == 0 && (d_in % 128) == 0 &&
                       choose_col_split(T, k) == 1;
     for (int32_t i = 0; i < n_proj && fused_wide; ++i) fused_wide = (d_out[i] % 128) == 0;

@@ -806,6 +806,8 @@ def test_packed_projections_match_the_oracle(dtype, r, d_in, d_outs, fused_buffe
 @pytest.mark.parametrize("r,d_in,d_outs,fused_buffer", [
     (32, 512, (512, 128, 128), True), (64, 1024, (1024, 128, 128), False), (64, 256, (1536, 1536), True),
     (48, 384, (128, 256), False), (20, 128, (256, 128, 384), True), (64, 8192, (1024, 1024), False),
+    # ranks that are not multiples of 4: the any-rank form of the same kernel
+    (31, 256, (256, 128), True), (50, 128, (384, 128, 256), False), (17, 512, (128, 128), True), (63, 384, (256, 256, 128), True),
 ])
 def test_packed_projections_in_the_row_split_kernel(r, d_in, d_outs, fused_buffer):
     """Rank 20..64 with widths that are multiples of 128 on a batch of more than 1024 rows: one launch
@@ -956,11 +958,13 @@ def test_two_launch_lora_equals_the_single_launch_and_the_oracle(rank, d_in, d_o
 
 
 @pytest.mark.parametrize("rank,d_in,d_outs", [(32, 256, (256, 128, 128)), (64, 128, (384, 128)), (64, 384, (128, 128, 256)),
-                                              (7, 264, (256, 136, 128)), (13, 128, (392, 128))])
+                                              (7, 264, (256, 136, 128)), (13, 128, (392, 128)), (29, 128, (256, 128)),
+                                              (61, 256, (128, 128, 128))])
 def test_packed_row_split_kernel_gives_the_exactly_rounded_result(rank, d_in, d_outs):
     """Small-integer data (every product and sum exact on both sides): the packed launch must equal
     the oracle's result rounded once to bf16, bit for bit, on every output.  (Rank 32 and 64: the
-    row-split kernel; rank 7 and 13: the column-split kernel's any-rank shape.)"""
+    row-split kernel; rank 7 and 13: the column-split kernel's any-rank shape; rank 29 and 61: the
+    row-split kernel's any-rank form.)"""
     from oracle import preft_oracle as ora
     from parity_util import dev_tables
     N = 4
