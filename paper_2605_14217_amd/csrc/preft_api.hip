@@ -8,6 +8,10 @@
 #include "row_kernel.hpp"
 #include "schedule.hpp"
 #include "valu_kernel.hpp"
+// most kernel instantiations are compiled in instances/group_*.hip (see gen_instances.py), in parallel
+#ifndef PREFT_NO_EXTERN_KERNELS
+#include "instances/extern_kernels.inc"
+#endif
 
 #include <mutex>
 
