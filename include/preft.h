@@ -81,10 +81,11 @@ enum {
  *   PREFT_TEST_VARIANT(v)    0 = automatic
  *                            1 = per-row kernel everywhere
  *                            2 = vector-ALU tile kernel where it applies (bf16, rank <= 8)
- *                            3 = MFMA tile kernel, column-split shape (bf16, rank % 4 == 0)
+ *                            3 = MFMA tile kernel, column-split shape (bf16, rank a multiple
+ *                                of 4 or between 5 and 15)
  *                            4 = MFMA tile kernel, row-split shape with the factors shared
- *                                through LDS where it applies (widths multiples of 128), and
- *                                no register-resident DiReFT
+ *                                through LDS where it applies (rank a multiple of 4 or above
+ *                                16, widths multiples of 128), and no register-resident DiReFT
  *                            5 = automatic, but both sweeps of a LoRA call in one launch even
  *                                if the workspace has room for z (preft_workspace_bytes_z)
  *   PREFT_TEST_WAVES(w)      wavefronts per tile workgroup: 0 = automatic, else 1, 2, 4 or 8
@@ -96,10 +97,10 @@ enum {
  *                            batches of up to 1024 rows, else 1), or 1..15.  Together with
  *                            variant 4 it names the column groups of the row-split kernel
  *                            instead: 0 = automatic, 1 or 2
- *   PREFT_TEST_RESIDENT(n)   LoRA: 1 = two launches (see preft_workspace_bytes_z) wherever that form
- *                            exists, whatever the batch size.  In-place MFMA kernel at rank
- *                            20..32: 0 = automatic (32-row tiles
- *                            streamed in both sweeps), 3 = every wavefront keeps 8 of its
+ *   PREFT_TEST_RESIDENT(n)   0 = automatic.  LoRA: 1 = two launches (preft_workspace_bytes_z)
+ *                            wherever that form exists, whatever the batch size.  In-place
+ *                            MFMA kernel at rank 20..32 (automatic: 32-row tiles streamed in
+ *                            both sweeps): 3 = every wavefront keeps 8 of its
  *                            128-column units in registers between the sweeps (half of a
  *                            32-row tile of 8192 columns) and streams the rest twice
  */
